@@ -1,0 +1,329 @@
+/*
+ * CPU oracle for the Contextual Token Sparsity hot path (LeMo, arXiv 2501.09767).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, fp64 statement of what the
+ * four operations compute, written from the paper's definitions so that a reader can check it
+ * against the paper by eye.  It shares no source, header, table or helper with the HIP library and
+ * must only be called from tests, the smoke check and the bench's cpu_baseline leg.
+ *
+ *   oracle_score            Sec. 4.2 Eq. 1 (token informativeness = column sum of attention scores,
+ *                           self excluded) with the head mean of Eq. 2; attention scores are the
+ *                           softmax probabilities (Sec. 4.2, "attention scores undergo a softmax").
+ *   oracle_score_bruteforce same quantity through a materialised S x S matrix (tiny S only).
+ *   oracle_select_topk      per-segment top-k at a keep ratio (the selection unit is the paper's
+ *                           token block, Sec. 4.2 "Layer-specific Threshold"; here the k best of
+ *                           each block are kept instead of thresholding).
+ *   oracle_gather_gemm      Sec. 4.4 "directly loads the selected tokens from original inputs":
+ *                           Y[m,:] = X[idx[m],:] . W^T (+ bias).
+ *   oracle_scatter_add      Sec. 4.4 "in-place addition ... completing token padding and residual
+ *                           addition in a single step": dX[idx[m],:] += G[m,:].
+ *
+ * Every floating-point reduction is carried in double.  Nothing here is blocked, fused or
+ * reordered beyond what the definitions state.  Parallelism (OpenMP) is over independent heads or
+ * independent output rows only.
+ *
+ * Pins (tests/test_oracle_pins.py): softmax rows sum to one => per-head column sums total S;
+ * brute-force S x S agreement; closed forms for constant logits (harmonic numbers under a causal
+ * mask); shift/permutation invariances; numpy textbook softmax; argsort top-k; numpy float64
+ * matmul; adjoint identity between gather and scatter.  The paper prints no worked numeric example
+ * for this path, so parity against paper-printed values is unpinned; the pins above are what fixes
+ * the oracle.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_CAUSAL = 1u, ORACLE_EXCLUDE_SELF = 2u };
+enum { ORACLE_SCATTER_ACCUMULATE = 0, ORACLE_SCATTER_ZERO_PAD = 1 };
+enum { ORACLE_OK = 0, ORACLE_ERR_ARG = -1, ORACLE_ERR_NOMEM = -2 };
+
+/* ---------------------------------------------------------------- element access */
+
+static float bf16_bits_to_float(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16; /* bf16 is the upper half of an IEEE binary32 */
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+static double load_elem(const void* base, int64_t index, int dtype) {
+    if (dtype == ORACLE_BF16) return (double)bf16_bits_to_float(((const uint16_t*)base)[index]);
+    return (double)((const float*)base)[index];
+}
+
+/* Round a double to the nearest bfloat16 (ties to even) in ONE rounding step and return its bit
+ * pattern.  bf16: 1 sign, 8 exponent, 7 stored fraction bits; smallest normal 2^-126, so the
+ * spacing of representable values never drops below 2^-133. */
+static uint16_t double_to_bf16_bits(double x) {
+    if (isnan(x)) return 0x7fc0;
+    uint16_t sign = signbit(x) ? 0x8000 : 0;
+    double a = fabs(x);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return sign | 0x7f80;
+    int e;
+    (void)frexp(a, &e);              /* a = m * 2^e, m in [0.5, 1) */
+    int q = e - 8;                   /* spacing 2^q keeps 8 significant bits */
+    if (q < -133) q = -133;          /* subnormal range: fixed spacing */
+    double r = nearbyint(ldexp(a, -q)); /* default rounding mode = ties to even; exact scaling */
+    double v = ldexp(r, q);          /* representable in bf16 unless it overflowed */
+    if (v > 3.3895313892515355e38) return sign | 0x7f80; /* beyond (2 - 2^-7) * 2^127: infinity */
+    float f = (float)v;              /* exact: v has <= 8 significant bits */
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    return sign | (uint16_t)(u >> 16);
+}
+
+static uint16_t float_to_bf16_bits(float x) { return double_to_bf16_bits((double)x); }
+
+/* ---------------------------------------------------------------- host helpers */
+
+/* k = ceil(ratio * L) kept tokens per full segment, clamped to [1, L].  A 1e-9 slack keeps exact
+ * products such as 0.5 * 128 from rounding up. */
+int32_t oracle_keep_k(int32_t L, double ratio) {
+    if (L <= 0) return 0;
+    double v = ceil(ratio * (double)L - 1e-9);
+    if (v < 1.0) v = 1.0;
+    if (v > (double)L) v = (double)L;
+    return (int32_t)v;
+}
+
+/* tokens kept in a segment of length len when full segments of length L keep k */
+static int32_t seg_keep(int64_t len, int32_t L, int32_t k) {
+    if (len == (int64_t)L) return k;
+    int64_t v = ((int64_t)k * len + (int64_t)L - 1) / (int64_t)L; /* ceil(k * len / L) */
+    if (v < 1) v = 1;
+    if (v > len) v = len;
+    return (int32_t)v;
+}
+
+int64_t oracle_kept_count(int64_t S, int32_t L, int32_t k) {
+    if (S <= 0 || L <= 0 || k <= 0 || k > L) return -1;
+    int64_t full = S / L, tail = S % L;
+    int64_t M = full * k;
+    if (tail) M += seg_keep(tail, L, k);
+    return M;
+}
+
+/* ---------------------------------------------------------------- scoring */
+
+/* One head, row by row.  For query i: logits s_ij = scale * <Q_i, K_j> over the allowed keys
+ * (j <= i under a causal mask, all j otherwise); p_ij = softmax over j; p_ij is added to column j
+ * and p_ii is remembered.  One O(S) row buffer; the S x S matrix never exists. */
+static void score_one_head(const void* Q, const void* K, int64_t S, int d, int dtype,
+                           int64_t q_ts, int64_t q_off, int64_t k_ts, int64_t k_off,
+                           double scale, int causal, double* row, double* col, double* dg) {
+    for (int64_t j = 0; j < S; ++j) { col[j] = 0.0; dg[j] = 0.0; }
+    for (int64_t i = 0; i < S; ++i) {
+        int64_t nk = causal ? i + 1 : S;
+        double mx = -INFINITY;
+        for (int64_t j = 0; j < nk; ++j) {
+            double dot = 0.0;
+            for (int c = 0; c < d; ++c)
+                dot += load_elem(Q, i * q_ts + q_off + c, dtype) * load_elem(K, j * k_ts + k_off + c, dtype);
+            row[j] = scale * dot;
+            if (row[j] > mx) mx = row[j];
+        }
+        double den = 0.0;
+        for (int64_t j = 0; j < nk; ++j) { row[j] = exp(row[j] - mx); den += row[j]; }
+        for (int64_t j = 0; j < nk; ++j) {
+            double p = row[j] / den;
+            col[j] += p;
+            if (j == i) dg[j] = p;
+        }
+    }
+}
+
+/* Q [S,H,d], K [S,H_kv,d] with element strides (d contiguous); query head h reads KV head
+ * floor(h * H_kv / H).  scores[S] (float) is the head mean of (column sum - [EXCLUDE_SELF] p_jj),
+ * rounded once from double.  colsum / diag, when not NULL, receive the per-head [H,S] doubles;
+ * colsum always INCLUDES the diagonal term. */
+int oracle_score(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, int dtype,
+                 int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                 double scale, uint32_t flags, float* scores, double* colsum, double* diag) {
+    if (!Q || !K || !scores || S <= 0 || H <= 0 || H_kv <= 0 || d <= 0 || H % H_kv) return ORACLE_ERR_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_ERR_ARG;
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)d);
+    const int causal = (flags & ORACLE_CAUSAL) != 0;
+    const int excl = (flags & ORACLE_EXCLUDE_SELF) != 0;
+    double* col = (double*)malloc(sizeof(double) * (size_t)H * (size_t)S);
+    double* dg = (double*)malloc(sizeof(double) * (size_t)H * (size_t)S);
+    if (!col || !dg) { free(col); free(dg); return ORACLE_ERR_NOMEM; }
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < H; ++h) {
+        double* row = (double*)malloc(sizeof(double) * (size_t)S);
+        if (!row) { failed = 1; continue; }
+        int g = (int)(((int64_t)h * H_kv) / H);
+        score_one_head(Q, K, S, d, dtype, q_tok_stride, (int64_t)h * q_head_stride, k_tok_stride,
+                       (int64_t)g * k_head_stride, scale, causal, row, col + (size_t)h * S, dg + (size_t)h * S);
+        free(row);
+    }
+    if (failed) { free(col); free(dg); return ORACLE_ERR_NOMEM; }
+    for (int64_t j = 0; j < S; ++j) {
+        double acc = 0.0;
+        for (int h = 0; h < H; ++h) {
+            double v = col[(size_t)h * S + j];
+            if (excl) v -= dg[(size_t)h * S + j];
+            acc += v;
+        }
+        scores[j] = (float)(acc / (double)H);
+    }
+    if (colsum) memcpy(colsum, col, sizeof(double) * (size_t)H * (size_t)S);
+    if (diag) memcpy(diag, dg, sizeof(double) * (size_t)H * (size_t)S);
+    free(col);
+    free(dg);
+    return ORACLE_OK;
+}
+
+/* The same scores through the full S x S probability matrix of each head: all logits first, then a
+ * softmax over every row, then a sum down every column with the i == j entry left out when
+ * EXCLUDE_SELF is set.  Memory is quadratic, so S is limited. */
+int oracle_score_bruteforce(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d,
+                            int dtype, int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride,
+                            int64_t k_head_stride, double scale, uint32_t flags, float* scores) {
+    if (!Q || !K || !scores || S <= 0 || S > 2048 || H <= 0 || H_kv <= 0 || d <= 0 || H % H_kv) return ORACLE_ERR_ARG;
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)d);
+    const int causal = (flags & ORACLE_CAUSAL) != 0;
+    const int excl = (flags & ORACLE_EXCLUDE_SELF) != 0;
+    double* P = (double*)malloc(sizeof(double) * (size_t)S * (size_t)S);
+    double* total = (double*)calloc((size_t)S, sizeof(double));
+    if (!P || !total) { free(P); free(total); return ORACLE_ERR_NOMEM; }
+    for (int h = 0; h < H; ++h) {
+        int g = (int)(((int64_t)h * H_kv) / H);
+        for (int64_t i = 0; i < S; ++i)
+            for (int64_t j = 0; j < S; ++j) {
+                double dot = 0.0;
+                for (int c = 0; c < d; ++c)
+                    dot += load_elem(Q, i * q_tok_stride + h * q_head_stride + c, dtype) *
+                           load_elem(K, j * k_tok_stride + g * k_head_stride + c, dtype);
+                P[i * S + j] = (causal && j > i) ? -INFINITY : scale * dot;
+            }
+        for (int64_t i = 0; i < S; ++i) {
+            double mx = -INFINITY, den = 0.0;
+            for (int64_t j = 0; j < S; ++j) if (P[i * S + j] > mx) mx = P[i * S + j];
+            for (int64_t j = 0; j < S; ++j) { P[i * S + j] = exp(P[i * S + j] - mx); den += P[i * S + j]; }
+            for (int64_t j = 0; j < S; ++j) P[i * S + j] /= den;
+        }
+        for (int64_t j = 0; j < S; ++j) {
+            double c = 0.0;
+            for (int64_t i = 0; i < S; ++i)
+                if (!(excl && i == j)) c += P[i * S + j];
+            total[j] += c;
+        }
+    }
+    for (int64_t j = 0; j < S; ++j) scores[j] = (float)(total[j] / (double)H);
+    free(P);
+    free(total);
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------- selection */
+
+typedef struct { float score; int32_t index; } scored_t;
+
+/* higher score first; equal scores (including -0.0 vs +0.0) keep the lower index first */
+static int by_score_desc_then_index(const void* a, const void* b) {
+    const scored_t* x = (const scored_t*)a;
+    const scored_t* y = (const scored_t*)b;
+    if (x->score > y->score) return -1;
+    if (x->score < y->score) return 1;
+    return (x->index > y->index) - (x->index < y->index);
+}
+
+static int by_int32(const void* a, const void* b) {
+    int32_t x = *(const int32_t*)a, y = *(const int32_t*)b;
+    return (x > y) - (x < y);
+}
+
+/* For every segment [n L, min((n+1) L, S)): order its tokens by score (descending, ties to the
+ * lower index), keep the first k (a ragged last segment keeps ceil(k * len / L), at least one),
+ * and append the kept token indices in ascending order. */
+int oracle_select_topk(const float* scores, int64_t S, int32_t L, int32_t k, int32_t* kept_idx) {
+    if (!scores || !kept_idx || S <= 0 || L <= 0 || k <= 0 || k > L) return ORACLE_ERR_ARG;
+    scored_t* seg = (scored_t*)malloc(sizeof(scored_t) * (size_t)L);
+    if (!seg) return ORACLE_ERR_NOMEM;
+    int64_t out = 0;
+    for (int64_t start = 0; start < S; start += L) {
+        int64_t len = (S - start < L) ? S - start : L;
+        int32_t keep = seg_keep(len, L, k);
+        for (int64_t t = 0; t < len; ++t) { seg[t].score = scores[start + t]; seg[t].index = (int32_t)(start + t); }
+        qsort(seg, (size_t)len, sizeof(scored_t), by_score_desc_then_index);
+        for (int32_t t = 0; t < keep; ++t) kept_idx[out + t] = seg[t].index;
+        qsort(kept_idx + out, (size_t)keep, sizeof(int32_t), by_int32);
+        out += keep;
+    }
+    free(seg);
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------- gather-GEMM */
+
+/* Y[m,n] = round( sum_c X[idx[m],c] * W[n,c] + bias[n] ), sum in double, ONE rounding to the
+ * output type (same type as the inputs).  idx == NULL means rows 0..M-1.  X is [S,C] with row
+ * stride ldx, W is [N,C] with row stride ldw, Y is [M,N] with row stride ldy (all in elements). */
+int oracle_gather_gemm(const void* X, int64_t S, int64_t ldx, const int32_t* idx, int64_t M,
+                       const void* W, int64_t ldw, const void* bias, void* Y, int64_t ldy,
+                       int32_t C, int32_t N, int dtype) {
+    if (!X || !W || !Y || S <= 0 || M < 0 || C <= 0 || N <= 0 || ldx < C || ldw < C || ldy < N) return ORACLE_ERR_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_ERR_ARG;
+    for (int64_t m = 0; m < M; ++m) {
+        int64_t r = idx ? idx[m] : m;
+        if (r < 0 || r >= S) return ORACLE_ERR_ARG;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        int64_t r = idx ? idx[m] : m;
+        for (int32_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int32_t c = 0; c < C; ++c)
+                acc += load_elem(X, r * ldx + c, dtype) * load_elem(W, (int64_t)n * ldw + c, dtype);
+            if (bias) acc += load_elem(bias, n, dtype);
+            if (dtype == ORACLE_BF16) ((uint16_t*)Y)[m * ldy + n] = double_to_bf16_bits(acc);
+            else ((float*)Y)[m * ldy + n] = (float)acc;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------- scatter-add */
+
+/* dX[idx[m],c] = round_to_dx_type( float(dX[idx[m],c]) + float(G[m,c]) ): one binary32 add and one
+ * rounding to the destination type per element (mixed bf16/fp32 precision, Sec. 6.1).  Rows not
+ * named by idx stay untouched in ACCUMULATE mode.  ZERO_PAD mode first sets the whole [S,C]
+ * destination to +0 and then accumulates, i.e. it writes the zero-padded G.  Indices must be
+ * unique and within [0,S). */
+int oracle_scatter_add(const void* G, int64_t ldg, const int32_t* idx, int64_t M, void* dX, int64_t lddx,
+                       int64_t S, int32_t C, int g_dtype, int dx_dtype, int mode) {
+    if (!G || !idx || !dX || S <= 0 || M < 0 || C <= 0 || ldg < C || lddx < C) return ORACLE_ERR_ARG;
+    if ((g_dtype != ORACLE_F32 && g_dtype != ORACLE_BF16) || (dx_dtype != ORACLE_F32 && dx_dtype != ORACLE_BF16)) return ORACLE_ERR_ARG;
+    if (mode != ORACLE_SCATTER_ACCUMULATE && mode != ORACLE_SCATTER_ZERO_PAD) return ORACLE_ERR_ARG;
+    unsigned char* seen = (unsigned char*)calloc((size_t)S, 1);
+    if (!seen) return ORACLE_ERR_NOMEM;
+    for (int64_t m = 0; m < M; ++m) {
+        if (idx[m] < 0 || idx[m] >= S || seen[idx[m]]) { free(seen); return ORACLE_ERR_ARG; }
+        seen[idx[m]] = 1;
+    }
+    free(seen);
+    if (mode == ORACLE_SCATTER_ZERO_PAD)
+        for (int64_t r = 0; r < S; ++r)
+            for (int32_t c = 0; c < C; ++c) {
+                if (dx_dtype == ORACLE_BF16) ((uint16_t*)dX)[r * lddx + c] = 0;
+                else ((float*)dX)[r * lddx + c] = 0.0f;
+            }
+    for (int64_t m = 0; m < M; ++m) {
+        int64_t r = idx[m];
+        for (int32_t c = 0; c < C; ++c) {
+            float g = (float)load_elem(G, m * ldg + c, g_dtype);
+            float x = (float)load_elem(dX, r * lddx + c, dx_dtype);
+            volatile float sum = x + g; /* a single binary32 addition, never contracted or widened */
+            if (dx_dtype == ORACLE_BF16) ((uint16_t*)dX)[r * lddx + c] = float_to_bf16_bits(sum);
+            else ((float*)dX)[r * lddx + c] = sum;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* exposed so tests can pin the bf16 rounding routine against an independent implementation */
+uint16_t oracle_double_to_bf16_bits(double x) { return double_to_bf16_bits(x); }

@@ -1,0 +1,201 @@
+"""ctypes front end of the C oracle.  TEST INFRASTRUCTURE ONLY (see lemo_oracle.c).
+
+bf16 tensors cross this boundary as numpy ``uint16`` arrays holding the raw bit patterns, so the
+oracle sees exactly the bits handed to the GPU.  fp32 tensors are ``float32`` arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+
+import numpy as np
+
+F32, BF16 = 0, 1
+CAUSAL, EXCLUDE_SELF = 1, 2
+SCATTER_ACCUMULATE, SCATTER_ZERO_PAD = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lemo_oracle.c")
+_LIB = os.path.join(_HERE, "liblemo_oracle.so")
+_lock = threading.Lock()
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile lemo_oracle.c into liblemo_oracle.so beside it (gcc -O2 -fopenmp)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.run(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off",
+                        "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    with _lock:
+        if _lib is None:
+            lib = ctypes.CDLL(build())
+            i64, i32, u32, dbl, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_double, ctypes.c_void_p
+            lib.oracle_keep_k.restype = i32
+            lib.oracle_keep_k.argtypes = [i32, dbl]
+            lib.oracle_kept_count.restype = i64
+            lib.oracle_kept_count.argtypes = [i64, i32, i32]
+            lib.oracle_score.restype = ctypes.c_int
+            lib.oracle_score.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, dbl, u32, vp, vp, vp]
+            lib.oracle_score_bruteforce.restype = ctypes.c_int
+            lib.oracle_score_bruteforce.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, dbl, u32, vp]
+            lib.oracle_select_topk.restype = ctypes.c_int
+            lib.oracle_select_topk.argtypes = [vp, i64, i32, i32, vp]
+            lib.oracle_gather_gemm.restype = ctypes.c_int
+            lib.oracle_gather_gemm.argtypes = [vp, i64, i64, vp, i64, vp, i64, vp, vp, i64, i32, i32, ctypes.c_int]
+            lib.oracle_scatter_add.restype = ctypes.c_int
+            lib.oracle_scatter_add.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+            lib.oracle_double_to_bf16_bits.restype = ctypes.c_uint16
+            lib.oracle_double_to_bf16_bits.argtypes = [dbl]
+            _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle takes float32 or uint16 (bf16 bits) arrays, got {a.dtype}")
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"{what} failed with oracle error {rc}")
+
+
+# ------------------------------------------------------------------ bf16 bit helpers (marshalling)
+
+def bf16_bits_to_float32(bits: np.ndarray) -> np.ndarray:
+    """Widen raw bf16 bit patterns exactly to float32."""
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def float32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to bf16 (ties to even) and return the bit patterns."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    lib = _load()
+    flat = x.reshape(-1)
+    out = np.empty(flat.shape, dtype=np.uint16)
+    for n, v in enumerate(flat):  # scalar routine; only used on small test arrays
+        out[n] = lib.oracle_double_to_bf16_bits(float(v))
+    return out.reshape(x.shape)
+
+
+def double_to_bf16_bits(x: float) -> int:
+    return int(_load().oracle_double_to_bf16_bits(float(x)))
+
+
+# ------------------------------------------------------------------ the four operations
+
+def keep_k(L: int, ratio: float) -> int:
+    return int(_load().oracle_keep_k(L, ratio))
+
+
+def kept_count(S: int, L: int, k: int) -> int:
+    return int(_load().oracle_kept_count(S, L, k))
+
+
+def _qk_layout(Q, K):
+    if Q.ndim != 3 or K.ndim != 3:
+        raise ValueError("Q must be [S,H,d] and K [S,H_kv,d]")
+    if Q.strides[2] != Q.itemsize or K.strides[2] != K.itemsize:
+        raise ValueError("head_dim must be contiguous")
+    S, H, d = Q.shape
+    if K.shape[0] != S or K.shape[2] != d:
+        raise ValueError("Q/K shape mismatch")
+    return S, H, K.shape[1], d, Q.strides[0] // Q.itemsize, Q.strides[1] // Q.itemsize, K.strides[0] // K.itemsize, K.strides[1] // K.itemsize
+
+
+def score(Q: np.ndarray, K: np.ndarray, flags: int = CAUSAL | EXCLUDE_SELF, scale: float = 0.0,
+          per_head: bool = False):
+    """Token informativeness (Sec. 4.2 Eq. 1, head mean of Eq. 2) -> float32 [S].
+
+    With ``per_head=True`` also returns the float64 [H,S] column sums (diagonal included) and the
+    float64 [H,S] diagonal probabilities.
+    """
+    S, H, Hkv, d, qts, qhs, kts, khs = _qk_layout(Q, K)
+    dt = _dtype_code(Q)
+    if _dtype_code(K) != dt:
+        raise TypeError("Q and K must share a dtype")
+    scores = np.empty(S, dtype=np.float32)
+    col = np.empty((H, S), dtype=np.float64) if per_head else None
+    dg = np.empty((H, S), dtype=np.float64) if per_head else None
+    _check(_load().oracle_score(_ptr(Q), _ptr(K), S, H, Hkv, d, dt, qts, qhs, kts, khs, float(scale), flags,
+                                _ptr(scores), _ptr(col), _ptr(dg)), "oracle_score")
+    return (scores, col, dg) if per_head else scores
+
+
+def score_bruteforce(Q: np.ndarray, K: np.ndarray, flags: int = CAUSAL | EXCLUDE_SELF, scale: float = 0.0):
+    """Same scores via the materialised S x S probability matrix (S <= 2048)."""
+    S, H, Hkv, d, qts, qhs, kts, khs = _qk_layout(Q, K)
+    dt = _dtype_code(Q)
+    scores = np.empty(S, dtype=np.float32)
+    _check(_load().oracle_score_bruteforce(_ptr(Q), _ptr(K), S, H, Hkv, d, dt, qts, qhs, kts, khs, float(scale),
+                                           flags, _ptr(scores)), "oracle_score_bruteforce")
+    return scores
+
+
+def select_topk(scores: np.ndarray, L: int, k: int) -> np.ndarray:
+    """Per-segment top-k (ties to the lower index), kept indices ascending -> int32 [M]."""
+    scores = np.ascontiguousarray(scores, dtype=np.float32)
+    S = scores.shape[0]
+    M = kept_count(S, L, k)
+    if M < 0:
+        raise ValueError("bad S/L/k")
+    out = np.empty(M, dtype=np.int32)
+    _check(_load().oracle_select_topk(_ptr(scores), S, L, k, _ptr(out)), "oracle_select_topk")
+    return out
+
+
+def gather_gemm(X: np.ndarray, idx, W: np.ndarray, bias=None) -> np.ndarray:
+    """Y[m,:] = X[idx[m],:] @ W.T (+ bias), fp64 accumulate, one rounding to the input dtype."""
+    X = np.ascontiguousarray(X)
+    W = np.ascontiguousarray(W)
+    dt = _dtype_code(X)
+    if _dtype_code(W) != dt:
+        raise TypeError("X and W must share a dtype")
+    S, C = X.shape
+    N = W.shape[0]
+    if W.shape[1] != C:
+        raise ValueError("W must be [N,C]")
+    if idx is not None:
+        idx = np.ascontiguousarray(idx, dtype=np.int32)
+        M = idx.shape[0]
+    else:
+        M = S
+    if bias is not None:
+        bias = np.ascontiguousarray(bias)
+        if _dtype_code(bias) != dt or bias.shape != (N,):
+            raise TypeError("bias must be [N] of the input dtype")
+    Y = np.empty((M, N), dtype=X.dtype)
+    _check(_load().oracle_gather_gemm(_ptr(X), S, C, _ptr(idx), M, _ptr(W), C, _ptr(bias), _ptr(Y), N, C, N, dt),
+           "oracle_gather_gemm")
+    return Y
+
+
+def scatter_add(G: np.ndarray, idx: np.ndarray, dX: np.ndarray, mode: int = SCATTER_ACCUMULATE) -> np.ndarray:
+    """In place: dX[idx[m],:] += G[m,:] (one binary32 add, one rounding).  Returns dX."""
+    G = np.ascontiguousarray(G)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    if not dX.flags.c_contiguous:
+        raise ValueError("dX must be C-contiguous (it is updated in place)")
+    M, C = G.shape
+    S = dX.shape[0]
+    if dX.shape[1] != C or idx.shape[0] != M:
+        raise ValueError("shape mismatch")
+    _check(_load().oracle_scatter_add(_ptr(G), C, _ptr(idx), M, _ptr(dX), C, S, C, _dtype_code(G), _dtype_code(dX), mode),
+           "oracle_scatter_add")
+    return dX
