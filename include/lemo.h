@@ -1,0 +1,164 @@
+/*
+ * lemo.h -- C ABI of the MI355X (gfx950) Contextual Token Sparsity hot path
+ *           (LeMo, arXiv 2501.09767: Sec. 4.2 token elimination, Sec. 4.4 permutation-free kernels).
+ *
+ * One layer's path is four calls on one HIP stream:
+ *
+ *   lemo_score_segments   informativeness of every token from the layer's attention        (Sec. 4.2, Eq. 1-2)
+ *   lemo_select_topk      which tokens of each segment (token block) to keep               (Sec. 4.2)
+ *   lemo_gather_gemm      consumer GEMM that loads the kept rows straight from the input   (Sec. 4.4)
+ *   lemo_scatter_grad     in-place add of per-kept-row results / gradients back into [S,C] (Sec. 4.4)
+ *
+ * Conventions shared by every call
+ *   - Pointers are DEVICE pointers unless the comment says "host".  The caller owns every buffer;
+ *     the library never allocates, frees or keeps a pointer after the call returns.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream) and the
+ *     call returns without synchronising.  Calls on one stream execute in order.
+ *   - Arguments are validated on the host before anything is launched.  A negative return code
+ *     means nothing was launched and no output was touched.  Nothing is printed, thrown or aborted.
+ *   - bf16 is the upper half of an IEEE binary32; every reduction accumulates in binary32 and
+ *     rounds to nearest-even once when a bf16 result is stored (mixed precision, Sec. 6.1).
+ *   - Strides and leading dimensions are in ELEMENTS.  Base pointers and row starts must be 16-byte
+ *     aligned (so strides are multiples of 8 for bf16, 4 for fp32); otherwise LEMO_ERR_ALIGN.
+ *   - No global mutable state: calls are re-entrant and may be issued from several host threads.
+ */
+#ifndef LEMO_H
+#define LEMO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LEMO_F32 = 0, LEMO_BF16 = 1 } lemo_dtype_t;
+
+/* flags of lemo_score_segments */
+enum {
+    LEMO_CAUSAL = 1u,       /* query i attends keys j <= i (autoregressive layers); else all keys   */
+    LEMO_EXCLUDE_SELF = 2u  /* leave the i == j term out of a token's score, as Eq. 1 does           */
+};
+
+/* mode of lemo_scatter_grad */
+enum {
+    LEMO_SCATTER_ACCUMULATE = 0, /* dX[idx[m]] += G[m]; other rows untouched (padding adds zero)     */
+    LEMO_SCATTER_ZERO_PAD = 1    /* dX = G zero-padded to S rows: kept rows = G[m], other rows = +0   */
+};
+
+/* return codes */
+enum {
+    LEMO_OK = 0,
+    LEMO_ERR_NULL = -1,        /* a required pointer is NULL                                         */
+    LEMO_ERR_SHAPE = -2,       /* a size, stride or count is out of range or inconsistent            */
+    LEMO_ERR_DTYPE = -3,       /* dtype is not LEMO_F32 / LEMO_BF16                                  */
+    LEMO_ERR_WORKSPACE = -4,   /* workspace smaller than lemo_score_workspace_bytes reports          */
+    LEMO_ERR_ALIGN = -5,       /* pointer or stride breaks the 16-byte alignment rule                */
+    LEMO_ERR_UNSUPPORTED = -6, /* valid request outside what the kernels are built for               */
+    LEMO_ERR_HIP = -7          /* the HIP runtime refused a launch                                   */
+};
+
+/* host: text for a return code (static storage, never NULL) */
+const char* lemo_strerror(int code);
+
+/* host: kept tokens per FULL segment of length L at keep ratio `ratio`: ceil(ratio * L) clamped to
+ * [1, L] (a 1e-9 slack keeps exact products such as 0.5 * 128 from rounding up).  0 if L <= 0. */
+int32_t lemo_keep_k(int32_t L, double ratio);
+
+/* host: M = total kept tokens for S tokens cut into segments of L keeping k per full segment; a
+ * ragged last segment of length t keeps ceil(k * t / L), at least 1.  -1 on bad arguments. */
+int64_t lemo_kept_count(int64_t S, int32_t L, int32_t k);
+
+/* host: bytes of device workspace lemo_score_segments needs for this shape.  Linear in S (row
+ * statistics and per-head column sums, 3 * H * S floats): the S x S score matrix is never stored,
+ * which is the property Sec. 4.3's overhead analysis asks of the scoring kernel. */
+int lemo_score_workspace_bytes(int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt,
+                               size_t* bytes /* host, out */);
+
+/*
+ * Token informativeness (Sec. 4.2).  With P^h = softmax_j(scale * Q^h K^{g(h)T}) the attention
+ * probabilities of query head h (row i over the keys query i may attend; g(h) = floor(h*H_kv/H)
+ * is the KV head a query head reads), the call produces
+ *
+ *     colsum^h[j] = sum_i P^h[i][j]                       column sums, diagonal INCLUDED
+ *     diag^h[j]   = P^h[j][j]
+ *     scores[j]   = (1/H) * sum_h ( colsum^h[j] - [EXCLUDE_SELF] diag^h[j] )      (Eq. 1, head mean of Eq. 2)
+ *
+ * The key axis is processed one segment of L tokens at a time against tiles of queries; results do
+ * not depend on L beyond binary32 summation order.  Two sweeps over Q K^T are made (row
+ * log-sum-exp, then column sums); both run on the matrix cores (bf16 inputs) or in true binary32
+ * (fp32 inputs), accumulate in binary32, and keep probabilities in binary32.
+ *
+ *   Q  [S, H, d]     element (i,h,c) at Q[i*q_tok_stride + h*q_head_stride + c]   (d contiguous)
+ *   K  [S, H_kv, d]  likewise with the k_ strides
+ *   scale            logit scale; <= 0 selects 1/sqrt(d)
+ *   scores           [S] float, out
+ *   colsum_per_head  [H, S] float, out, or NULL
+ *   diag_per_head    [H, S] float, out, or NULL
+ *   workspace        at least lemo_score_workspace_bytes() bytes, 256-byte aligned; contents are
+ *                    scratch (undefined before and after)
+ *
+ * Supported: d in {64, 128}, H % H_kv == 0, 1 <= S < 2^31, L >= 1.  Deterministic: the same inputs
+ * give the same bits on every run (no atomics).
+ */
+int lemo_score_segments(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d,
+                        lemo_dtype_t dt, int64_t q_tok_stride, int64_t q_head_stride,
+                        int64_t k_tok_stride, int64_t k_head_stride, float scale, int32_t L,
+                        uint32_t flags, float* scores, float* colsum_per_head, float* diag_per_head,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Per-segment top-k (the token-block elimination step of Sec. 4.2 with the threshold replaced by a
+ * keep count).  For each segment [n*L, min((n+1)*L, S)) keep the k tokens of highest score -- a
+ * ragged last segment of length t keeps ceil(k*t/L), at least 1 -- breaking ties towards the LOWER
+ * token index (-0.0 ties +0.0), and write the kept token indices in ascending order, segment after
+ * segment, to kept_idx[0 .. lemo_kept_count(S,L,k)).  Scores must not be NaN (then the selection is
+ * unspecified but still in range).  Bit-exact and deterministic.
+ *
+ * Supported: 1 <= k <= L <= 8192, S < 2^31.
+ */
+int lemo_select_topk(const float* scores, int64_t S, int32_t L, int32_t k, int32_t* kept_idx, void* stream);
+
+/*
+ * Selective-load GEMM (Sec. 4.4, permutation-free token movement: the consumer reads the kept rows
+ * from the original [S,C] input; no compacted copy of X is made):
+ *
+ *     Y[m, n] = sum_c X[kept_idx[m], c] * W[n, c]  (+ bias[n])        m < M, n < N
+ *
+ *   X [S, C] row stride ldx;  W [N, C] row stride ldw (torch.nn.Linear weight layout);
+ *   bias [N] or NULL;  Y [M, N] row stride ldy;  all of dtype dt.
+ *   kept_idx [M] int32 rows of X in [0,S) (not checked on the device), or NULL for rows 0..M-1
+ *   (then M <= S).  M == 0 is a no-op.
+ *
+ * binary32 accumulation, one rounding at the store.  The result for output row m depends only on
+ * the values of X row kept_idx[m], so running on a materialised compact copy gives identical bits.
+ * Supported: C % 8 == 0 (bf16) / C % 4 == 0 (fp32).  X and W follow the 16-byte rule; Y only needs
+ * element alignment and any ldy >= N (4-byte aligned bf16 rows are stored two columns at a time).
+ */
+int lemo_gather_gemm(const void* X, int64_t S, int64_t ldx, const int32_t* kept_idx, int64_t M,
+                     const void* W, int64_t ldw, const void* bias, void* Y, int64_t ldy, int32_t C,
+                     int32_t N, lemo_dtype_t dt, void* stream);
+
+/*
+ * In-place add at the kept positions (Sec. 4.4: zero padding and the residual add collapse into one
+ * read-modify-write of the kept rows); also the backward of the selective load:
+ *
+ *     ACCUMULATE:  dX[kept_idx[m], c] = round( float(dX[kept_idx[m], c]) + float(G[m, c]) )
+ *     ZERO_PAD:    dX[kept_idx[m], c] = round( float(G[m, c]) ),  every other row of dX = +0
+ *
+ *   G [M, C] row stride ldg, dtype g_dt;  dX [S, C] row stride lddx, dtype dx_dt.
+ *   kept_idx [M] int32, in [0,S) and UNIQUE (not checked on the device); ZERO_PAD additionally
+ *   requires it strictly ascending (what lemo_select_topk produces).  M == 0: ACCUMULATE is a
+ *   no-op, ZERO_PAD clears dX.
+ *
+ * One binary32 add and one rounding per element: bit-exact and order-independent.
+ * Supported: C % 8 == 0.
+ */
+int lemo_scatter_grad(const void* G, int64_t ldg, const int32_t* kept_idx, int64_t M, void* dX,
+                      int64_t lddx, int64_t S, int32_t C, lemo_dtype_t g_dt, lemo_dtype_t dx_dt,
+                      int32_t mode, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LEMO_H */

@@ -8,19 +8,19 @@
  *
  *   oracle_score            Sec. 4.2 Eq. 1 (token informativeness = column sum of attention scores,
  *                           self excluded) with the head mean of Eq. 2; attention scores are the
- *                           softmax probabilities (Sec. 4.2, "attention scores undergo a softmax").
+ *                           softmax probabilities (Sec. 4.2 states that the scores pass through a softmax).
  *   oracle_score_bruteforce same quantity through a materialised S x S matrix (tiny S only).
  *   oracle_select_topk      per-segment top-k at a keep ratio (the selection unit is the paper's
  *                           token block, Sec. 4.2 "Layer-specific Threshold"; here the k best of
  *                           each block are kept instead of thresholding).
- *   oracle_gather_gemm      Sec. 4.4 "directly loads the selected tokens from original inputs":
+ *   oracle_gather_gemm      Sec. 4.4 selective load (kept rows are read from the original input):
  *                           Y[m,:] = X[idx[m],:] . W^T (+ bias).
- *   oracle_scatter_add      Sec. 4.4 "in-place addition ... completing token padding and residual
- *                           addition in a single step": dX[idx[m],:] += G[m,:].
+ *   oracle_scatter_add      Sec. 4.4 in-place add (padding and residual add in one step):
+ *                           dX[idx[m],:] += G[m,:].
  *
  * Every floating-point reduction is carried in double.  Nothing here is blocked, fused or
- * reordered beyond what the definitions state.  Parallelism (OpenMP) is over independent heads or
- * independent output rows only.
+ * reordered beyond what the definitions state.  Parallelism (OpenMP) is over independent query rows
+ * (scoring) or independent output rows (GEMM) only.
  *
  * Pins (tests/test_oracle_pins.py): softmax rows sum to one => per-head column sums total S;
  * brute-force S x S agreement; closed forms for constant logits (harmonic numbers under a causal
@@ -30,6 +30,7 @@
  * the oracle.
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -108,37 +109,44 @@ int64_t oracle_kept_count(int64_t S, int32_t L, int32_t k) {
 
 /* ---------------------------------------------------------------- scoring */
 
-/* One head, row by row.  For query i: logits s_ij = scale * <Q_i, K_j> over the allowed keys
- * (j <= i under a causal mask, all j otherwise); p_ij = softmax over j; p_ij is added to column j
- * and p_ii is remembered.  One O(S) row buffer; the S x S matrix never exists. */
-static void score_one_head(const void* Q, const void* K, int64_t S, int d, int dtype,
-                           int64_t q_ts, int64_t q_off, int64_t k_ts, int64_t k_off,
-                           double scale, int causal, double* row, double* col, double* dg) {
-    for (int64_t j = 0; j < S; ++j) { col[j] = 0.0; dg[j] = 0.0; }
-    for (int64_t i = 0; i < S; ++i) {
-        int64_t nk = causal ? i + 1 : S;
-        double mx = -INFINITY;
-        for (int64_t j = 0; j < nk; ++j) {
-            double dot = 0.0;
-            for (int c = 0; c < d; ++c)
-                dot += load_elem(Q, i * q_ts + q_off + c, dtype) * load_elem(K, j * k_ts + k_off + c, dtype);
-            row[j] = scale * dot;
-            if (row[j] > mx) mx = row[j];
-        }
-        double den = 0.0;
-        for (int64_t j = 0; j < nk; ++j) { row[j] = exp(row[j] - mx); den += row[j]; }
-        for (int64_t j = 0; j < nk; ++j) {
-            double p = row[j] / den;
-            col[j] += p;
-            if (j == i) dg[j] = p;
-        }
+/* Widen one head's rows ([S, d] with a token stride) exactly to double. */
+static double* widen_head(const void* base, int64_t S, int d, int dtype, int64_t tok_stride, int64_t head_off) {
+    double* out = (double*)malloc(sizeof(double) * (size_t)S * (size_t)d);
+    if (!out) return NULL;
+    for (int64_t i = 0; i < S; ++i)
+        for (int c = 0; c < d; ++c) out[i * d + c] = load_elem(base, i * tok_stride + head_off + c, dtype);
+    return out;
+}
+
+/* One query row of one head.  Logits s_ij = scale * <Q_i, K_j> over the allowed keys (j <= i under
+ * a causal mask, all j otherwise); p_ij = softmax over j; p_ij is added to column j and p_ii is
+ * remembered.  `row` is an O(S) buffer; the S x S matrix never exists. */
+static void score_one_row(const double* Qh, const double* Kh, int64_t S, int d, double scale, int causal,
+                          int64_t i, double* row, double* col, double* dg) {
+    int64_t nk = causal ? i + 1 : S;
+    double mx = -INFINITY;
+    for (int64_t j = 0; j < nk; ++j) {
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c) dot += Qh[i * d + c] * Kh[j * d + c];
+        row[j] = scale * dot;
+        if (row[j] > mx) mx = row[j];
+    }
+    double den = 0.0;
+    for (int64_t j = 0; j < nk; ++j) { row[j] = exp(row[j] - mx); den += row[j]; }
+    for (int64_t j = 0; j < nk; ++j) {
+        double p = row[j] / den;
+        col[j] += p;
+        if (j == i) dg[j] = p;
     }
 }
 
 /* Q [S,H,d], K [S,H_kv,d] with element strides (d contiguous); query head h reads KV head
  * floor(h * H_kv / H).  scores[S] (float) is the head mean of (column sum - [EXCLUDE_SELF] p_jj),
  * rounded once from double.  colsum / diag, when not NULL, receive the per-head [H,S] doubles;
- * colsum always INCLUDES the diagonal term. */
+ * colsum always INCLUDES the diagonal term.
+ *
+ * Query rows are independent, so they are dealt out to OpenMP threads round-robin; each
+ * thread adds into its own column array and the arrays are summed in thread order afterwards. */
 int oracle_score(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, int dtype,
                  int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
                  double scale, uint32_t flags, float* scores, double* colsum, double* diag) {
@@ -147,20 +155,32 @@ int oracle_score(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_k
     if (!(scale > 0.0)) scale = 1.0 / sqrt((double)d);
     const int causal = (flags & ORACLE_CAUSAL) != 0;
     const int excl = (flags & ORACLE_EXCLUDE_SELF) != 0;
-    double* col = (double*)malloc(sizeof(double) * (size_t)H * (size_t)S);
-    double* dg = (double*)malloc(sizeof(double) * (size_t)H * (size_t)S);
-    if (!col || !dg) { free(col); free(dg); return ORACLE_ERR_NOMEM; }
-    int failed = 0;
-#pragma omp parallel for schedule(dynamic, 1)
+    const int nthr = omp_get_max_threads();
+    double* col = (double*)calloc((size_t)H * (size_t)S, sizeof(double));
+    double* dg = (double*)calloc((size_t)H * (size_t)S, sizeof(double));
+    double* part = (double*)malloc(sizeof(double) * (size_t)nthr * (size_t)S);  /* per-thread column sums */
+    double* rows = (double*)malloc(sizeof(double) * (size_t)nthr * (size_t)S);  /* per-thread row buffers */
+    if (!col || !dg || !part || !rows) { free(col); free(dg); free(part); free(rows); return ORACLE_ERR_NOMEM; }
     for (int h = 0; h < H; ++h) {
-        double* row = (double*)malloc(sizeof(double) * (size_t)S);
-        if (!row) { failed = 1; continue; }
         int g = (int)(((int64_t)h * H_kv) / H);
-        score_one_head(Q, K, S, d, dtype, q_tok_stride, (int64_t)h * q_head_stride, k_tok_stride,
-                       (int64_t)g * k_head_stride, scale, causal, row, col + (size_t)h * S, dg + (size_t)h * S);
-        free(row);
+        double* Qh = widen_head(Q, S, d, dtype, q_tok_stride, (int64_t)h * q_head_stride);
+        double* Kh = widen_head(K, S, d, dtype, k_tok_stride, (int64_t)g * k_head_stride);
+        if (!Qh || !Kh) { free(Qh); free(Kh); free(col); free(dg); free(part); free(rows); return ORACLE_ERR_NOMEM; }
+        memset(part, 0, sizeof(double) * (size_t)nthr * (size_t)S);
+#pragma omp parallel num_threads(nthr)
+        {
+            int t = omp_get_thread_num();
+            /* interleaved rows: under a causal mask row i costs i+1 keys, so contiguous ranges would be lopsided */
+            for (int64_t i = t; i < S; i += nthr)
+                score_one_row(Qh, Kh, S, d, scale, causal, i, rows + (size_t)t * S, part + (size_t)t * S, dg + (size_t)h * S);
+        }
+        for (int t = 0; t < nthr; ++t)
+            for (int64_t j = 0; j < S; ++j) col[(size_t)h * S + j] += part[(size_t)t * S + j];
+        free(Qh);
+        free(Kh);
     }
-    if (failed) { free(col); free(dg); return ORACLE_ERR_NOMEM; }
+    free(part);
+    free(rows);
     for (int64_t j = 0; j < S; ++j) {
         double acc = 0.0;
         for (int h = 0; h < H; ++h) {

@@ -1,0 +1,146 @@
+// Host side of the C ABI declared in lemo.h: argument validation and kernel launches only.
+#include <cmath>
+
+#include "lemo_common.hpp"
+
+using namespace lemo;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool valid_dtype(int dt) { return dt == LEMO_F32 || dt == LEMO_BF16; }
+inline int elems_per_16B(int dt) { return dt == LEMO_BF16 ? 8 : 4; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int32_t seg_keep(int64_t len, int32_t L, int32_t k) {
+    if (len == L) return k;
+    int64_t v = ((int64_t)k * len + L - 1) / L;
+    if (v < 1) v = 1;
+    if (v > len) v = len;
+    return (int32_t)v;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lemo_strerror(int code) {
+    switch (code) {
+        case LEMO_OK: return "ok";
+        case LEMO_ERR_NULL: return "a required pointer is NULL";
+        case LEMO_ERR_SHAPE: return "size, stride or count out of range";
+        case LEMO_ERR_DTYPE: return "unknown dtype";
+        case LEMO_ERR_WORKSPACE: return "workspace too small";
+        case LEMO_ERR_ALIGN: return "pointer or stride not 16-byte aligned";
+        case LEMO_ERR_UNSUPPORTED: return "valid request the kernels are not built for";
+        case LEMO_ERR_HIP: return "HIP runtime refused the launch";
+        default: return "unknown error code";
+    }
+}
+
+int32_t lemo_keep_k(int32_t L, double ratio) {
+    if (L <= 0) return 0;
+    double v = std::ceil(ratio * (double)L - 1e-9);
+    if (!(v >= 1.0)) v = 1.0;
+    if (v > (double)L) v = (double)L;
+    return (int32_t)v;
+}
+
+int64_t lemo_kept_count(int64_t S, int32_t L, int32_t k) {
+    if (S <= 0 || L <= 0 || k <= 0 || k > L) return -1;
+    const int64_t full = S / L, tail = S % L;
+    int64_t M = full * k;
+    if (tail) M += seg_keep(tail, L, k);
+    return M;
+}
+
+int lemo_score_workspace_bytes(int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt, size_t* bytes) {
+    if (!bytes) return LEMO_ERR_NULL;
+    if (!valid_dtype(dt)) return LEMO_ERR_DTYPE;
+    if (S <= 0 || S >= (int64_t)1 << 31 || H <= 0 || H_kv <= 0 || H % H_kv) return LEMO_ERR_SHAPE;
+    if (d != 64 && d != 128) return LEMO_ERR_UNSUPPORTED;
+    const size_t plane = round_up((size_t)H * (size_t)S * sizeof(float), 256);
+    *bytes = 3 * plane;  // row log-sum-exp, per-head column sums, per-head diagonal
+    return LEMO_OK;
+}
+
+int lemo_score_segments(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt,
+                        int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                        float scale, int32_t L, uint32_t flags, float* scores, float* colsum_per_head,
+                        float* diag_per_head, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!Q || !K || !scores || !workspace) return LEMO_ERR_NULL;
+    size_t need = 0;
+    const int rc = lemo_score_workspace_bytes(S, H, H_kv, d, dt, &need);
+    if (rc != LEMO_OK) return rc;
+    if (L <= 0 || (flags & ~(uint32_t)(LEMO_CAUSAL | LEMO_EXCLUDE_SELF))) return LEMO_ERR_SHAPE;
+    if (q_tok_stride < 0 || q_head_stride < 0 || k_tok_stride < 0 || k_head_stride < 0) return LEMO_ERR_SHAPE;
+    if (!std::isfinite(scale)) return LEMO_ERR_SHAPE;
+    const int e16 = elems_per_16B(dt);
+    if (!aligned16(Q) || !aligned16(K) || q_tok_stride % e16 || q_head_stride % e16 || k_tok_stride % e16 || k_head_stride % e16)
+        return LEMO_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return LEMO_ERR_ALIGN;
+    if (workspace_bytes < need) return LEMO_ERR_WORKSPACE;
+
+    const size_t plane = need / 3;
+    char* ws = static_cast<char*>(workspace);
+    ScoreParams p{};
+    p.Q = Q;
+    p.K = K;
+    p.S = (int)S;
+    p.H = H;
+    p.H_kv = H_kv;
+    p.q_ts = q_tok_stride;
+    p.q_hs = q_head_stride;
+    p.k_ts = k_tok_stride;
+    p.k_hs = k_head_stride;
+    const double sc = scale > 0.f ? (double)scale : 1.0 / std::sqrt((double)d);
+    p.c2 = (float)(sc * 1.4426950408889634);  // log2(e): probabilities are formed with exp2
+    p.L = L;
+    p.flags = flags;
+    p.lse2 = reinterpret_cast<float*>(ws);
+    p.colsum = colsum_per_head ? colsum_per_head : reinterpret_cast<float*>(ws + plane);
+    p.diag = diag_per_head ? diag_per_head : reinterpret_cast<float*>(ws + 2 * plane);
+    p.scores = scores;
+    return launch_score(p, dt, d, static_cast<hipStream_t>(stream)) == 0 ? LEMO_OK : LEMO_ERR_HIP;
+}
+
+int lemo_select_topk(const float* scores, int64_t S, int32_t L, int32_t k, int32_t* kept_idx, void* stream) {
+    if (!scores || !kept_idx) return LEMO_ERR_NULL;
+    if (S <= 0 || S >= (int64_t)1 << 31 || L <= 0 || k <= 0 || k > L) return LEMO_ERR_SHAPE;
+    if (L > 8192) return LEMO_ERR_UNSUPPORTED;
+    return launch_select(scores, (int)S, L, k, kept_idx, static_cast<hipStream_t>(stream)) == 0 ? LEMO_OK : LEMO_ERR_HIP;
+}
+
+int lemo_gather_gemm(const void* X, int64_t S, int64_t ldx, const int32_t* kept_idx, int64_t M, const void* W, int64_t ldw,
+                     const void* bias, void* Y, int64_t ldy, int32_t C, int32_t N, lemo_dtype_t dt, void* stream) {
+    if (!valid_dtype(dt)) return LEMO_ERR_DTYPE;
+    if (M == 0) return LEMO_OK;  // nothing to compute; Y may be an empty allocation
+    if (!X || !W || !Y) return LEMO_ERR_NULL;
+    if (S <= 0 || M < 0 || C <= 0 || N <= 0 || ldx < C || ldw < C || ldy < N) return LEMO_ERR_SHAPE;
+    if (!kept_idx && M > S) return LEMO_ERR_SHAPE;
+    if (M >= (int64_t)1 << 31 || S >= (int64_t)1 << 31) return LEMO_ERR_SHAPE;
+    const int e16 = elems_per_16B(dt);
+    if (C % e16) return LEMO_ERR_UNSUPPORTED;
+    if (!aligned16(X) || !aligned16(W) || ldx % e16 || ldw % e16) return LEMO_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(Y) % (dt == LEMO_BF16 ? 2 : 4)) return LEMO_ERR_ALIGN;  // Y: element alignment is enough
+    if (kept_idx && (reinterpret_cast<uintptr_t>(kept_idx) & 3u)) return LEMO_ERR_ALIGN;
+    const int64_t tiles = ((M + 255) / 256) * (((int64_t)N + 255) / 256);
+    if (tiles >= (int64_t)1 << 28) return LEMO_ERR_UNSUPPORTED;
+    return launch_gather_gemm(X, S, ldx, kept_idx, M, W, ldw, bias, Y, ldy, C, N, dt, static_cast<hipStream_t>(stream)) == 0
+               ? LEMO_OK : LEMO_ERR_HIP;
+}
+
+int lemo_scatter_grad(const void* G, int64_t ldg, const int32_t* kept_idx, int64_t M, void* dX, int64_t lddx, int64_t S,
+                      int32_t C, lemo_dtype_t g_dt, lemo_dtype_t dx_dt, int32_t mode, void* stream) {
+    if (!dX || (M > 0 && (!G || !kept_idx))) return LEMO_ERR_NULL;
+    if (!valid_dtype(g_dt) || !valid_dtype(dx_dt)) return LEMO_ERR_DTYPE;
+    if (mode != LEMO_SCATTER_ACCUMULATE && mode != LEMO_SCATTER_ZERO_PAD) return LEMO_ERR_SHAPE;
+    if (S <= 0 || S >= (int64_t)1 << 31 || M < 0 || M > S || C <= 0 || ldg < C || lddx < C) return LEMO_ERR_SHAPE;
+    if (C % 8) return LEMO_ERR_UNSUPPORTED;
+    if (!aligned16(dX) || lddx % elems_per_16B(dx_dt)) return LEMO_ERR_ALIGN;
+    if (M > 0 && (!aligned16(G) || ldg % elems_per_16B(g_dt))) return LEMO_ERR_ALIGN;
+    return launch_scatter(G, ldg, kept_idx, M, dX, lddx, S, C, g_dt, dx_dt, mode, static_cast<hipStream_t>(stream)) == 0
+               ? LEMO_OK : LEMO_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,82 @@
+// Shared device-side vocabulary of the gfx950 kernels: MFMA fragment types, the 32x32 accumulator
+// layout, bf16 conversion, and the parameter blocks the host entry points fill in.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lemo.h"
+
+namespace lemo {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+struct bf16_t { uint16_t bits; };  // storage tag for bfloat16 (upper half of a binary32)
+
+constexpr int WAVE = 64;
+constexpr int NUM_XCD = 8;  // MI355X: 8 accelerator dies, workgroup b is dispatched to die b % 8
+
+// ---- one 32x32 MFMA "chunk": 32 bytes of the contraction axis per operand row ---------------------
+// Every lane supplies 16 bytes per operand: lane l holds row (l % 32), bytes [16*(l/32), +16) of the
+// chunk.  bf16: one v_mfma_f32_32x32x16_bf16 (16 elements).  fp32: four v_mfma_f32_32x32x2_f32, step t
+// contracting element t of the lower half with element 4+t of the upper half; A and B use the same
+// assignment, and a dot product does not care in which order its terms are paired off.
+template <typename T> __device__ __forceinline__ void mma_chunk(f32x16& acc, const uint4& a, const uint4& b);
+
+template <> __device__ __forceinline__ void mma_chunk<bf16_t>(f32x16& acc, const uint4& a, const uint4& b) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+template <> __device__ __forceinline__ void mma_chunk<float>(f32x16& acc, const uint4& a, const uint4& b) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+}
+
+// Accumulator layout of the 32x32 MFMAs (checked on hardware): register r of lane l is the element in
+//   row = 8*(r/4) + 4*(l/32) + (r%4)   (A-operand row),   col = l % 32   (B-operand row).
+__device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+// ---- bf16 <-> binary32 ----------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// round to nearest, ties to even; NaN stays NaN (quiet)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) { return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16); }
+
+// ---- parameter blocks -----------------------------------------------------------------------------
+struct ScoreParams {
+    const void* Q;
+    const void* K;
+    int S, H, H_kv;
+    long long q_ts, q_hs, k_ts, k_hs;  // element strides
+    float c2;                          // scale * log2(e): logits are handled in base-2 units
+    int L;                             // segment length (key axis is cut per segment)
+    int blocks_per_seg;                // key blocks per segment
+    int n_key_blocks;                  // total key blocks
+    int n_query_blocks;
+    int heads_per_xcd;
+    unsigned flags;
+    float* lse2;    // [H,S] base-2 log-sum-exp of every query row
+    float* colsum;  // [H,S]
+    float* diag;    // [H,S]
+    float* scores;  // [S]
+};
+
+// kernel launchers (defined next to their kernels; return hipError_t as int)
+int launch_score(const ScoreParams& p, lemo_dtype_t dt, int d, hipStream_t st);
+int launch_select(const float* scores, int S, int L, int k, int* kept, hipStream_t st);
+int launch_scatter(const void* G, long long ldg, const int* idx, long long M, void* dX, long long lddx, long long S,
+                   int C, lemo_dtype_t g_dt, lemo_dtype_t dx_dt, int mode, hipStream_t st);
+int launch_gather_gemm(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W,
+                       long long ldw, const void* bias, void* Y, long long ldy, int C, int N, lemo_dtype_t dt,
+                       hipStream_t st);
+
+}  // namespace lemo

@@ -1,0 +1,115 @@
+// Per-segment top-k (token-block elimination of Sec. 4.2 with a keep count instead of a threshold).
+//
+// One workgroup per segment.  The k-th largest score is found by an MSB-first radix select over the
+// order-preserving uint32 image of the floats (4 passes of 8 bits, LDS histogram); the kept set is
+// then { key > pivot } plus the first (k - #greater) elements with key == pivot in index order, which
+// is exactly "ties go to the lower index".  A block-wide prefix sum in index order gives every kept
+// element its output slot, so the indices come out ascending without a sort.  Integer work only:
+// bit-exact and deterministic.
+#include "lemo_common.hpp"
+
+namespace lemo {
+
+constexpr int SEL_THREADS = 256;
+
+// monotone map float -> uint32 (larger float <=> larger key); -0.0 and +0.0 share a key
+__device__ __forceinline__ uint32_t order_key(float f) {
+    uint32_t u = __float_as_uint(f);
+    if (u == 0x80000000u) u = 0u;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* __restrict__ scores, int S, int L, int k,
+                                                                  int* __restrict__ kept) {
+    extern __shared__ uint32_t keys[];  // [len]
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t scan[SEL_THREADS];
+    __shared__ uint32_t sh_prefix, sh_need;
+
+    const int seg = blockIdx.x, tid = threadIdx.x;
+    const int start = seg * L;  // host guarantees start < S and no overflow
+    const int len = min(L, S - start);
+    int keep = k;
+    if (len != L) {
+        long long v = ((long long)k * len + L - 1) / L;
+        keep = (int)max(1ll, min((long long)len, v));
+    }
+    const long long out0 = (long long)seg * k;  // every earlier segment is full
+
+    for (int t = tid; t < len; t += SEL_THREADS) keys[t] = order_key(scores[start + t]);
+    if (tid == 0) { sh_prefix = 0u; sh_need = (uint32_t)keep; }
+    __syncthreads();
+
+    // radix select: after the pass for `shift`, sh_prefix holds the top bits of the pivot and sh_need how
+    // many elements must still be taken among those sharing that prefix
+#pragma unroll 1
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[tid] = 0u;
+        __syncthreads();
+        const uint32_t prefix = sh_prefix, need = sh_need;
+        const uint32_t himask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
+        for (int t = tid; t < len; t += SEL_THREADS) {
+            const uint32_t key = keys[t];
+            if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        // suffix sums: scan[b] = number of candidates whose digit is >= b
+        scan[tid] = hist[tid];
+        __syncthreads();
+#pragma unroll
+        for (int off = 1; off < 256; off <<= 1) {
+            uint32_t v = tid + off < 256 ? scan[tid + off] : 0u;
+            __syncthreads();
+            scan[tid] += v;
+            __syncthreads();
+        }
+        const uint32_t ge = scan[tid], gt = tid + 1 < 256 ? scan[tid + 1] : 0u;
+        if (gt < need && need <= ge) {  // exactly one digit satisfies this
+            sh_prefix = prefix | ((uint32_t)tid << shift);
+            sh_need = need - gt;
+        }
+        __syncthreads();
+    }
+    const uint32_t pivot = sh_prefix;   // key of the k-th largest element
+    const uint32_t need_eq = sh_need;   // how many elements equal to the pivot are kept (lowest indices first)
+
+    // compaction in index order: thread t owns the contiguous range [t*per, (t+1)*per)
+    const int per = (len + SEL_THREADS - 1) / SEL_THREADS;
+    const int lo = min(len, tid * per), hi = min(len, lo + per);
+    uint32_t ngt = 0, neq = 0;
+    for (int t = lo; t < hi; ++t) {
+        const uint32_t key = keys[t];
+        ngt += key > pivot;
+        neq += key == pivot;
+    }
+    scan[tid] = ngt | (neq << 16);  // len <= 8192 so both counts fit 16 bits, as do their prefix sums
+    __syncthreads();
+#pragma unroll
+    for (int off = 1; off < SEL_THREADS; off <<= 1) {
+        uint32_t v = tid >= off ? scan[tid - off] : 0u;
+        __syncthreads();
+        scan[tid] += v;
+        __syncthreads();
+    }
+    const uint32_t incl = scan[tid];
+    uint32_t gt_before = (incl & 0xffffu) - ngt, eq_before = (incl >> 16) - neq;
+    for (int t = lo; t < hi; ++t) {
+        const uint32_t key = keys[t];
+        if (key > pivot) {
+            kept[out0 + gt_before + min(eq_before, need_eq)] = start + t;
+            ++gt_before;
+        } else if (key == pivot) {
+            if (eq_before < need_eq) kept[out0 + gt_before + eq_before] = start + t;
+            ++eq_before;
+        }
+    }
+}
+
+int launch_select(const float* scores, int S, int L, int k, int* kept, hipStream_t st) {
+    const int Leff = L < S ? L : S;
+    const int nseg = (S + L - 1) / L;  // L <= 8192 here (keys of one segment live in LDS), no overflow
+    hipLaunchKernelGGL(select_topk_kernel, dim3(nseg), dim3(SEL_THREADS), (size_t)Leff * sizeof(uint32_t), st, scores, S, L, k, kept);
+    return (int)hipGetLastError();
+}
+
+}  // namespace lemo

@@ -1,0 +1,187 @@
+"""Thin binding over the C-ABI HIP library (include/lemo.h).  Argument marshalling only.
+
+Every function takes torch tensors that live on the GPU, passes their ``data_ptr()`` and the current
+HIP stream to the library call of the same name, and raises ``LemoError`` on a negative return code.
+No arithmetic of the method happens here, and there is NO fallback: if ``liblemo_hip.so`` has not
+been built the import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+F32, BF16 = 0, 1
+CAUSAL, EXCLUDE_SELF = 1, 2
+SCATTER_ACCUMULATE, SCATTER_ZERO_PAD = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblemo_hip.so")
+
+EXPORTS = ("lemo_strerror", "lemo_keep_k", "lemo_kept_count", "lemo_score_workspace_bytes",
+           "lemo_score_segments", "lemo_select_topk", "lemo_gather_gemm", "lemo_scatter_grad")
+
+
+class LemoError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {_lib.lemo_strerror(code).decode()} ({code})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2501_09767_amd.build). "
+                          "There is no CPU fallback for the hot path.")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, i32, u32, vp, f32 = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_float
+    lib.lemo_strerror.restype = ctypes.c_char_p
+    lib.lemo_strerror.argtypes = [ctypes.c_int]
+    lib.lemo_keep_k.restype = i32
+    lib.lemo_keep_k.argtypes = [i32, ctypes.c_double]
+    lib.lemo_kept_count.restype = i64
+    lib.lemo_kept_count.argtypes = [i64, i32, i32]
+    lib.lemo_score_workspace_bytes.restype = ctypes.c_int
+    lib.lemo_score_workspace_bytes.argtypes = [i64, i32, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    lib.lemo_score_segments.restype = ctypes.c_int
+    lib.lemo_score_segments.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, f32, i32, u32,
+                                        vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.lemo_select_topk.restype = ctypes.c_int
+    lib.lemo_select_topk.argtypes = [vp, i64, i32, i32, vp, vp]
+    lib.lemo_gather_gemm.restype = ctypes.c_int
+    lib.lemo_gather_gemm.argtypes = [vp, i64, i64, vp, i64, vp, i64, vp, vp, i64, i32, i32, ctypes.c_int, vp]
+    lib.lemo_scatter_grad.restype = ctypes.c_int
+    lib.lemo_scatter_grad.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, ctypes.c_int, ctypes.c_int, i32, vp]
+    return lib
+
+
+_lib = _load()
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"expected float32 or bfloat16, got {t.dtype}")
+
+
+def _dev(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("tensors must live on the GPU")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise LemoError(rc, what)
+
+
+# --------------------------------------------------------------------------------- host helpers
+
+def lemo_keep_k(L: int, ratio: float) -> int:
+    return int(_lib.lemo_keep_k(L, ratio))
+
+
+def lemo_kept_count(S: int, L: int, k: int) -> int:
+    return int(_lib.lemo_kept_count(S, L, k))
+
+
+def lemo_score_workspace_bytes(S: int, H: int, H_kv: int, d: int, dtype: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.lemo_score_workspace_bytes(S, H, H_kv, d, dtype, ctypes.byref(n)), "lemo_score_workspace_bytes")
+    return int(n.value)
+
+
+# --------------------------------------------------------------------------------- the four calls
+
+def lemo_score_segments(Q: torch.Tensor, K: torch.Tensor, L: int, flags: int = CAUSAL | EXCLUDE_SELF,
+                        scale: float = 0.0, scores: Optional[torch.Tensor] = None,
+                        colsum_per_head: Optional[torch.Tensor] = None, diag_per_head: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Q [S,H,d], K [S,H_kv,d] (last dim contiguous) -> scores [S] float32."""
+    _dev(Q, K, scores, colsum_per_head, diag_per_head, workspace)
+    if Q.dim() != 3 or K.dim() != 3 or Q.stride(2) != 1 or K.stride(2) != 1:
+        raise ValueError("Q must be [S,H,d] and K [S,H_kv,d] with head_dim contiguous")
+    S, H, d = Q.shape
+    if K.shape[0] != S or K.shape[2] != d or _dt(K) != _dt(Q):
+        raise ValueError("Q/K mismatch")
+    Hkv = K.shape[1]
+    if scores is None:
+        scores = torch.empty(S, dtype=torch.float32, device=Q.device)
+    need = lemo_score_workspace_bytes(S, H, Hkv, d, _dt(Q))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    for o, shape in ((scores, (S,)), (colsum_per_head, (H, S)), (diag_per_head, (H, S))):
+        if o is not None and (o.dtype != torch.float32 or tuple(o.shape) != shape or not o.is_contiguous()):
+            raise ValueError("output tensors must be contiguous float32 of shape [S] / [H,S]")
+    _check(_lib.lemo_score_segments(_ptr(Q), _ptr(K), S, H, Hkv, d, _dt(Q), Q.stride(0), Q.stride(1), K.stride(0),
+                                    K.stride(1), float(scale), int(L), int(flags), _ptr(scores), _ptr(colsum_per_head),
+                                    _ptr(diag_per_head), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                    _stream()), "lemo_score_segments")
+    return scores
+
+
+def lemo_select_topk(scores: torch.Tensor, L: int, k: int, kept_idx: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """scores [S] float32 -> kept_idx [M] int32, ascending."""
+    _dev(scores, kept_idx)
+    if scores.dtype != torch.float32 or scores.dim() != 1 or not scores.is_contiguous():
+        raise ValueError("scores must be contiguous float32 [S]")
+    S = scores.shape[0]
+    M = lemo_kept_count(S, L, k)
+    if M < 0:
+        raise LemoError(-2, "lemo_kept_count")
+    if kept_idx is None:
+        kept_idx = torch.empty(M, dtype=torch.int32, device=scores.device)
+    elif kept_idx.dtype != torch.int32 or kept_idx.numel() != M or not kept_idx.is_contiguous():
+        raise ValueError("kept_idx must be contiguous int32 [M]")
+    _check(_lib.lemo_select_topk(_ptr(scores), S, int(L), int(k), _ptr(kept_idx), _stream()), "lemo_select_topk")
+    return kept_idx
+
+
+def lemo_gather_gemm(X: torch.Tensor, kept_idx: Optional[torch.Tensor], W: torch.Tensor,
+                     bias: Optional[torch.Tensor] = None, Y: Optional[torch.Tensor] = None,
+                     M: Optional[int] = None) -> torch.Tensor:
+    """Y[m,:] = X[kept_idx[m],:] @ W.T (+ bias).  X [S,C], W [N,C], rows contiguous."""
+    _dev(X, kept_idx, W, bias, Y)
+    if X.dim() != 2 or W.dim() != 2 or X.stride(1) != 1 or W.stride(1) != 1 or X.shape[1] != W.shape[1] or _dt(X) != _dt(W):
+        raise ValueError("X must be [S,C], W [N,C], same dtype, rows contiguous")
+    S, C = X.shape
+    N = W.shape[0]
+    if kept_idx is not None:
+        if kept_idx.dtype != torch.int32 or kept_idx.dim() != 1 or not kept_idx.is_contiguous():
+            raise ValueError("kept_idx must be contiguous int32 [M]")
+        M = kept_idx.numel() if M is None else M
+    elif M is None:
+        M = S
+    if bias is not None and (bias.dtype != X.dtype or tuple(bias.shape) != (N,) or not bias.is_contiguous()):
+        raise ValueError("bias must be [N] of the input dtype")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    elif Y.dtype != X.dtype or Y.dim() != 2 or Y.shape[0] < M or Y.shape[1] != N or Y.stride(1) != 1:
+        raise ValueError("Y must be [M,N] of the input dtype, rows contiguous")
+    _check(_lib.lemo_gather_gemm(_ptr(X), S, X.stride(0), _ptr(kept_idx), M, _ptr(W), W.stride(0), _ptr(bias), _ptr(Y),
+                                 Y.stride(0) if M > 0 else N, C, N, _dt(X), _stream()), "lemo_gather_gemm")
+    return Y
+
+
+def lemo_scatter_grad(G: torch.Tensor, kept_idx: torch.Tensor, dX: torch.Tensor, mode: int = SCATTER_ACCUMULATE) -> torch.Tensor:
+    """In place: dX[kept_idx[m],:] += G[m,:] (ACCUMULATE) or dX = zero-padded G (ZERO_PAD)."""
+    _dev(G, kept_idx, dX)
+    if G.dim() != 2 or dX.dim() != 2 or G.shape[1] != dX.shape[1] or dX.stride(1) != 1 or (G.shape[0] > 0 and G.stride(1) != 1):
+        raise ValueError("G must be [M,C] and dX [S,C], rows contiguous")
+    if kept_idx.dtype != torch.int32 or kept_idx.dim() != 1 or kept_idx.numel() != G.shape[0] or not kept_idx.is_contiguous():
+        raise ValueError("kept_idx must be contiguous int32 [M]")
+    M, C = G.shape
+    _check(_lib.lemo_scatter_grad(_ptr(G), G.stride(0) if M > 0 else C, _ptr(kept_idx), M, _ptr(dX), dX.stride(0),
+                                  dX.shape[0], C, _dt(G), _dt(dX), int(mode), _stream()), "lemo_scatter_grad")
+    return dX

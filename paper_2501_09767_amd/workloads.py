@@ -7,7 +7,7 @@ HIP path's callers and the CPU oracle's callers use, so that both see the same b
 
 The paper fine-tunes on real text with trained weights (Sec. 6.1); neither is available here, so
 each configuration takes the shapes, dtypes and value distributions of a Llama-shaped layer and
-adds the column structure the paper observes in attention maps (Sec. 3, "grid-like" heavy tokens)
+adds the column structure the paper reports for attention maps (Sec. 3: a few token columns dominate)
 by scaling the keys of a few positions.
 
 Draw order for a configuration (numpy ``default_rng(seed)``): X, Wq, Wk, W, heavy positions or
@@ -164,7 +164,7 @@ def make_layer(cfg: LayerConfig, *, seed: Optional[int] = None, heads: Optional[
         X = _normal(rng, (cfg.S, cfg.C))
         Wq = _normal(rng, (cfg.H * cfg.d, cfg.C), 0.02)
         Wk = _normal(rng, (cfg.H_kv * cfg.d, cfg.C), 0.02)
-        W = _normal(rng, (cfg.N, cfg.C), 0.02) if want_gemm or want_grad else None
+        W = _normal(rng, (cfg.N, cfg.C), 0.02)  # always drawn, so later draws do not depend on want_gemm
         mult = key_multipliers(cfg, rng)
         rows_q = torch.cat([torch.arange(h * cfg.d, (h + 1) * cfg.d) for h in hsel])
         rows_k = torch.cat([torch.arange(g * cfg.d, (g + 1) * cfg.d) for g in kvsel])

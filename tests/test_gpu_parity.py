@@ -1,0 +1,389 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bars: scores |gpu - oracle| <= 2e-3 * |oracle| + 1e-6; kept-index sets bit-exact when
+fed the oracle's own scores, and equal up to swaps inside the 2e-3 band around the cut when fed the
+GPU's scores; gather bit-exact and the GEMM within one bf16 step plus the binary32 accumulation bound; scatter bit-exact.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2501_09767_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 2e-3, 1e-6
+
+
+@pytest.fixture(scope="module")
+def lemo():
+    from paper_2501_09767_amd import lemo as m  # fails loudly if the HIP library is not built
+    return m
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def assert_scores_close(got, want, what=""):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    err = np.abs(got - want)
+    tol = RTOL * np.abs(want) + ATOL
+    bad = np.nonzero(err > tol)[0]
+    assert bad.size == 0, f"{what}: {bad.size} of {want.size} outside tolerance; worst at {bad[:5]}: got {got[bad[:5]]}, want {want[bad[:5]]}"
+    return float((err / (np.abs(want) + 1e-30))[np.abs(want) > 1e-3].max(initial=0.0))
+
+
+def assert_selection_equivalent(kept_gpu, scores_oracle, L, k):
+    """Kept sets from GPU scores may differ from the oracle's only by elements whose ORACLE score lies
+    within the score tolerance of the segment's cut value."""
+    kept_ref = oracle.select_topk(scores_oracle, L, k)
+    assert len(kept_gpu) == len(kept_ref)
+    assert np.all(np.diff(kept_gpu) > 0)
+    S = len(scores_oracle)
+    out = 0
+    nswap = 0
+    for s0 in range(0, S, L):
+        seg = scores_oracle[s0:s0 + L].astype(np.float64)
+        kk = k if len(seg) == L else max(1, min(len(seg), -(-k * len(seg) // L)))
+        a = set(kept_gpu[out:out + kk].tolist())
+        b = set(kept_ref[out:out + kk].tolist())
+        assert all(s0 <= i < s0 + len(seg) for i in a)
+        out += kk
+        if a == b:
+            continue
+        cut = np.sort(seg)[::-1][kk - 1]
+        band = 2 * (RTOL * abs(cut) + ATOL)
+        for i in a ^ b:
+            assert abs(seg[i - s0] - cut) <= band, f"token {i}: oracle score {seg[i - s0]} is not within {band} of the cut {cut}"
+            nswap += 1
+    return nswap
+
+
+def run_score(lemo, Q, K, L, flags, per_head=True, scale=0.0):
+    S, H, _ = Q.shape
+    Qd, Kd = Q.cuda(), K.cuda()
+    col = torch.empty((H, S), dtype=torch.float32, device="cuda") if per_head else None
+    dg = torch.empty((H, S), dtype=torch.float32, device="cuda") if per_head else None
+    s = lemo.lemo_score_segments(Qd, Kd, L, flags=flags, scale=scale, colsum_per_head=col, diag_per_head=dg)
+    torch.cuda.synchronize()
+    return s.cpu().numpy(), (col.cpu().numpy() if per_head else None), (dg.cpu().numpy() if per_head else None)
+
+
+# ------------------------------------------------------------------------------------ scoring
+
+SCORE_CASES = [
+    # S, H, Hkv, d, dtype, L
+    (1, 2, 1, 64, "f32", 8), (2, 2, 2, 128, "bf16", 1), (7, 4, 2, 64, "bf16", 4), (64, 2, 2, 128, "bf16", 64),
+    (129, 3, 3, 64, "f32", 50), (1000, 4, 2, 128, "bf16", 128), (777, 8, 2, 64, "bf16", 300), (600, 2, 1, 128, "f32", 256),
+    (1500, 9, 3, 128, "bf16", 512),
+]
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+@pytest.mark.parametrize("S,H,Hkv,d,dtype,L", SCORE_CASES)
+def test_score_small_shapes(lemo, S, H, Hkv, d, dtype, L, flags):
+    say(f"[score] S={S} H={H}/{Hkv} d={d} {dtype} L={L} flags={flags}")
+    Q, K = wl.tiny_qk(S, H, Hkv, d, dtype, seed=S * 31 + H + flags, heavy=max(1, S // 64))
+    got, col, dg = run_score(lemo, Q, K, L, flags)
+    want, wcol, wdg = oracle.score(wl.as_numpy(Q), wl.as_numpy(K), flags=flags, per_head=True)
+    assert_scores_close(col.ravel(), wcol.ravel(), "colsum_per_head")
+    assert_scores_close(dg.ravel(), wdg.ravel(), "diag_per_head")
+    assert_scores_close(got, want, "scores")
+    # rows of a softmax sum to one: every head's column sums total S (diagonal included)
+    np.testing.assert_allclose(col.astype(np.float64).sum(axis=1), S, rtol=1e-4)
+    if flags == 3:
+        assert got[-1] == 0.0  # last token under causal + exclude-self: its column holds only its own diagonal
+
+
+def test_score_config_C1_fp32(lemo):
+    cfg = wl.CONFIGS["C1"]
+    lay = wl.make_layer(cfg)
+    for flags in (3, 0):
+        say(f"[score] C1 flags={flags}")
+        got, col, _ = run_score(lemo, lay["Q"], lay["K"], cfg.L, flags)
+        want = oracle.score(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), flags=flags)
+        worst = assert_scores_close(got, want, "C1 scores")
+        say(f"    worst relative error {worst:.2e}")
+    # soft sanity: the 16 heavy-key tokens are all kept
+    got, _, _ = run_score(lemo, lay["Q"], lay["K"], cfg.L, 3, per_head=False)
+    kept = lemo.lemo_select_topk(torch.from_numpy(got).cuda(), cfg.L, cfg.k).cpu().numpy()
+    heavy = np.nonzero(lay["mult"].numpy() > 1)[0]
+    assert np.isin(heavy, kept).all()
+
+
+def test_score_independent_of_segment_length_and_deterministic(lemo):
+    Q, K = wl.tiny_qk(1100, 4, 2, 128, "bf16", seed=77, heavy=8)
+    base, _, _ = run_score(lemo, Q, K, 128, 3, per_head=False)
+    again, _, _ = run_score(lemo, Q, K, 128, 3, per_head=False)
+    np.testing.assert_array_equal(base, again)  # no atomics: bitwise repeatable
+    for L in (1, 100, 256, 333, 1024, 5000):
+        say(f"[score] L-independence L={L}")
+        other, _, _ = run_score(lemo, Q, K, L, 3, per_head=False)
+        np.testing.assert_allclose(other, base, rtol=2e-5, atol=1e-7)  # only the fp32 summation order moves
+
+
+def test_score_strided_views_and_scale(lemo):
+    S, H, Hkv, d = 300, 4, 2, 64
+    Q, K = wl.tiny_qk(S, H, Hkv, d, "bf16", seed=5, heavy=4)
+    big = torch.zeros((S, H + 2, d + 64), dtype=torch.bfloat16)
+    big[:, 1:H + 1, 64:] = Q
+    say("[score] strided Q view")
+    Qd = big.cuda()[:, 1:H + 1, 64:]
+    s1 = lemo.lemo_score_segments(Qd, K.cuda(), 128, scale=0.2)
+    s2 = lemo.lemo_score_segments(Q.cuda(), K.cuda(), 128, scale=0.2)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(s1.cpu().numpy(), s2.cpu().numpy())
+    want = oracle.score(wl.as_numpy(Q), wl.as_numpy(K), scale=0.2)
+    assert_scores_close(s2.cpu().numpy(), want, "scale=0.2")
+
+
+def test_score_config_C2_full(lemo):
+    """Llama2-7B-shaped layer, S=4096, all 32 heads, against the full oracle."""
+    cfg = wl.CONFIGS["C2"]
+    lay = wl.make_layer(cfg, want_gemm=False)
+    say("[score] C2 full: GPU")
+    got, col, dg = run_score(lemo, lay["Q"], lay["K"], cfg.L, 3)
+    say("[score] C2 full: oracle")
+    want, wcol, wdg = oracle.score(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), flags=3, per_head=True)
+    worst = assert_scores_close(got, want, "C2 scores")
+    assert_scores_close(col.ravel(), wcol.ravel(), "C2 colsum")
+    say(f"    worst relative error {worst:.2e}")
+    kept = lemo.lemo_select_topk(torch.from_numpy(got).cuda(), cfg.L, cfg.k).cpu().numpy()
+    nswap = assert_selection_equivalent(kept, want, cfg.L, cfg.k)
+    say(f"    kept sets equal up to {nswap} in-band swaps")
+    heavy = np.nonzero(lay["mult"].numpy() > 1)[0]
+    say(f"    heavy-key tokens kept: {int(np.isin(heavy, kept).sum())} of {len(heavy)}")
+
+
+@pytest.mark.parametrize("name,heads", [("C4", [4, 5, 6, 7]), ("C5", [9, 30])])
+def test_score_full_length_head_subset(lemo, name, heads):
+    """Full sequence length of the large configurations on a few heads (the oracle is O(S^2 d) per head):
+    per-head column sums and diagonals against the oracle, plus the sum-to-S invariant."""
+    cfg = wl.CONFIGS[name]
+    say(f"[score] {name} S={cfg.S} heads={heads}: inputs")
+    lay = wl.make_layer(cfg, heads=heads, want_gemm=False, want_grad=False)
+    say(f"[score] {name}: GPU")
+    got, col, dg = run_score(lemo, lay["Q"], lay["K"], cfg.L, 3)
+    np.testing.assert_allclose(col.astype(np.float64).sum(axis=1), cfg.S, rtol=1e-4)
+    say(f"[score] {name}: oracle")
+    want, wcol, wdg = oracle.score(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), flags=3, per_head=True)
+    worst = assert_scores_close(got, want, f"{name} scores")
+    assert_scores_close(col.ravel(), wcol.ravel(), f"{name} colsum")
+    assert_scores_close(dg.ravel(), wdg.ravel(), f"{name} diag")
+    say(f"    worst relative error {worst:.2e}")
+
+
+# ------------------------------------------------------------------------------------ selection
+
+@pytest.mark.parametrize("S,L,k", [(1024, 128, 64), (1000, 128, 64), (7, 4, 3), (1, 8, 8), (8192, 512, 205), (32768, 1024, 308),
+                                   (16384, 1024, 512), (300, 100, 1), (300, 100, 100), (20000, 8192, 3000), (513, 512, 205), (100, 1, 1)])
+def test_select_bit_exact(lemo, S, L, k):
+    say(f"[select] S={S} L={L} k={k}")
+    rng = np.random.default_rng(S + L + k)
+    scores = rng.random(S).astype(np.float32)
+    scores[rng.integers(0, S, S // 3)] = np.float32(0.25)        # many exact ties
+    scores[rng.integers(0, S, max(1, S // 50))] *= np.float32(-1.0)  # some negatives
+    scores[rng.integers(0, S, max(1, S // 100))] = np.float32(-0.0)
+    scores[rng.integers(0, S, max(1, S // 100))] = np.float32(0.0)
+    got = lemo.lemo_select_topk(torch.from_numpy(scores).cuda(), L, k).cpu().numpy()
+    np.testing.assert_array_equal(got, oracle.select_topk(scores, L, k))
+
+
+def test_select_all_equal_and_extremes(lemo):
+    say("[select] ties and extremes")
+    const = torch.full((4096,), 0.5, dtype=torch.float32)
+    got = lemo.lemo_select_topk(const.cuda(), 1024, 300).cpu().numpy()
+    np.testing.assert_array_equal(got, oracle.select_topk(const.numpy(), 1024, 300))
+    ext = np.array([np.inf, -np.inf, 3.4e38, -3.4e38, 1e-45, -1e-45, 0.0, -0.0] * 16, dtype=np.float32)
+    for k in (1, 17, 64, 128):
+        got = lemo.lemo_select_topk(torch.from_numpy(ext).cuda(), 128, k).cpu().numpy()
+        np.testing.assert_array_equal(got, oracle.select_topk(ext, 128, k))
+
+
+# ------------------------------------------------------------------------------------ gather-GEMM
+
+def widen(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def assert_gemm_close(got_bits, want_bits, Xrows, W, bias=None):
+    """GPU = RNE_bf16(binary32 accumulation), oracle = RNE_bf16(exact).  The two roundings can land one
+    bf16 step apart, and the binary32 accumulation over C terms adds an error of about
+    sqrt(C) * 2^-24 * sum_c |x_c w_c| (4x that is allowed), which matters only where the terms cancel."""
+    g = widen(got_bits).astype(np.float64)
+    o = widen(want_bits).astype(np.float64)
+    C = Xrows.shape[1]
+    mag = np.abs(widen(Xrows).astype(np.float64)) @ np.abs(widen(W).astype(np.float64)).T
+    if bias is not None:
+        mag = mag + np.abs(widen(bias).astype(np.float64))
+    ulp = np.maximum(np.abs(g), np.abs(o))
+    ulp = np.where(ulp > 0, 2.0 ** (np.floor(np.log2(np.maximum(ulp, 1e-300))) - 7), 0.0)
+    tol = ulp + 2 * 4 * np.sqrt(C) * 2.0 ** -24 * mag
+    bad = np.abs(g - o) > tol
+    assert not bad.any(), f"{bad.sum()} of {bad.size} outputs beyond one bf16 step + accumulation bound"
+    assert (got_bits == want_bits).mean() > 0.98
+
+
+@pytest.mark.parametrize("S,C,N,M,bias", [(300, 64, 40, 130, False), (1000, 256, 300, 517, True), (513, 1000, 257, 513, False),
+                                          (64, 8, 2, 1, True), (700, 4096, 512, 300, False)])
+def test_gather_gemm_bf16(lemo, S, C, N, M, bias):
+    say(f"[gemm] bf16 S={S} C={C} N={N} M={M} bias={bias}")
+    rng = np.random.default_rng(S + C + N)
+    X = torch.from_numpy(rng.standard_normal((S, C)).astype(np.float32)).to(torch.bfloat16)
+    W = torch.from_numpy((rng.standard_normal((N, C)) * 0.02).astype(np.float32)).to(torch.bfloat16)
+    b = torch.from_numpy(rng.standard_normal(N).astype(np.float32)).to(torch.bfloat16) if bias else None
+    idx = np.sort(rng.choice(S, M, replace=False)).astype(np.int32)
+    Xd, Wd, idxd = X.cuda(), W.cuda(), torch.from_numpy(idx).cuda()
+    Y = lemo.lemo_gather_gemm(Xd, idxd, Wd, b.cuda() if bias else None)
+    # the same kernel on a materialised compact copy must give identical bits (the gather is exact)
+    Yc = lemo.lemo_gather_gemm(Xd[idxd.long()].contiguous(), None, Wd, b.cuda() if bias else None)
+    torch.cuda.synchronize()
+    got = wl.to_bf16_bits(Y)
+    np.testing.assert_array_equal(got, wl.to_bf16_bits(Yc))
+    want = oracle.gather_gemm(wl.as_numpy(X), idx, wl.as_numpy(W), wl.as_numpy(b) if bias else None)
+    assert_gemm_close(got, want, wl.as_numpy(X)[idx], wl.as_numpy(W), wl.as_numpy(b) if bias else None)
+
+
+def test_gather_gemm_identity_weight_is_a_bit_exact_gather(lemo):
+    say("[gemm] identity weight")
+    rng = np.random.default_rng(3)
+    S, C, M = 500, 256, 333
+    X = torch.from_numpy(rng.standard_normal((S, C)).astype(np.float32)).to(torch.bfloat16)
+    idx = rng.permutation(S)[:M].astype(np.int32)  # unsorted on purpose: any row order is a valid gather
+    Y = lemo.lemo_gather_gemm(X.cuda(), torch.from_numpy(idx).cuda(), torch.eye(C, dtype=torch.bfloat16).cuda())
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(wl.to_bf16_bits(Y), wl.to_bf16_bits(X)[idx])
+
+
+def test_gather_gemm_fp32_config_C1(lemo):
+    cfg = wl.CONFIGS["C1"]
+    lay = wl.make_layer(cfg)
+    say("[gemm] C1 fp32")
+    s = oracle.score(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]))
+    idx = oracle.select_topk(s, cfg.L, cfg.k)
+    Y = lemo.lemo_gather_gemm(lay["X"].cuda(), torch.from_numpy(idx).cuda(), lay["W"].cuda()).cpu().numpy()
+    want = oracle.gather_gemm(wl.as_numpy(lay["X"]), idx, wl.as_numpy(lay["W"]))
+    np.testing.assert_allclose(Y, want, rtol=1e-5, atol=1e-6)  # fp32 accumulation over C=256 vs fp64
+    # strided output and M == 0
+    Ybig = torch.zeros((cfg.M, cfg.N + 64), dtype=torch.float32, device="cuda")
+    lemo.lemo_gather_gemm(lay["X"].cuda(), torch.from_numpy(idx).cuda(), lay["W"].cuda(), Y=Ybig[:, :cfg.N])
+    np.testing.assert_array_equal(Ybig[:, :cfg.N].cpu().numpy(), Y)
+    assert not Ybig[:, cfg.N:].any()
+    empty = lemo.lemo_gather_gemm(lay["X"].cuda(), torch.empty(0, dtype=torch.int32, device="cuda"), lay["W"].cuda())
+    assert empty.shape == (0, cfg.N)
+
+
+def test_gather_gemm_llama_shape_sampled(lemo):
+    """C3-shaped consumer GEMM (M=3280 kept rows of 8192, C=4096, N=11008): sampled output rows against
+    the oracle, all columns of each sampled row."""
+    cfg = wl.CONFIGS["C3"]
+    say("[gemm] C3 shape: inputs")
+    rng = np.random.default_rng(cfg.seed)
+    X = torch.from_numpy(rng.standard_normal((cfg.S, cfg.C), dtype=np.float32)).to(torch.bfloat16)
+    W = torch.from_numpy(rng.standard_normal((cfg.N, cfg.C), dtype=np.float32) * np.float32(0.02)).to(torch.bfloat16)
+    scores = rng.random(cfg.S).astype(np.float32)
+    idx = oracle.select_topk(scores, cfg.L, cfg.k)
+    assert len(idx) == cfg.M == 3280
+    say("[gemm] C3 shape: GPU")
+    Y = lemo.lemo_gather_gemm(X.cuda(), torch.from_numpy(idx).cuda(), W.cuda())
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, 3071, 3072, 3279], rng.integers(0, cfg.M, 25)]))
+    say(f"[gemm] C3 shape: oracle on {len(rows)} rows")
+    want = oracle.gather_gemm(wl.as_numpy(X), idx[rows], wl.as_numpy(W))
+    assert_gemm_close(wl.to_bf16_bits(Y)[rows], want, wl.as_numpy(X)[idx[rows]], wl.as_numpy(W))
+
+
+# ------------------------------------------------------------------------------------ scatter-add
+
+@pytest.mark.parametrize("gdt,xdt", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32"), ("f32", "bf16")])
+@pytest.mark.parametrize("S,C,M", [(100, 8, 37), (1000, 4096, 400), (513, 264, 513), (50, 64, 0)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_scatter_bit_exact(lemo, S, C, M, gdt, xdt, mode):
+    say(f"[scatter] S={S} C={C} M={M} {gdt}->{xdt} mode={mode}")
+    rng = np.random.default_rng(S + C + M)
+    tg = torch.bfloat16 if gdt == "bf16" else torch.float32
+    tx = torch.bfloat16 if xdt == "bf16" else torch.float32
+    G = torch.from_numpy(rng.standard_normal((M, C)).astype(np.float32)).to(tg)
+    D = torch.from_numpy(rng.standard_normal((S, C)).astype(np.float32)).to(tx)
+    idx = np.sort(rng.choice(S, M, replace=False)).astype(np.int32)
+    Dd = D.cuda()
+    lemo.lemo_scatter_grad(G.cuda(), torch.from_numpy(idx).cuda(), Dd, mode=mode)
+    torch.cuda.synchronize()
+    want = wl.as_numpy(D).copy()
+    oracle.scatter_add(wl.as_numpy(G), idx, want, mode=mode)
+    np.testing.assert_array_equal(wl.as_numpy(Dd), want)
+
+
+def test_scatter_unsorted_indices_and_strided_rows(lemo):
+    say("[scatter] unsorted indices, padded leading dimension")
+    rng = np.random.default_rng(12)
+    S, C, M = 400, 128, 150
+    G = torch.from_numpy(rng.standard_normal((M, C)).astype(np.float32)).to(torch.bfloat16)
+    D = torch.from_numpy(rng.standard_normal((S, C + 32)).astype(np.float32)).to(torch.bfloat16)
+    idx = rng.permutation(S)[:M].astype(np.int32)
+    Dd = D.cuda()
+    lemo.lemo_scatter_grad(G.cuda(), torch.from_numpy(idx).cuda(), Dd[:, :C])
+    torch.cuda.synchronize()
+    want = np.ascontiguousarray(wl.as_numpy(D)[:, :C])
+    oracle.scatter_add(wl.as_numpy(G), idx, want)
+    got = wl.as_numpy(Dd)
+    np.testing.assert_array_equal(got[:, :C], want)
+    np.testing.assert_array_equal(got[:, C:], wl.as_numpy(D)[:, C:])  # the padding columns are not touched
+
+
+def test_scatter_config_C3_backward(lemo):
+    """C3's backward: G ~ N(0,1) [3280,4096] bf16 scatter-added into a zero buffer and into a residual."""
+    cfg = wl.CONFIGS["C3"]
+    say("[scatter] C3 backward")
+    rng = np.random.default_rng(cfg.seed)
+    G = torch.from_numpy(rng.standard_normal((cfg.M, cfg.C), dtype=np.float32)).to(torch.bfloat16)
+    R = torch.from_numpy(rng.standard_normal((cfg.S, cfg.C), dtype=np.float32)).to(torch.bfloat16)
+    idx = oracle.select_topk(rng.random(cfg.S).astype(np.float32), cfg.L, cfg.k)
+    idxd = torch.from_numpy(idx).cuda()
+    for init in (torch.zeros_like(R), R):
+        Dd = init.cuda()
+        lemo.lemo_scatter_grad(G.cuda(), idxd, Dd)
+        Dd2 = init.cuda()
+        lemo.lemo_scatter_grad(G.cuda(), idxd, Dd2)
+        torch.cuda.synchronize()
+        want = wl.as_numpy(init).copy()
+        oracle.scatter_add(wl.as_numpy(G), idx, want)
+        np.testing.assert_array_equal(wl.as_numpy(Dd), want)
+        assert torch.equal(Dd, Dd2)
+    # gather(scatter(G)) on a zero buffer returns G (via an identity-weight-free check: plain row read)
+    Z = torch.zeros_like(R).cuda()
+    lemo.lemo_scatter_grad(G.cuda(), idxd, Z, mode=1)
+    assert torch.equal(Z[idxd.long()].cpu(), G)
+
+
+# ------------------------------------------------------------------------------------ whole path
+
+def test_whole_path_small_layer(lemo):
+    """score -> select -> gather-GEMM -> scatter on a small bf16 layer, each stage against the oracle fed
+    with the oracle's own upstream result."""
+    cfg = wl.scaled(wl.CONFIGS["C2"], S=1536, H=8, H_kv=8, C=512, N=768, L=512, ratio=0.4, backward=True)
+    say("[path] small layer")
+    lay = wl.make_layer(cfg)
+    Q, K, X, W, G = (lay[n].cuda() for n in ("Q", "K", "X", "W", "G"))
+    scores = lemo.lemo_score_segments(Q, K, cfg.L)
+    kept = lemo.lemo_select_topk(scores, cfg.L, cfg.k)
+    Y = lemo.lemo_gather_gemm(X, kept, W)
+    dX = torch.zeros_like(X)
+    lemo.lemo_scatter_grad(G, kept, dX)
+    torch.cuda.synchronize()
+    o_scores = oracle.score(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]))
+    assert_scores_close(scores.cpu().numpy(), o_scores, "path scores")
+    kept_np = kept.cpu().numpy()
+    assert_selection_equivalent(kept_np, o_scores, cfg.L, cfg.k)
+    # downstream stages are compared on the GPU's own kept set (it is valid by the check above)
+    assert_gemm_close(wl.to_bf16_bits(Y), oracle.gather_gemm(wl.as_numpy(lay["X"]), kept_np, wl.as_numpy(lay["W"])),
+                      wl.as_numpy(lay["X"])[kept_np], wl.as_numpy(lay["W"]))
+    want = np.zeros((cfg.S, cfg.C), dtype=np.uint16)
+    oracle.scatter_add(wl.as_numpy(lay["G"]), kept_np, want)
+    np.testing.assert_array_equal(wl.as_numpy(dX), want)
