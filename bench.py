@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Benchmark of the Contextual Token Sparsity hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic layer, through the C ABI:
+    lemo_score_rowstats -> lemo_score_colsums -> lemo_score_head_mean   (= lemo_score_segments)
+    -> lemo_select_topk -> lemo_gather_gemm -> lemo_scatter_grad (when the configuration has a backward)
+with every input already resident in HBM.  HIP events recorded between the calls, on the stream the
+kernels run on, give each kernel's share of the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--no-cpu-baseline]
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+
+
+class HipEvents:
+    """hipEvent_t handles created straight from the HIP runtime, recorded on a given stream."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        e = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(e))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+        return e
+
+    def record(self, e, stream):
+        rc = self.hip.hipEventRecord(e, ctypes.c_void_p(stream))
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord failed: {rc}")
+
+    def elapsed_ms(self, a, b) -> float:
+        self.hip.hipEventSynchronize(b)
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+
+def algorithmic_work(cfg):
+    """Work the method must do per launch (not what an implementation happens to move)."""
+    S, H, d, C, N, M = cfg.S, cfg.H, cfg.d, cfg.C, cfg.N, cfg.M
+    esz = 2 if cfg.dtype == "bf16" else 4
+    pairs = H * S * (S + 1) // 2          # causal: allowed (query, key) pairs over all heads
+    return {
+        "rowstats": {"flops": 2.0 * d * pairs},
+        "colsum": {"flops": 2.0 * d * pairs},
+        "head_mean": {"bytes": 2.0 * H * S * 4 + S * 4},
+        "select": {"bytes": S * 4.0 + M * 4.0},
+        "gather_gemm": {"flops": 2.0 * M * C * N, "bytes": (M * C + N * C + M * N) * float(esz)},
+        "scatter": {"bytes": 3.0 * M * C * esz + 4.0 * M},
+    }
+
+
+def cpu_baseline(cfg, lay, wl, steps_note=""):
+    """The oracle, as it stands, timed on this host on a bounded sample of the same workload."""
+    import numpy as np
+
+    import oracle
+    group = cfg.H // cfg.H_kv
+    S1 = min(cfg.S, 8192)                                   # queries [0, S1): under the causal mask they only see keys < S1
+    H1 = max(group, min(cfg.H, 16) // group * group)        # a few whole GQA groups
+    Q = wl.as_numpy(lay["Q"][:S1, :H1].cpu())
+    K = wl.as_numpy(lay["K"][:S1, :max(1, H1 // group)].cpu())
+    t0 = time.perf_counter()
+    sc = oracle.score(Q, K, flags=oracle.CAUSAL | oracle.EXCLUDE_SELF)
+    t_score_s = time.perf_counter() - t0
+    frac = (H1 * S1 * (S1 + 1)) / (cfg.H * cfg.S * (cfg.S + 1))
+    t_score = t_score_s / frac
+    scores_full = np.resize(sc, cfg.S).astype(np.float32)   # any scores do for timing the selection
+    t0 = time.perf_counter()
+    kept = oracle.select_topk(scores_full, cfg.L, cfg.k)
+    t_select = time.perf_counter() - t0
+    M1 = 48
+    X = wl.as_numpy(lay["X"].cpu())
+    W = wl.as_numpy(lay["W"].cpu())
+    t0 = time.perf_counter()
+    oracle.gather_gemm(X, kept[:M1], W)
+    t_gemm = (time.perf_counter() - t0) * (len(kept) / M1)
+    t_scatter = 0.0
+    if cfg.backward:
+        G = wl.as_numpy(lay["G"].cpu())
+        dX = np.zeros((cfg.S, cfg.C), dtype=G.dtype)
+        t0 = time.perf_counter()
+        oracle.scatter_add(G, kept, dX)
+        t_scatter = time.perf_counter() - t0
+    total = t_score + t_select + t_gemm + t_scatter
+    return {
+        "value": cfg.S / total, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": (f"score: queries [0,{S1}) x {H1} of {cfg.H} heads = {frac:.4f} of the causal pairs, {t_score_s:.2f} s, scaled by 1/fraction; "
+                   f"select: all {cfg.S} tokens; gather-GEMM: {M1} of {len(kept)} kept rows, scaled; "
+                   f"scatter: all {len(kept)} rows" + ("" if cfg.backward else " (not in this configuration)")),
+        "est_seconds_per_step": total,
+        "seconds": {"score": t_score, "select": t_select, "gather_gemm": t_gemm, "scatter": t_scatter},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C5", help="C1..C5 (default C5: S=32768 Llama2-7B-shaped layer with backward scatter)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (torch copy_) so that a counter profile of this command "
+                         "contains a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU (the path has no cross-GPU step; see DESIGN.md 'Sharding'); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2501_09767_amd import lemo, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    cfg = wl.CONFIGS[args.config]
+    flags = lemo.CAUSAL | lemo.EXCLUDE_SELF
+    print(f"[bench] building synthetic layer {cfg.name}: S={cfg.S} H={cfg.H}/{cfg.H_kv} d={cfg.d} C={cfg.C} N={cfg.N} "
+          f"L={cfg.L} k={cfg.k} M={cfg.M} {cfg.dtype}", file=sys.stderr, flush=True)
+    lay = wl.make_layer(cfg, device="cuda")
+    Q, K, X, W, G = lay["Q"], lay["K"], lay["X"], lay["W"], lay.get("G")
+    dev = Q.device
+    S, H = cfg.S, cfg.H
+    lse2 = torch.empty((H, S), dtype=torch.float32, device=dev)
+    col = torch.empty((H, S), dtype=torch.float32, device=dev)
+    dg = torch.empty((H, S), dtype=torch.float32, device=dev)
+    scores = torch.empty(S, dtype=torch.float32, device=dev)
+    kept = torch.empty(cfg.M, dtype=torch.int32, device=dev)
+    Y = torch.empty((cfg.M, cfg.N), dtype=X.dtype, device=dev)
+    dX = torch.zeros((S, cfg.C), dtype=X.dtype, device=dev)
+    do_scatter = cfg.backward
+
+    phases = ["rowstats", "colsum", "head_mean", "select", "gather_gemm"] + (["scatter"] if do_scatter else [])
+    ev = HipEvents()
+    stream = torch.cuda.current_stream().cuda_stream
+    marks = [[ev.create() for _ in range(len(phases) + 1)] for _ in range(args.steps)]
+
+    def step(m=None):
+        if m: ev.record(m[0], stream)
+        lemo.lemo_score_rowstats(Q, K, flags=flags, lse2=lse2)
+        if m: ev.record(m[1], stream)
+        lemo.lemo_score_colsums(Q, K, cfg.L, lse2, flags=flags, colsum_per_head=col, diag_per_head=dg)
+        if m: ev.record(m[2], stream)
+        lemo.lemo_score_head_mean(col, dg, flags=flags, scores=scores)
+        if m: ev.record(m[3], stream)
+        lemo.lemo_select_topk(scores, cfg.L, cfg.k, kept_idx=kept)
+        if m: ev.record(m[4], stream)
+        lemo.lemo_gather_gemm(X, kept, W, Y=Y)
+        if m: ev.record(m[5], stream)
+        if do_scatter:
+            lemo.lemo_scatter_grad(G, kept, dX)
+            ev.record(m[6], stream) if m else None
+
+    if args.copy_calibration:
+        a = torch.ones(1 << 29, dtype=torch.bfloat16, device=dev)  # 1 GiB read + 1 GiB written per copy
+        b = torch.empty_like(a)
+        for _ in range(2):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(marks[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    work = algorithmic_work(cfg)
+    phase_ms = {}
+    for pi, name in enumerate(phases):
+        phase_ms[name] = sum(ev.elapsed_ms(marks[i][pi], marks[i][pi + 1]) for i in range(args.steps)) / args.steps
+    peak_tflops = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS
+    report = {}
+    for name in phases:
+        ms = phase_ms[name]
+        w = work[name]
+        r = {"ms": round(ms, 5)}
+        if "flops" in w:
+            r["tflops"] = round(w["flops"] / (ms * 1e-3) * 1e-12, 2)
+            r["frac_mfma_peak"] = round(r["tflops"] / peak_tflops, 4)
+        if "bytes" in w:
+            r["gbs"] = round(w["bytes"] / (ms * 1e-3) * 1e-9, 2)
+            r["frac_hbm_peak"] = round(r["gbs"] / PEAK_HBM_GBS, 5)
+        report[name] = r
+
+    dominant = max(phases, key=lambda n: phase_ms[n])
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(f"{cfg.name}:{dominant}")
+    if "flops" in work[dominant]:
+        roof = {"bound": "mfma", "kernel": dominant, "achieved": report[dominant]["tflops"], "peak": peak_tflops,
+                "unit": "TFLOP/s", "frac": round(report[dominant]["tflops"] / peak_tflops, 4), "traffic": traffic}
+    else:
+        roof = {"bound": "hbm", "kernel": dominant, "achieved": report[dominant]["gbs"], "peak": PEAK_HBM_GBS,
+                "unit": "GB/s", "frac": round(report[dominant]["gbs"] / PEAK_HBM_GBS, 4), "traffic": traffic}
+
+    out = {
+        "metric": "tokens scored+selected+gathered/sec per layer",
+        "value": round(S / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: one Llama-shaped layer, S={S}, {cfg.H}x{cfg.d} heads ({cfg.H_kv} KV), hidden {cfg.C}, "
+                               f"consumer GEMM {cfg.C}->{cfg.N}, segment {cfg.L}, keep ratio {cfg.ratio} (k={cfg.k}, M={cfg.M}), causal, "
+                               f"self term excluded" + (", backward scatter-add included" if do_scatter else ""),
+                   "S": S, "H": cfg.H, "H_kv": cfg.H_kv, "d": cfg.d, "C": cfg.C, "N": cfg.N, "L": cfg.L, "k": cfg.k, "M": cfg.M},
+        "roofline": roof,
+        "phases": report,
+    }
+    if not args.no_cpu_baseline:
+        print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
+        out["cpu_baseline"] = cpu_baseline(cfg, lay, wl)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

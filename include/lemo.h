@@ -108,6 +108,29 @@ int lemo_score_segments(const void* Q, const void* K, int64_t S, int32_t H, int3
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The three steps lemo_score_segments runs back to back, callable one at a time (same kernels, same
+ * bits) so that each can be timed or reused.  Arguments mean what they mean above.
+ *
+ *   lemo_score_rowstats   sweep 1: lse2[h][i] = log2 sum_j 2^(c * <Q_i^h, K_j^g(h)>) over the keys query i
+ *                         may attend, c = scale * log2(e)            -> lse2 [H, S] float, out
+ *   lemo_score_colsums    sweep 2: colsum^h[j], diag^h[j] from Q, K and lse2 (read-only, [H, S]);
+ *                         both outputs are required here             -> [H, S] float each, out
+ *   lemo_score_head_mean  scores[j] = (1/H) sum_h (colsum - [EXCLUDE_SELF] diag), heads added in
+ *                         ascending order                            -> scores [S] float, out
+ */
+int lemo_score_rowstats(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d,
+                        lemo_dtype_t dt, int64_t q_tok_stride, int64_t q_head_stride,
+                        int64_t k_tok_stride, int64_t k_head_stride, float scale, uint32_t flags,
+                        float* lse2, void* stream);
+int lemo_score_colsums(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d,
+                       lemo_dtype_t dt, int64_t q_tok_stride, int64_t q_head_stride,
+                       int64_t k_tok_stride, int64_t k_head_stride, float scale, int32_t L,
+                       uint32_t flags, const float* lse2, float* colsum_per_head, float* diag_per_head,
+                       void* stream);
+int lemo_score_head_mean(const float* colsum_per_head, const float* diag_per_head, int64_t S, int32_t H,
+                         uint32_t flags, float* scores, void* stream);
+
+/*
  * Per-segment top-k (the token-block elimination step of Sec. 4.2 with the threshold replaced by a
  * keep count).  For each segment [n*L, min((n+1)*L, S)) keep the k tokens of highest score -- a
  * ragged last segment of length t keeps ceil(k*t/L), at least 1 -- breaking ties towards the LOWER

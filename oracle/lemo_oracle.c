@@ -345,5 +345,8 @@ int oracle_scatter_add(const void* G, int64_t ldg, const int32_t* idx, int64_t M
     return ORACLE_OK;
 }
 
+/* threads the scoring and GEMM loops will use (for reporting beside timings) */
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+
 /* exposed so tests can pin the bf16 rounding routine against an independent implementation */
 uint16_t oracle_double_to_bf16_bits(double x) { return double_to_bf16_bits(x); }

@@ -53,6 +53,8 @@ def _load():
             lib.oracle_gather_gemm.argtypes = [vp, i64, i64, vp, i64, vp, i64, vp, vp, i64, i32, i32, ctypes.c_int]
             lib.oracle_scatter_add.restype = ctypes.c_int
             lib.oracle_scatter_add.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+            lib.oracle_num_threads.restype = ctypes.c_int
+            lib.oracle_num_threads.argtypes = []
             lib.oracle_double_to_bf16_bits.restype = ctypes.c_uint16
             lib.oracle_double_to_bf16_bits.argtypes = [dbl]
             _lib = lib
@@ -99,6 +101,11 @@ def double_to_bf16_bits(x: float) -> int:
 
 
 # ------------------------------------------------------------------ the four operations
+
+def num_threads() -> int:
+    """OpenMP threads the oracle's parallel loops use."""
+    return int(_load().oracle_num_threads())
+
 
 def keep_k(L: int, ratio: float) -> int:
     return int(_load().oracle_keep_k(L, ratio))

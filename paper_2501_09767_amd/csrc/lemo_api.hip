@@ -64,44 +64,100 @@ int lemo_score_workspace_bytes(int64_t S, int32_t H, int32_t H_kv, int32_t d, le
     return LEMO_OK;
 }
 
-int lemo_score_segments(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt,
-                        int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
-                        float scale, int32_t L, uint32_t flags, float* scores, float* colsum_per_head,
-                        float* diag_per_head, void* workspace, size_t workspace_bytes, void* stream) {
-    if (!Q || !K || !scores || !workspace) return LEMO_ERR_NULL;
+// shared validation of the Q/K description; fills the shape part of the parameter block
+static int check_qk(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt,
+                    int64_t q_ts, int64_t q_hs, int64_t k_ts, int64_t k_hs, float scale, uint32_t flags, ScoreParams& p) {
+    if (!Q || !K) return LEMO_ERR_NULL;
     size_t need = 0;
     const int rc = lemo_score_workspace_bytes(S, H, H_kv, d, dt, &need);
     if (rc != LEMO_OK) return rc;
-    if (L <= 0 || (flags & ~(uint32_t)(LEMO_CAUSAL | LEMO_EXCLUDE_SELF))) return LEMO_ERR_SHAPE;
-    if (q_tok_stride < 0 || q_head_stride < 0 || k_tok_stride < 0 || k_head_stride < 0) return LEMO_ERR_SHAPE;
-    if (!std::isfinite(scale)) return LEMO_ERR_SHAPE;
+    if (flags & ~(uint32_t)(LEMO_CAUSAL | LEMO_EXCLUDE_SELF)) return LEMO_ERR_SHAPE;
+    if (q_ts < 0 || q_hs < 0 || k_ts < 0 || k_hs < 0 || !std::isfinite(scale)) return LEMO_ERR_SHAPE;
     const int e16 = elems_per_16B(dt);
-    if (!aligned16(Q) || !aligned16(K) || q_tok_stride % e16 || q_head_stride % e16 || k_tok_stride % e16 || k_head_stride % e16)
-        return LEMO_ERR_ALIGN;
-    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return LEMO_ERR_ALIGN;
-    if (workspace_bytes < need) return LEMO_ERR_WORKSPACE;
-
-    const size_t plane = need / 3;
-    char* ws = static_cast<char*>(workspace);
-    ScoreParams p{};
+    if (!aligned16(Q) || !aligned16(K) || q_ts % e16 || q_hs % e16 || k_ts % e16 || k_hs % e16) return LEMO_ERR_ALIGN;
+    p = ScoreParams{};
     p.Q = Q;
     p.K = K;
     p.S = (int)S;
     p.H = H;
     p.H_kv = H_kv;
-    p.q_ts = q_tok_stride;
-    p.q_hs = q_head_stride;
-    p.k_ts = k_tok_stride;
-    p.k_hs = k_head_stride;
+    p.q_ts = q_ts;
+    p.q_hs = q_hs;
+    p.k_ts = k_ts;
+    p.k_hs = k_hs;
     const double sc = scale > 0.f ? (double)scale : 1.0 / std::sqrt((double)d);
     p.c2 = (float)(sc * 1.4426950408889634);  // log2(e): probabilities are formed with exp2
-    p.L = L;
+    p.L = 1;
     p.flags = flags;
+    return LEMO_OK;
+}
+
+static inline int hip_rc(int e) { return e == 0 ? LEMO_OK : LEMO_ERR_HIP; }
+
+int lemo_score_rowstats(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt,
+                        int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                        float scale, uint32_t flags, float* lse2, void* stream) {
+    ScoreParams p;
+    const int rc = check_qk(Q, K, S, H, H_kv, d, dt, q_tok_stride, q_head_stride, k_tok_stride, k_head_stride, scale, flags, p);
+    if (rc != LEMO_OK) return rc;
+    if (!lse2) return LEMO_ERR_NULL;
+    p.lse2 = lse2;
+    return hip_rc(launch_score(p, dt, d, 1, static_cast<hipStream_t>(stream)));
+}
+
+int lemo_score_colsums(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt,
+                       int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                       float scale, int32_t L, uint32_t flags, const float* lse2, float* colsum_per_head,
+                       float* diag_per_head, void* stream) {
+    ScoreParams p;
+    const int rc = check_qk(Q, K, S, H, H_kv, d, dt, q_tok_stride, q_head_stride, k_tok_stride, k_head_stride, scale, flags, p);
+    if (rc != LEMO_OK) return rc;
+    if (!lse2 || !colsum_per_head || !diag_per_head) return LEMO_ERR_NULL;
+    if (L <= 0) return LEMO_ERR_SHAPE;
+    p.L = L;
+    p.lse2 = const_cast<float*>(lse2);
+    p.colsum = colsum_per_head;
+    p.diag = diag_per_head;
+    return hip_rc(launch_score(p, dt, d, 2, static_cast<hipStream_t>(stream)));
+}
+
+int lemo_score_head_mean(const float* colsum_per_head, const float* diag_per_head, int64_t S, int32_t H, uint32_t flags,
+                         float* scores, void* stream) {
+    if (!colsum_per_head || !diag_per_head || !scores) return LEMO_ERR_NULL;
+    if (S <= 0 || S >= (int64_t)1 << 31 || H <= 0 || (flags & ~(uint32_t)(LEMO_CAUSAL | LEMO_EXCLUDE_SELF))) return LEMO_ERR_SHAPE;
+    ScoreParams p{};
+    p.S = (int)S;
+    p.H = H;
+    p.H_kv = H;
+    p.L = 1;
+    p.flags = flags;
+    p.colsum = const_cast<float*>(colsum_per_head);
+    p.diag = const_cast<float*>(diag_per_head);
+    p.scores = scores;
+    return hip_rc(launch_score(p, LEMO_F32, 64, 4, static_cast<hipStream_t>(stream)));
+}
+
+int lemo_score_segments(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt,
+                        int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                        float scale, int32_t L, uint32_t flags, float* scores, float* colsum_per_head,
+                        float* diag_per_head, void* workspace, size_t workspace_bytes, void* stream) {
+    ScoreParams p;
+    const int rc = check_qk(Q, K, S, H, H_kv, d, dt, q_tok_stride, q_head_stride, k_tok_stride, k_head_stride, scale, flags, p);
+    if (rc != LEMO_OK) return rc;
+    if (!scores || !workspace) return LEMO_ERR_NULL;
+    if (L <= 0) return LEMO_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return LEMO_ERR_ALIGN;
+    size_t need = 0;
+    lemo_score_workspace_bytes(S, H, H_kv, d, dt, &need);
+    if (workspace_bytes < need) return LEMO_ERR_WORKSPACE;
+    const size_t plane = need / 3;
+    char* ws = static_cast<char*>(workspace);
+    p.L = L;
     p.lse2 = reinterpret_cast<float*>(ws);
     p.colsum = colsum_per_head ? colsum_per_head : reinterpret_cast<float*>(ws + plane);
     p.diag = diag_per_head ? diag_per_head : reinterpret_cast<float*>(ws + 2 * plane);
     p.scores = scores;
-    return launch_score(p, dt, d, static_cast<hipStream_t>(stream)) == 0 ? LEMO_OK : LEMO_ERR_HIP;
+    return hip_rc(launch_score(p, dt, d, 7, static_cast<hipStream_t>(stream)));  // the three steps, back to back
 }
 
 int lemo_select_topk(const float* scores, int64_t S, int32_t L, int32_t k, int32_t* kept_idx, void* stream) {

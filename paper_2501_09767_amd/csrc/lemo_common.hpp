@@ -71,7 +71,7 @@ struct ScoreParams {
 };
 
 // kernel launchers (defined next to their kernels; return hipError_t as int)
-int launch_score(const ScoreParams& p, lemo_dtype_t dt, int d, hipStream_t st);
+int launch_score(const ScoreParams& p, lemo_dtype_t dt, int d, int which, hipStream_t st);  // which: 1 row stats | 2 column sums | 4 head mean
 int launch_select(const float* scores, int S, int L, int k, int* kept, hipStream_t st);
 int launch_scatter(const void* G, long long ldg, const int* idx, long long M, void* dX, long long lddx, long long S,
                    int C, lemo_dtype_t g_dt, lemo_dtype_t dx_dt, int mode, hipStream_t st);

@@ -319,18 +319,20 @@ __global__ __launch_bounds__(256) void head_mean_kernel(const float* __restrict_
     scores[j] = acc / (float)H;
 }
 
+// which: bit 0 = sweep 1 (row statistics), bit 1 = sweep 2 (column sums), bit 2 = head mean
 template <typename T, int D>
-static int launch_score_t(const ScoreParams& p, hipStream_t st) {
+static int launch_score_t(const ScoreParams& p, int which, hipStream_t st) {
     const unsigned g1 = (unsigned)(NUM_XCD * p.heads_per_xcd * p.n_query_blocks);
     const unsigned g2 = (unsigned)(NUM_XCD * p.heads_per_xcd * p.n_key_blocks);
-    hipLaunchKernelGGL((rowstats_kernel<T, D>), dim3(g1), dim3(SC_THREADS), 0, st, p);
-    hipLaunchKernelGGL((colsum_kernel<T, D>), dim3(g2), dim3(SC_THREADS), 0, st, p);
-    hipLaunchKernelGGL(head_mean_kernel, dim3((p.S + 255) / 256), dim3(256), 0, st, p.colsum, p.diag, p.scores, p.S, p.H,
-                       (p.flags & LEMO_EXCLUDE_SELF) ? 1 : 0);
+    if (which & 1) hipLaunchKernelGGL((rowstats_kernel<T, D>), dim3(g1), dim3(SC_THREADS), 0, st, p);
+    if (which & 2) hipLaunchKernelGGL((colsum_kernel<T, D>), dim3(g2), dim3(SC_THREADS), 0, st, p);
+    if (which & 4)
+        hipLaunchKernelGGL(head_mean_kernel, dim3((p.S + 255) / 256), dim3(256), 0, st, p.colsum, p.diag, p.scores, p.S, p.H,
+                           (p.flags & LEMO_EXCLUDE_SELF) ? 1 : 0);
     return (int)hipGetLastError();
 }
 
-int launch_score(const ScoreParams& p_in, lemo_dtype_t dt, int d, hipStream_t st) {
+int launch_score(const ScoreParams& p_in, lemo_dtype_t dt, int d, int which, hipStream_t st) {
     ScoreParams p = p_in;
     p.heads_per_xcd = (p.H + NUM_XCD - 1) / NUM_XCD;
     p.n_query_blocks = (p.S + SC_BLOCK - 1) / SC_BLOCK;
@@ -343,10 +345,11 @@ int launch_score(const ScoreParams& p_in, lemo_dtype_t dt, int d, hipStream_t st
     p.blocks_per_seg = (int)((Leff + SC_BLOCK - 1) / SC_BLOCK);
     const long long nseg = ((long long)p.S + Leff - 1) / Leff;
     p.n_key_blocks = (int)(nseg * p.blocks_per_seg);
-    if (dt == LEMO_BF16 && d == 128) return launch_score_t<bf16_t, 128>(p, st);
-    if (dt == LEMO_BF16 && d == 64) return launch_score_t<bf16_t, 64>(p, st);
-    if (dt == LEMO_F32 && d == 128) return launch_score_t<float, 128>(p, st);
-    if (dt == LEMO_F32 && d == 64) return launch_score_t<float, 64>(p, st);
+    if (which == 4) return launch_score_t<float, 64>(p, which, st);  // the head mean has no dtype
+    if (dt == LEMO_BF16 && d == 128) return launch_score_t<bf16_t, 128>(p, which, st);
+    if (dt == LEMO_BF16 && d == 64) return launch_score_t<bf16_t, 64>(p, which, st);
+    if (dt == LEMO_F32 && d == 128) return launch_score_t<float, 128>(p, which, st);
+    if (dt == LEMO_F32 && d == 64) return launch_score_t<float, 64>(p, which, st);
     return (int)hipErrorInvalidValue;
 }
 

@@ -21,7 +21,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblemo_hip.so")
 
 EXPORTS = ("lemo_strerror", "lemo_keep_k", "lemo_kept_count", "lemo_score_workspace_bytes",
-           "lemo_score_segments", "lemo_select_topk", "lemo_gather_gemm", "lemo_scatter_grad")
+           "lemo_score_segments", "lemo_score_rowstats", "lemo_score_colsums", "lemo_score_head_mean",
+           "lemo_select_topk", "lemo_gather_gemm", "lemo_scatter_grad")
 
 
 class LemoError(RuntimeError):
@@ -47,6 +48,12 @@ def _load() -> ctypes.CDLL:
     lib.lemo_score_segments.restype = ctypes.c_int
     lib.lemo_score_segments.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, f32, i32, u32,
                                         vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.lemo_score_rowstats.restype = ctypes.c_int
+    lib.lemo_score_rowstats.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, f32, u32, vp, vp]
+    lib.lemo_score_colsums.restype = ctypes.c_int
+    lib.lemo_score_colsums.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, f32, i32, u32, vp, vp, vp, vp]
+    lib.lemo_score_head_mean.restype = ctypes.c_int
+    lib.lemo_score_head_mean.argtypes = [vp, vp, i64, i32, u32, vp, vp]
     lib.lemo_select_topk.restype = ctypes.c_int
     lib.lemo_select_topk.argtypes = [vp, i64, i32, i32, vp, vp]
     lib.lemo_gather_gemm.restype = ctypes.c_int
@@ -128,6 +135,61 @@ def lemo_score_segments(Q: torch.Tensor, K: torch.Tensor, L: int, flags: int = C
                                     K.stride(1), float(scale), int(L), int(flags), _ptr(scores), _ptr(colsum_per_head),
                                     _ptr(diag_per_head), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                     _stream()), "lemo_score_segments")
+    return scores
+
+
+def _qk_args(Q: torch.Tensor, K: torch.Tensor):
+    _dev(Q, K)
+    if Q.dim() != 3 or K.dim() != 3 or Q.stride(2) != 1 or K.stride(2) != 1:
+        raise ValueError("Q must be [S,H,d] and K [S,H_kv,d] with head_dim contiguous")
+    S, H, d = Q.shape
+    if K.shape[0] != S or K.shape[2] != d or _dt(K) != _dt(Q):
+        raise ValueError("Q/K mismatch")
+    return (_ptr(Q), _ptr(K), S, H, K.shape[1], d, _dt(Q), Q.stride(0), Q.stride(1), K.stride(0), K.stride(1))
+
+
+def _plane(t: Optional[torch.Tensor], H: int, S: int, device) -> torch.Tensor:
+    if t is None:
+        return torch.empty((H, S), dtype=torch.float32, device=device)
+    _dev(t)
+    if t.dtype != torch.float32 or tuple(t.shape) != (H, S) or not t.is_contiguous():
+        raise ValueError("per-head planes must be contiguous float32 [H,S]")
+    return t
+
+
+def lemo_score_rowstats(Q: torch.Tensor, K: torch.Tensor, flags: int = CAUSAL | EXCLUDE_SELF, scale: float = 0.0,
+                        lse2: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Sweep 1 of the scoring: base-2 log-sum-exp of every query row -> [H,S] float32."""
+    a = _qk_args(Q, K)
+    lse2 = _plane(lse2, a[3], a[2], Q.device)
+    _check(_lib.lemo_score_rowstats(*a, float(scale), int(flags), _ptr(lse2), _stream()), "lemo_score_rowstats")
+    return lse2
+
+
+def lemo_score_colsums(Q: torch.Tensor, K: torch.Tensor, L: int, lse2: torch.Tensor, flags: int = CAUSAL | EXCLUDE_SELF,
+                       scale: float = 0.0, colsum_per_head: Optional[torch.Tensor] = None,
+                       diag_per_head: Optional[torch.Tensor] = None):
+    """Sweep 2 of the scoring: per-head column sums and diagonal -> two [H,S] float32 tensors."""
+    a = _qk_args(Q, K)
+    lse2 = _plane(lse2, a[3], a[2], Q.device)
+    col = _plane(colsum_per_head, a[3], a[2], Q.device)
+    dg = _plane(diag_per_head, a[3], a[2], Q.device)
+    _check(_lib.lemo_score_colsums(*a, float(scale), int(L), int(flags), _ptr(lse2), _ptr(col), _ptr(dg), _stream()),
+           "lemo_score_colsums")
+    return col, dg
+
+
+def lemo_score_head_mean(colsum_per_head: torch.Tensor, diag_per_head: torch.Tensor, flags: int = CAUSAL | EXCLUDE_SELF,
+                         scores: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Head mean of (column sums - [EXCLUDE_SELF] diagonal) -> scores [S] float32."""
+    H, S = colsum_per_head.shape
+    col = _plane(colsum_per_head, H, S, colsum_per_head.device)
+    dg = _plane(diag_per_head, H, S, colsum_per_head.device)
+    if scores is None:
+        scores = torch.empty(S, dtype=torch.float32, device=col.device)
+    elif scores.dtype != torch.float32 or tuple(scores.shape) != (S,) or not scores.is_contiguous() or not scores.is_cuda:
+        raise ValueError("scores must be contiguous float32 [S] on the GPU")
+    _check(_lib.lemo_score_head_mean(_ptr(col), _ptr(dg), S, H, int(flags), _ptr(scores), _stream()), "lemo_score_head_mean")
     return scores
 
 

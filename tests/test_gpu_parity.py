@@ -143,6 +143,28 @@ def test_score_strided_views_and_scale(lemo):
     assert_scores_close(s2.cpu().numpy(), want, "scale=0.2")
 
 
+def test_score_steps_compose_to_the_full_call(lemo):
+    """lemo_score_rowstats -> lemo_score_colsums -> lemo_score_head_mean is what lemo_score_segments runs."""
+    say("[score] three steps vs one call")
+    Q, K = wl.tiny_qk(900, 6, 2, 128, "bf16", seed=41, heavy=8)
+    Qd, Kd = Q.cuda(), K.cuda()
+    for flags in (3, 0):
+        whole = lemo.lemo_score_segments(Qd, Kd, 256, flags=flags)
+        lse2 = lemo.lemo_score_rowstats(Qd, Kd, flags=flags)
+        col, dg = lemo.lemo_score_colsums(Qd, Kd, 256, lse2, flags=flags)
+        parts = lemo.lemo_score_head_mean(col, dg, flags=flags)
+        torch.cuda.synchronize()
+        assert torch.equal(whole, parts)
+        # lse2 is the base-2 log-sum-exp of each row: check a few rows against numpy
+        q = Q.float().numpy().astype(np.float64)
+        k = K.float().numpy().astype(np.float64)
+        for h, i in ((0, 0), (3, 450), (5, 899)):
+            n = i + 1 if flags & 1 else 900
+            logits = (k[:n, h // 3] @ q[i, h]) / np.sqrt(128.0)
+            want = (logits.max() + np.log(np.exp(logits - logits.max()).sum())) / np.log(2.0)
+            assert abs(float(lse2[h, i]) - want) < 1e-4 * max(1.0, abs(want))
+
+
 def test_score_config_C2_full(lemo):
     """Llama2-7B-shaped layer, S=4096, all 32 heads, against the full oracle."""
     cfg = wl.CONFIGS["C2"]
