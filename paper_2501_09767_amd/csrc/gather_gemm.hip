@@ -72,15 +72,15 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
         b_ptr[i] = n < N ? reinterpret_cast<const char*>(W + (long long)n * ldw) + pcc * 16 : nullptr;
     }
 
-    uint4 pa[GG_NLD], pb[GG_NLD];
+    u32x4 pa[GG_NLD], pb[GG_NLD];
     auto fetch = [&](int kbyte) {
         const bool in_k = kbyte + pcc * 16 + 16 <= cbytes;  // C is a multiple of 16 bytes: a piece is all in or all out
 #pragma unroll
         for (int i = 0; i < GG_NLD; ++i) {
-            pa[i] = make_uint4(0, 0, 0, 0);
-            pb[i] = make_uint4(0, 0, 0, 0);
-            if (in_k && a_ptr[i]) pa[i] = *reinterpret_cast<const uint4*>(a_ptr[i] + kbyte);
-            if (in_k && b_ptr[i]) pb[i] = *reinterpret_cast<const uint4*>(b_ptr[i] + kbyte);
+            pa[i] = u32x4{0u, 0u, 0u, 0u};
+            pb[i] = u32x4{0u, 0u, 0u, 0u};
+            if (in_k && a_ptr[i]) pa[i] = *reinterpret_cast<const u32x4*>(a_ptr[i] + kbyte);
+            if (in_k && b_ptr[i]) pb[i] = *reinterpret_cast<const u32x4*>(b_ptr[i] + kbyte);
         }
     };
     auto stash = [&](int buf) {
@@ -88,8 +88,8 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
         char* sB = sA + GG_BM * GG_STRIDE;
 #pragma unroll
         for (int i = 0; i < GG_NLD; ++i) {
-            *reinterpret_cast<uint4*>(sA + (i * 32 + prow) * GG_STRIDE + pcc * 16) = pa[i];
-            *reinterpret_cast<uint4*>(sB + (i * 32 + prow) * GG_STRIDE + pcc * 16) = pb[i];
+            *reinterpret_cast<u32x4*>(sA + (i * 32 + prow) * GG_STRIDE + pcc * 16) = pa[i];
+            *reinterpret_cast<u32x4*>(sB + (i * 32 + prow) * GG_STRIDE + pcc * 16) = pb[i];
         }
     };
 
@@ -110,11 +110,11 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
         const char* sB = smem + (kt & 1) * GG_STAGE + GG_BM * GG_STRIDE + (wn * 128 + l32) * GG_STRIDE + half * 16;
 #pragma unroll
         for (int c = 0; c < GG_NCH; ++c) {
-            uint4 af[4], bf[4];
+            u32x4 af[4], bf[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const uint4*>(sA + i * 32 * GG_STRIDE + c * 32);
+            for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const u32x4*>(sA + i * 32 * GG_STRIDE + c * 32);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bf[j] = *reinterpret_cast<const uint4*>(sB + j * 32 * GG_STRIDE + c * 32);
+            for (int j = 0; j < 4; ++j) bf[j] = *reinterpret_cast<const u32x4*>(sB + j * 32 * GG_STRIDE + c * 32);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll

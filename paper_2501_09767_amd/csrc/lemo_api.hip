@@ -73,6 +73,7 @@ static int check_qk(const void* Q, const void* K, int64_t S, int32_t H, int32_t 
     if (rc != LEMO_OK) return rc;
     if (flags & ~(uint32_t)(LEMO_CAUSAL | LEMO_EXCLUDE_SELF)) return LEMO_ERR_SHAPE;
     if (q_ts < 0 || q_hs < 0 || k_ts < 0 || k_hs < 0 || !std::isfinite(scale)) return LEMO_ERR_SHAPE;
+    if (q_ts >= (1 << 22) || k_ts >= (1 << 22)) return LEMO_ERR_UNSUPPORTED;  // token pitch must stay below 16 MiB
     const int e16 = elems_per_16B(dt);
     if (!aligned16(Q) || !aligned16(K) || q_ts % e16 || q_hs % e16 || k_ts % e16 || k_hs % e16) return LEMO_ERR_ALIGN;
     p = ScoreParams{};

@@ -11,6 +11,7 @@ namespace lemo {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // one 16-byte piece; a native vector, so copies are plain loads/stores
 
 struct bf16_t { uint16_t bits; };  // storage tag for bfloat16 (upper half of a binary32)
 
@@ -22,12 +23,12 @@ constexpr int NUM_XCD = 8;  // MI355X: 8 accelerator dies, workgroup b is dispat
 // chunk.  bf16: one v_mfma_f32_32x32x16_bf16 (16 elements).  fp32: four v_mfma_f32_32x32x2_f32, step t
 // contracting element t of the lower half with element 4+t of the upper half; A and B use the same
 // assignment, and a dot product does not care in which order its terms are paired off.
-template <typename T> __device__ __forceinline__ void mma_chunk(f32x16& acc, const uint4& a, const uint4& b);
+template <typename T> __device__ __forceinline__ void mma_chunk(f32x16& acc, const u32x4& a, const u32x4& b);
 
-template <> __device__ __forceinline__ void mma_chunk<bf16_t>(f32x16& acc, const uint4& a, const uint4& b) {
+template <> __device__ __forceinline__ void mma_chunk<bf16_t>(f32x16& acc, const u32x4& a, const u32x4& b) {
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
 }
-template <> __device__ __forceinline__ void mma_chunk<float>(f32x16& acc, const uint4& a, const uint4& b) {
+template <> __device__ __forceinline__ void mma_chunk<float>(f32x16& acc, const u32x4& a, const u32x4& b) {
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);

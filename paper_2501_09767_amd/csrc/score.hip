@@ -1,7 +1,7 @@
 // Token informativeness (Sec. 4.2, Eq. 1 with the head mean of Eq. 2) on gfx950.
 //
 // Column sums of softmax(Q K^T) need every row's FINAL normaliser, so Q K^T is swept twice and the
-// S x S matrix is never stored (Sec. 4.3: derived online, memory linear in S):
+// S x S matrix is never stored (memory linear in S, as Sec. 4.3 requires of the scoring kernel):
 //
 //   sweep 1  rowstats_kernel   per (head, 256-query block): keys stream through LDS, the block's
 //                              queries stay in registers; an online max/sum per query gives the
@@ -17,6 +17,13 @@
 // REGISTERS of a lane and the axis being kept runs along LANES: sweep 1 computes K.Q^T (lane = query),
 // sweep 2 computes Q.K^T (lane = key).  Row and column statistics are then plain in-register chains
 // with one cross-lane step at the very end.
+//
+// Per logit the matrix core spends as many cycles (2*d flops) as the vector ALU does on fma + exp2 + add,
+// so the two must run at the same time.  Tiles that need no masking go through a software pipeline:
+// while the MFMA chain of tile n runs, the exp/sum work of tile n-1 (kept in a "carry" accumulator)
+// is issued between the MFMAs; the instruction order is pinned with scheduling-group barriers.
+#include <mutex>
+
 #include "lemo_common.hpp"
 
 namespace lemo {
@@ -31,9 +38,13 @@ template <typename T, int D> struct Geo {
     static constexpr int NCH = ROWB / 32;            // MFMA chunks per row
     static constexpr int CPR = ROWB / 16;            // 16-byte pieces per row
     static constexpr int STRIDE = ROWB + 16;         // LDS row pitch: +16 B so that 16 consecutive rows hit 16 distinct bank groups
-    static constexpr int TILE = ROWB > 256 ? 32 : 64;  // streamed rows per LDS stage
+    static constexpr int TILE = ROWB > 256 ? 64 : 128; // streamed rows per LDS stage (two stages; long enough to hide a global load)
     static constexpr int NSUB = TILE / 32;           // 32-row MFMA subtiles per stage
     static constexpr int NLOAD = TILE * CPR / SC_THREADS;  // 16-byte global loads per thread per stage
+    static constexpr int ROWS_PER_LOAD = SC_THREADS / CPR; // rows covered by one load of the whole workgroup
+    static constexpr int STAGE_BYTES = TILE * STRIDE;
+    static constexpr int LDS_ROWSTATS = 2 * STAGE_BYTES;
+    static constexpr int LDS_COLSUM = 2 * STAGE_BYTES + 2 * TILE * (int)sizeof(float);
     static constexpr int MIN_WG = ROWB > 256 ? 1 : 2;  // workgroups per CU the register budget is set for
     static_assert(TILE * CPR % SC_THREADS == 0, "tile must split evenly over the workgroup");
 };
@@ -50,21 +61,87 @@ __device__ __forceinline__ bool decode_block(int nblk, int heads_per_xcd, int H,
     return h < H;
 }
 
-// 16-byte piece `c` of row `row` of a [rows, heads, D] tensor, zero beyond `nrows`
+// 16 bytes at byte offset `byte_off` of row `row` of a [rows, heads, D] tensor, zero beyond `nrows`
 template <typename T>
-__device__ __forceinline__ uint4 load_piece(const T* base, long long tok_stride, long long head_off, int row, int nrows, int byte_off) {
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (row < nrows) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(base + (long long)row * tok_stride + head_off) + byte_off);
+__device__ __forceinline__ u32x4 load_piece(const T* base, long long tok_stride, long long head_off, int row, int nrows, int byte_off) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (row < nrows) v = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(base + (long long)row * tok_stride + head_off) + byte_off);
     return v;
 }
+
+// Stage loads: thread owns the 16-byte piece (tid % CPR) of rows tid / CPR + i * ROWS_PER_LOAD of the tile
+// that starts at row0.  They go through a buffer descriptor rebuilt per stage (wave-uniform base = first
+// row of the stage, size = bytes up to the end of the last valid row): the address is one per-thread
+// 32-bit offset plus a scalar offset per load, so it costs no vector instructions, and pieces of rows
+// beyond the end of the tensor are returned as zero by the hardware range check instead of being read.
+template <typename G>
+__device__ __forceinline__ void stage_fetch(u32x4 (&pre)[G::NLOAD], const char* head, int row_bytes, int row0, int nrows, int voff) {
+    const long long span = (long long)(nrows - row0 - 1) * row_bytes + G::ROWB;  // bytes from row0 to the end of row nrows-1
+    const int nrec = span <= 0 ? 0 : (span > 0x7fffffffLL ? 0x7fffffff : (int)span);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(head) + (long long)row0 * row_bytes, 0, nrec, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < G::NLOAD; ++i) pre[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, i * G::ROWS_PER_LOAD * row_bytes, 0);
+}
+template <typename G>
+__device__ __forceinline__ void stage_stash(const u32x4 (&pre)[G::NLOAD], char* lds_piece) {
+#pragma unroll
+    for (int i = 0; i < G::NLOAD; ++i) *reinterpret_cast<u32x4*>(lds_piece + i * G::ROWS_PER_LOAD * G::STRIDE) = pre[i];
+}
+
+// The scheduler may not move anything across this point: the source order of the pipeline slots below
+// (a share of the carried tile's vector work, then the next MFMAs) is the order the wave issues them in.
+__device__ __forceinline__ void slot_fence() { __builtin_amdgcn_sched_barrier(0); }
 
 // ------------------------------------------------------------------------------------------------
 // Sweep 1: base-2 log-sum-exp of every query row.
 // ------------------------------------------------------------------------------------------------
+
+// Online softmax update of one query's (m, l) with the 16 logits a lane holds of one tile, cut into NS
+// slices so that it can be issued between the MFMAs of the next tile.  `raw` are unscaled dot products
+// (-inf = masked, or "no tile at all"); everything stays finite-safe when all inputs so far are -inf.
+struct RowStat {
+    float mn, ms, sum0, sum1, corr;
+};
+template <int NS>
+__device__ __forceinline__ void rowstat_slice(int c, const f32x16& raw, float c2, float m, RowStat& st) {
+    if (c == 0) {
+        float t0 = fmaxf(fmaxf(raw[0], raw[1]), raw[2]);  // v_max3_f32
+        float t1 = fmaxf(fmaxf(raw[3], raw[4]), raw[5]);
+        float t2 = fmaxf(fmaxf(raw[6], raw[7]), raw[8]);
+        float t3 = fmaxf(fmaxf(raw[9], raw[10]), raw[11]);
+        float t4 = fmaxf(fmaxf(raw[12], raw[13]), raw[14]);
+        t0 = fmaxf(fmaxf(t0, t1), t2);
+        t3 = fmaxf(fmaxf(t3, t4), raw[15]);
+        st.mn = fmaxf(m, fmaxf(t0, t3) * c2);
+        st.ms = st.mn == -INFINITY ? 0.f : st.mn;  // nothing seen yet: keep the exp2 arguments finite
+        st.corr = __builtin_amdgcn_exp2f(m - st.ms);
+        st.sum0 = 0.f;
+        st.sum1 = 0.f;
+    } else {
+        const int lo = (c - 1) * 16 / (NS - 1), hi = c * 16 / (NS - 1);
+#pragma unroll
+        for (int r = lo; r < hi; ++r) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(raw[r], c2, -st.ms));
+            if (r & 1) st.sum1 += e; else st.sum0 += e;
+        }
+    }
+}
+__device__ __forceinline__ void rowstat_finish(const RowStat& st, float& m, float& l) {
+    l = fmaf(l, st.corr, st.sum0 + st.sum1);
+    m = st.mn;
+}
+// the whole update at once (masked tiles, pipeline drain)
+__device__ __forceinline__ void rowstat_update(const f32x16& raw, float c2, float& m, float& l) {
+    RowStat st;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) rowstat_slice<8>(c, raw, c2, m, st);
+    rowstat_finish(st, m, l);
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kernel(ScoreParams p) {
     using G = Geo<T, D>;
-    __shared__ __attribute__((aligned(16))) char sK[2][G::TILE * G::STRIDE];
+    extern __shared__ __attribute__((aligned(16))) char smem[];
 
     int h, qb;
     if (!decode_block(p.n_query_blocks, p.heads_per_xcd, p.H, h, qb)) return;
@@ -76,11 +153,12 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kern
     const T* Kb = static_cast<const T*>(p.K);
     const long long q_off = (long long)h * p.q_hs, k_off = (long long)g * p.k_hs;
     const int S = p.S;
-    const int q0 = qb * SC_BLOCK;     // first query of the workgroup
+    const float c2 = p.c2;
+    const int q0 = qb * SC_BLOCK;        // first query of the workgroup
     const int qw0 = q0 + wave * SC_RES;  // first query of this wave
 
     // resident operand: this wave's 64 queries as MFMA B fragments
-    uint4 qf[2][G::NCH];
+    u32x4 qf[2][G::NCH];
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
@@ -93,77 +171,99 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kern
     const int q_last = min(q0 + SC_BLOCK, S) - 1;
     const int ntile = (causal ? q_last : S - 1) / G::TILE + 1;
 
-    uint4 pre[G::NLOAD];
-    auto fetch = [&](int t) {
-#pragma unroll
-        for (int i = 0; i < G::NLOAD; ++i) {
-            int piece = i * SC_THREADS + tid, row = piece / G::CPR, cc = piece % G::CPR;
-            pre[i] = load_piece(Kb, p.k_ts, k_off, t * G::TILE + row, S, cc * 16);
-        }
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < G::NLOAD; ++i) {
-            int piece = i * SC_THREADS + tid, row = piece / G::CPR, cc = piece % G::CPR;
-            *reinterpret_cast<uint4*>(&sK[buf][row * G::STRIDE + cc * 16]) = pre[i];
-        }
-    };
+    // staging: thread owns piece (tid % CPR) of rows tid / CPR + i * ROWS_PER_LOAD.  Rows beyond the end
+    // are clamped to the last row: those keys are always masked (or belong to queries that are not stored).
+    const int st_row = tid / G::CPR, st_cc = tid % G::CPR;
+    const char* k_head = reinterpret_cast<const char*>(Kb + k_off);  // wave-uniform
+    const int k_row_bytes = (int)p.k_ts * (int)sizeof(T);           // host guarantees < 2^24
+    const int st_voff = st_row * k_row_bytes + st_cc * 16;
+    const int st_off = st_row * G::STRIDE + st_cc * 16;
+    u32x4 pre[G::NLOAD];
 
-    fetch(0);
-    stash(0);
+    // carry: the last computed tile whose statistics have not been folded in yet (it belongs to query
+    // subtile 1); -inf means "none"
+    f32x16 carry;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) carry[r] = -INFINITY;
+
+    stage_fetch<G>(pre, k_head, k_row_bytes, 0, S, st_voff);
+    stage_stash<G>(pre, smem + st_off);
     for (int t = 0; t < ntile; ++t) {
         __syncthreads();  // stage t is complete; every wave is done reading stage t-1
         const bool more = t + 1 < ntile;
-        if (more) fetch(t + 1);
+        if (more) stage_fetch<G>(pre, k_head, k_row_bytes, (t + 1) * G::TILE, S, st_voff);
         const int k0 = t * G::TILE;
-        // wave-uniform classification of this 64x64 tile against the wave's queries [qw0, qw0+63]
+        // wave-uniform classification of this tile of keys against the wave's queries [qw0, qw0+63]
         const bool skip = causal && k0 > qw0 + SC_RES - 1;  // every key lies after every query
         const bool clean = causal ? (k0 + G::TILE - 1 <= qw0) : (k0 + G::TILE <= S);
-        if (!skip) {
-            const char* sbuf = sK[t & 1];
+        const char* sbuf = smem + (t & 1) * G::STAGE_BYTES;
+        if (clean) {
+            // pipelined: the statistics update of the previous tile is issued slice by slice between the
+            // MFMAs of tile (ks, qt); fragments of the next key subtile are read while the last chain runs
+            u32x4 kf[G::NCH];
+#pragma unroll
+            for (int c = 0; c < G::NCH; ++c) kf[c] = *reinterpret_cast<const u32x4*>(&sbuf[l32 * G::STRIDE + c * 32 + half * 16]);
 #pragma unroll
             for (int ks = 0; ks < G::NSUB; ++ks) {
-                uint4 kf[G::NCH];
+                RowStat st;
+                f32x16 acc0 = {0}, acc1 = {0};
+                slot_fence();
 #pragma unroll
-                for (int c = 0; c < G::NCH; ++c) kf[c] = *reinterpret_cast<const uint4*>(&sbuf[(ks * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                for (int c = 0; c < G::NCH; ++c) {  // tile (ks, 0) while the carried tile (query subtile 1) is folded in
+                    rowstat_slice<G::NCH>(c, carry, c2, m[1], st);
+                    mma_chunk<T>(acc0, kf[c], qf[0][c]);  // acc[key row][query col]
+                    slot_fence();
+                }
+                rowstat_finish(st, m[1], l[1]);
+                u32x4 kn[G::NCH];
+#pragma unroll
+                for (int c = 0; c < G::NCH; ++c) {  // tile (ks, 1) while tile (ks, 0) is folded in
+                    rowstat_slice<G::NCH>(c, acc0, c2, m[0], st);
+                    mma_chunk<T>(acc1, kf[c], qf[1][c]);
+                    if (ks + 1 < G::NSUB) kn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((ks + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                    slot_fence();
+                }
+                rowstat_finish(st, m[0], l[0]);
+                carry = acc1;
+                if (ks + 1 < G::NSUB) {
+#pragma unroll
+                    for (int c = 0; c < G::NCH; ++c) kf[c] = kn[c];
+                }
+            }
+        } else if (!skip) {
+            rowstat_update(carry, c2, m[1], l[1]);  // drain the pipeline before the masked tiles
+#pragma unroll
+            for (int r = 0; r < 16; ++r) carry[r] = -INFINITY;
+#pragma unroll
+            for (int ks = 0; ks < G::NSUB; ++ks) {
+                u32x4 kf[G::NCH];
+#pragma unroll
+                for (int c = 0; c < G::NCH; ++c) kf[c] = *reinterpret_cast<const u32x4*>(&sbuf[(ks * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt) {
+                    // this 32x32 tile: keys [kmin, kmin+31] against queries [qmin, qmin+31] (wave-uniform tests)
+                    const int kmin = k0 + ks * 32, qmin = qw0 + qt * 32;
+                    if (causal && kmin > qmin + 31) continue;  // every key lies after every query
                     f32x16 acc = {0};
 #pragma unroll
-                    for (int c = 0; c < G::NCH; ++c) mma_chunk<T>(acc, kf[c], qf[qt][c]);  // acc[key row][query col]
-                    if (clean) {
-                        float tmax = acc[0];
-#pragma unroll
-                        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, acc[r]);
-                        const float mn = fmaxf(m[qt], tmax * p.c2);
-                        float sum = 0.f;
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], p.c2, -mn));
-                        l[qt] = fmaf(l[qt], __builtin_amdgcn_exp2f(m[qt] - mn), sum);
-                        m[qt] = mn;
-                    } else {
+                    for (int c = 0; c < G::NCH; ++c) mma_chunk<T>(acc, kf[c], qf[qt][c]);
+                    const bool all_allowed = causal ? (kmin + 31 <= qmin) : (kmin + 31 < S);
+                    if (!all_allowed) {
                         // key j may be used by query i iff j <= lim(i): i itself under the causal mask, S-1 otherwise
                         const int lim = causal ? my_q[qt] : S - 1;
-                        float tmax = -INFINITY;
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
-                            const int key = k0 + ks * 32 + acc_row(r, lane);
-                            acc[r] = key <= lim ? acc[r] * p.c2 : -INFINITY;
-                            tmax = fmaxf(tmax, acc[r]);
+                            const int key = kmin + acc_row(r, lane);
+                            acc[r] = key <= lim ? acc[r] : -INFINITY;
                         }
-                        const float mn = fmaxf(m[qt], tmax);
-                        const float ms = mn == -INFINITY ? 0.f : mn;  // nothing seen yet: keep exp2 arguments finite
-                        float sum = 0.f;
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(acc[r] - ms);
-                        l[qt] = fmaf(l[qt], __builtin_amdgcn_exp2f(m[qt] - ms), sum);
-                        m[qt] = mn;
                     }
+                    rowstat_update(acc, c2, m[qt], l[qt]);
                 }
             }
         }
-        if (more) stash((t + 1) & 1);
+        if (more) stage_stash<G>(pre, smem + ((t + 1) & 1) * G::STAGE_BYTES + st_off);
     }
+    rowstat_update(carry, c2, m[1], l[1]);
 
     // the two half-waves hold disjoint key rows of the same queries: merge, then lse2 = m + log2(l)
 #pragma unroll
@@ -179,16 +279,39 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kern
 // ------------------------------------------------------------------------------------------------
 // Sweep 2: column sums (and the diagonal) of the probabilities, one key block per workgroup.
 // ------------------------------------------------------------------------------------------------
+
+// sum over the 16 probabilities a lane holds of one tile, p = exp2(raw * c2 + nl) with nl = -lse2 of the
+// row; slice c of NS covers elements [c*16/NS, (c+1)*16/NS) and adds into two partial sums
+template <int NS>
+__device__ __forceinline__ void colsum_slice(int c, const f32x16& raw, const float (&nl)[16], float c2, float& s0, float& s1) {
+    const int lo = c * 16 / NS, hi = (c + 1) * 16 / NS;
+#pragma unroll
+    for (int r = lo; r < hi; ++r) {
+        const float e = __builtin_amdgcn_exp2f(fmaf(raw[r], c2, nl[r]));
+        if (r & 1) s1 += e; else s0 += e;
+    }
+}
+__device__ __forceinline__ float colsum_tile(const f32x16& raw, const float (&nl)[16], float c2) {
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) colsum_slice<8>(c, raw, nl, c2, s0, s1);
+    return s0 + s1;
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel(ScoreParams p) {
     using G = Geo<T, D>;
-    __shared__ __attribute__((aligned(16))) char sQ[2][G::TILE * G::STRIDE];
-    __shared__ __attribute__((aligned(16))) float sL[2][G::TILE];
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    float* const sLbase = reinterpret_cast<float*>(smem + 2 * G::STAGE_BYTES);
 
+#ifdef LEMO_DEBUG_CLOCK
+    const long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
+#endif
     int h, kb;
     if (!decode_block(p.n_key_blocks, p.heads_per_xcd, p.H, h, kb)) return;
     const bool causal = (p.flags & LEMO_CAUSAL) != 0;
     const int S = p.S;
+    const float c2 = p.c2;
     // key block -> (segment, block inside the segment); blocks never straddle a segment boundary
     const int seg = kb / p.blocks_per_seg, bis = kb - seg * p.blocks_per_seg;
     const long long seg0 = (long long)seg * p.L;
@@ -206,7 +329,7 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
     const int kw0 = key0 + wave * SC_RES;  // first key of this wave
 
     // resident operand: this wave's 64 keys as MFMA B fragments (zero beyond the block's end)
-    uint4 kf[2][G::NCH];
+    u32x4 kf[2][G::NCH];
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -220,78 +343,145 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
     const int t_hi = (S - 1) / G::TILE;
     const int t_lo = causal ? key0 / G::TILE : 0;
 
-    uint4 pre[G::NLOAD];
+    // staging (see sweep 1).  Query rows beyond the end are clamped; their lse2 is +inf, so p = 0.
+    const int st_row = tid / G::CPR, st_cc = tid % G::CPR;
+    const char* q_head = reinterpret_cast<const char*>(Qb + q_off);  // wave-uniform
+    const int q_row_bytes = (int)p.q_ts * (int)sizeof(T);           // host guarantees < 2^24
+    const int st_voff = st_row * q_row_bytes + st_cc * 16;
+    const int st_off = st_row * G::STRIDE + st_cc * 16;
+    u32x4 pre[G::NLOAD];
     float pre_l = 0.f;
-    auto fetch = [&](int t) {
-#pragma unroll
-        for (int i = 0; i < G::NLOAD; ++i) {
-            int piece = i * SC_THREADS + tid, row = piece / G::CPR, cc = piece % G::CPR;
-            pre[i] = load_piece(Qb, p.q_ts, q_off, t * G::TILE + row, S, cc * 16);
-        }
-        if (tid < G::TILE) {
-            int q = t * G::TILE + tid;
-            pre_l = q < S ? lse[q] : INFINITY;  // rows beyond S: exp2(-inf) = 0, they add nothing
-        }
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < G::NLOAD; ++i) {
-            int piece = i * SC_THREADS + tid, row = piece / G::CPR, cc = piece % G::CPR;
-            *reinterpret_cast<uint4*>(&sQ[buf][row * G::STRIDE + cc * 16]) = pre[i];
-        }
-        if (tid < G::TILE) sL[buf][tid] = pre_l;
-    };
+    // row statistics of a stage: thread tid < TILE owns row tid; beyond the end +inf, so that p = exp2(-inf) = 0
+    auto fetch_l = [&](int t) { return tid < G::TILE ? lse[min(t * G::TILE + tid, S - 1)] : 0.f; };
+    auto fix_l = [&](int t, float v) { return t * G::TILE + tid < S ? -v : -INFINITY; };  // stored negated: p = exp2(s*c2 + nl)
 
-    fetch(t_hi);
-    stash(0);
+    // carry: last computed tile not yet summed (always a tile of key subtile 1); nl = -inf means "none"
+    f32x16 carry = {0};
+    float carry_nl[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) carry_nl[r] = -INFINITY;
+
+    stage_fetch<G>(pre, q_head, q_row_bytes, t_hi * G::TILE, S, st_voff);
+    pre_l = fetch_l(t_hi);
+    stage_stash<G>(pre, smem + st_off);
+    if (tid < G::TILE) sLbase[tid] = fix_l(t_hi, pre_l);
     int buf = 0;
     for (int t = t_hi; t >= t_lo; --t, buf ^= 1) {
         __syncthreads();
         const bool more = t > t_lo;
-        if (more) fetch(t - 1);
+        if (more) {
+            stage_fetch<G>(pre, q_head, q_row_bytes, (t - 1) * G::TILE, S, st_voff);
+            pre_l = fetch_l(t - 1);
+        }
         const int i0 = t * G::TILE;
         const bool on_diag = i0 <= kw0 + SC_RES - 1 && i0 + G::TILE - 1 >= kw0;  // tile meets the diagonal band of this wave
         const bool skip = causal && i0 + G::TILE - 1 < kw0;                     // every query lies before every key
-        if (!skip) {
-            const char* sbuf = sQ[buf];
-            const float* lbuf = sL[buf];
+        const char* sbuf = smem + buf * G::STAGE_BYTES;
+        const float* lbuf = sLbase + buf * G::TILE;
+        if (!on_diag && !skip) {
+            // pipelined: exp/sum of the previous tile is issued slice by slice between the MFMAs of tile
+            // (qs, kt); fragments and row statistics of the next query subtile are read during the last chain
+            u32x4 qf[G::NCH];
+            float nl[16];
+#pragma unroll
+            for (int c = 0; c < G::NCH; ++c) qf[c] = *reinterpret_cast<const u32x4*>(&sbuf[l32 * G::STRIDE + c * 32 + half * 16]);
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(&lbuf[gq * 8 + half * 4]);
+                nl[gq * 4 + 0] = v[0]; nl[gq * 4 + 1] = v[1]; nl[gq * 4 + 2] = v[2]; nl[gq * 4 + 3] = v[3];
+            }
 #pragma unroll
             for (int qs = 0; qs < G::NSUB; ++qs) {
-                uint4 qf[G::NCH];
+                f32x16 acc0 = {0}, acc1 = {0};
+                float s0 = 0.f, s1 = 0.f;
+                slot_fence();
 #pragma unroll
-                for (int c = 0; c < G::NCH; ++c) qf[c] = *reinterpret_cast<const uint4*>(&sbuf[(qs * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
-                float nl[16];  // -lse2 of the 16 query rows this lane sees
+                for (int c = 0; c < G::NCH; ++c) {  // tile (qs, 0) while the carried tile (key subtile 1) is summed
+                    colsum_slice<G::NCH>(c, carry, carry_nl, c2, s0, s1);
+                    mma_chunk<T>(acc0, qf[c], kf[0][c]);  // acc[query row][key col]
+                    slot_fence();
+                }
+                col[1] += s0 + s1;
+                s0 = 0.f;
+                s1 = 0.f;
+                u32x4 qn[G::NCH];
+                float nn[16];
+#pragma unroll
+                for (int c = 0; c < G::NCH; ++c) {  // tile (qs, 1) while tile (qs, 0) is summed
+                    colsum_slice<G::NCH>(c, acc0, nl, c2, s0, s1);
+                    mma_chunk<T>(acc1, qf[c], kf[1][c]);
+                    if (qs + 1 < G::NSUB) {
+                        qn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((qs + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                        if (c < 4) {
+                            const f32x4 v = *reinterpret_cast<const f32x4*>(&lbuf[(qs + 1) * 32 + c * 8 + half * 4]);
+                            nn[c * 4 + 0] = v[0]; nn[c * 4 + 1] = v[1]; nn[c * 4 + 2] = v[2]; nn[c * 4 + 3] = v[3];
+                        }
+                    }
+                    slot_fence();
+                }
+                col[0] += s0 + s1;
+                carry = acc1;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) carry_nl[r] = nl[r];
+                if (qs + 1 < G::NSUB) {
+#pragma unroll
+                    for (int c = 0; c < G::NCH; ++c) qf[c] = qn[c];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) nl[r] = nn[r];
+                }
+            }
+        } else if (!skip) {
+            col[1] += colsum_tile(carry, carry_nl, c2);  // drain the pipeline before the masked tiles
+#pragma unroll
+            for (int r = 0; r < 16; ++r) carry_nl[r] = -INFINITY;
+#pragma unroll
+            for (int qs = 0; qs < G::NSUB; ++qs) {
+                u32x4 qf[G::NCH];
+#pragma unroll
+                for (int c = 0; c < G::NCH; ++c) qf[c] = *reinterpret_cast<const u32x4*>(&sbuf[(qs * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                float nl[16];
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const f32x4 v = *reinterpret_cast<const f32x4*>(&lbuf[qs * 32 + gq * 8 + half * 4]);
-                    nl[gq * 4 + 0] = -v[0]; nl[gq * 4 + 1] = -v[1]; nl[gq * 4 + 2] = -v[2]; nl[gq * 4 + 3] = -v[3];
+                    nl[gq * 4 + 0] = v[0]; nl[gq * 4 + 1] = v[1]; nl[gq * 4 + 2] = v[2]; nl[gq * 4 + 3] = v[3];
                 }
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt) {
+                    // this 32x32 tile: queries [qmin, qmin+31] against keys [kmin, kmin+31] (wave-uniform tests)
+                    const int qmin = i0 + qs * 32, kmin = kw0 + kt * 32;
+                    if (causal && qmin + 31 < kmin) continue;  // every query lies before every key
                     f32x16 acc = {0};
 #pragma unroll
-                    for (int c = 0; c < G::NCH; ++c) mma_chunk<T>(acc, qf[c], kf[kt][c]);  // acc[query row][key col]
-                    float part = 0.f;
-                    if (!on_diag) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) part += __builtin_amdgcn_exp2f(fmaf(acc[r], p.c2, nl[r]));
+                    for (int c = 0; c < G::NCH; ++c) mma_chunk<T>(acc, qf[c], kf[kt][c]);
+                    if (qmin > kmin + 31 || qmin + 31 < kmin) {  // off the diagonal: nothing to mask, no self term
+                        col[kt] += colsum_tile(acc, nl, c2);
                     } else {
+                        float part = 0.f;
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
-                            const int q = i0 + qs * 32 + acc_row(r, lane);
-                            float pr = __builtin_amdgcn_exp2f(fmaf(acc[r], p.c2, nl[r]));
+                            const int q = qmin + acc_row(r, lane);
+                            float pr = __builtin_amdgcn_exp2f(fmaf(acc[r], c2, nl[r]));
                             if (causal && q < my_k[kt]) pr = 0.f;
                             if (q == my_k[kt]) dg[kt] = pr;
                             part += pr;
                         }
+                        col[kt] += part;
                     }
-                    col[kt] += part;
                 }
             }
         }
-        if (more) stash(buf ^ 1);
+        if (more) {
+            stage_stash<G>(pre, smem + (buf ^ 1) * G::STAGE_BYTES + st_off);
+            if (tid < G::TILE) sLbase[(buf ^ 1) * G::TILE + tid] = fix_l(t - 1, pre_l);
+        }
     }
+    col[1] += colsum_tile(carry, carry_nl, c2);
 
+#ifdef LEMO_DEBUG_CLOCK
+    if (threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == 8 * 64 || blockIdx.x == 8 * 120 || blockIdx.x == 8 * 127 || blockIdx.x == 8 * (128 * 3 + 100)))
+        printf("colsum block %d: clock64 %lld wall %lld -> %.0f MHz, stages %d\n", (int)blockIdx.x, clock64() - dbg_c0, wall_clock64() - dbg_w0,
+               (double)(clock64() - dbg_c0) / (double)(wall_clock64() - dbg_w0) * 100.0, t_hi - t_lo + 1);
+#endif
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
         const float c = col[kt] + __shfl_xor(col[kt], 32);
@@ -324,8 +514,19 @@ template <typename T, int D>
 static int launch_score_t(const ScoreParams& p, int which, hipStream_t st) {
     const unsigned g1 = (unsigned)(NUM_XCD * p.heads_per_xcd * p.n_query_blocks);
     const unsigned g2 = (unsigned)(NUM_XCD * p.heads_per_xcd * p.n_key_blocks);
-    if (which & 1) hipLaunchKernelGGL((rowstats_kernel<T, D>), dim3(g1), dim3(SC_THREADS), 0, st, p);
-    if (which & 2) hipLaunchKernelGGL((colsum_kernel<T, D>), dim3(g2), dim3(SC_THREADS), 0, st, p);
+    using G = Geo<T, D>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {  // both kernels use more dynamic LDS than the default limit
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&rowstats_kernel<T, D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_ROWSTATS);
+        if (attr_err == hipSuccess)
+            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&colsum_kernel<T, D>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_COLSUM);
+    });
+    if (attr_err != hipSuccess) return (int)attr_err;
+    if (which & 1) hipLaunchKernelGGL((rowstats_kernel<T, D>), dim3(g1), dim3(SC_THREADS), G::LDS_ROWSTATS, st, p);
+    if (which & 2) hipLaunchKernelGGL((colsum_kernel<T, D>), dim3(g2), dim3(SC_THREADS), G::LDS_COLSUM, st, p);
     if (which & 4)
         hipLaunchKernelGGL(head_mean_kernel, dim3((p.S + 255) / 256), dim3(256), 0, st, p.colsum, p.diag, p.scores, p.S, p.H,
                            (p.flags & LEMO_EXCLUDE_SELF) ? 1 : 0);
