@@ -8,6 +8,7 @@
 // Both operands are K-contiguous in memory (X rows, nn.Linear weight rows), which is exactly the
 // per-lane 16-byte fragment the 32x32 MFMAs take, so neither needs a transpose.
 #include <mutex>
+#include <type_traits>
 
 #include "lemo_common.hpp"
 
@@ -34,7 +35,8 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
                                                                     const int* __restrict__ idx, long long M,
                                                                     const T* __restrict__ W, long long ldw,
                                                                     const T* __restrict__ bias, T* __restrict__ Y,
-                                                                    long long ldy, int C, int N, int tiles_m, int tiles_n) {
+                                                                    long long ldy, int C, int N, int tiles_m, int tiles_n,
+                                                                    unsigned x_bytes) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     // tile assignment: die x = b % 8 takes a contiguous run of tiles in grouped order (GROUP_M tile rows
@@ -56,42 +58,46 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
     const int wm = wave >> 1, wn = wave & 1;
     const int cbytes = C * (int)sizeof(T);
 
-    // rows this thread stages: piece i*256+tid -> tile row i*32 + tid/8, 16-byte piece tid%8
+    // rows this thread stages: piece i*256+tid -> tile row i*32 + tid/8, 16-byte piece tid%8.
+    // Both operands are read through buffer descriptors (X: the whole [S,C] tensor, rows picked by kept_idx;
+    // W: this tile's rows): a 32-bit per-thread offset plus a scalar offset per load, no vector address
+    // arithmetic, and the hardware range check returns zero instead of reading past the end, so the steady
+    // state has no branches.  Rows past M are clamped to the last kept row (computed, never stored).
     const int prow = tid >> 3, pcc = tid & 7;
-    const char* a_ptr[GG_NLD];
-    const char* b_ptr[GG_NLD];
+    const int ldx_bytes = (int)ldx * (int)sizeof(T), ldw_bytes = (int)ldw * (int)sizeof(T);  // host: both < 2^23
+    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(X)), 0, (int)x_bytes, 0x00020000);
+    unsigned a_voff[GG_NLD];
 #pragma unroll
     for (int i = 0; i < GG_NLD; ++i) {
-        const long long m = m0 + i * 32 + prow;
-        a_ptr[i] = nullptr;
-        if (m < M) {
-            const long long row = idx ? (long long)idx[m] : m;
-            a_ptr[i] = reinterpret_cast<const char*>(X + row * ldx) + pcc * 16;
-        }
-        const int n = n0 + i * 32 + prow;
-        b_ptr[i] = n < N ? reinterpret_cast<const char*>(W + (long long)n * ldw) + pcc * 16 : nullptr;
+        const long long m = min(m0 + i * 32 + prow, M - 1);
+        const unsigned row = idx ? (unsigned)idx[m] : (unsigned)m;
+        a_voff[i] = row * (unsigned)ldx_bytes + pcc * 16;  // host guarantees S * ldx * sizeof(T) < 2^32
     }
+    const int b_rows = min(GG_BN, N - n0);
+    const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(W + (long long)n0 * ldw)), 0, (b_rows - 1) * ldw_bytes + cbytes, 0x00020000);
+    const int b_voff = prow * ldw_bytes + pcc * 16;
 
-    u32x4 pa[GG_NLD], pb[GG_NLD];
-    auto fetch = [&](int kbyte) {
+    // Global loads take longer than one slab of MFMAs, so two slabs are kept in flight: the pieces of slab s
+    // live in register set s & 1 from the moment they are requested (during slab s-2) until they are written
+    // to LDS (during slab s-1).
+    u32x4 pa[2][GG_NLD], pb[2][GG_NLD];
+    // pieces of one slab, all at once (prologue and the ragged last slab: pieces past C are zero in BOTH operands)
+    auto fetch = [&](int kbyte, auto set_tag) {
+        constexpr int SET = decltype(set_tag)::value;
         const bool in_k = kbyte + pcc * 16 + 16 <= cbytes;  // C is a multiple of 16 bytes: a piece is all in or all out
 #pragma unroll
         for (int i = 0; i < GG_NLD; ++i) {
-            pa[i] = u32x4{0u, 0u, 0u, 0u};
-            pb[i] = u32x4{0u, 0u, 0u, 0u};
-            if (in_k && a_ptr[i]) pa[i] = *reinterpret_cast<const u32x4*>(a_ptr[i] + kbyte);
-            if (in_k && b_ptr[i]) pb[i] = *reinterpret_cast<const u32x4*>(b_ptr[i] + kbyte);
+            pa[SET][i] = u32x4{0u, 0u, 0u, 0u};
+            pb[SET][i] = u32x4{0u, 0u, 0u, 0u};
+            if (in_k) {
+                pa[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)a_voff[i], kbyte, 0);
+                pb[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff, kbyte + i * 32 * ldw_bytes, 0);
+            }
         }
     };
-    auto stash = [&](int buf) {
-        char* sA = smem + buf * GG_STAGE;
-        char* sB = sA + GG_BM * GG_STRIDE;
-#pragma unroll
-        for (int i = 0; i < GG_NLD; ++i) {
-            *reinterpret_cast<u32x4*>(sA + (i * 32 + prow) * GG_STRIDE + pcc * 16) = pa[i];
-            *reinterpret_cast<u32x4*>(sB + (i * 32 + prow) * GG_STRIDE + pcc * 16) = pb[i];
-        }
-    };
+    const int st_off = prow * GG_STRIDE + pcc * 16;
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -99,66 +105,145 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x16{0};
 
+    // Main loop.  One wave per SIMD, so the overlap is written out: the source order below is the issue
+    // order (scheduling fences), one memory instruction between consecutive MFMAs.
+    //   every third MFMA of chunks 0-2: one global load of the slab after next (almost two slabs to arrive)
+    //   the MFMA after it: one LDS write of the next slab (requested during the previous slab)
+    //   chunks 0-2: LDS reads of the next chunk's fragments;  after chunk 3: barrier, then the next slab's first chunk
     const int nk = (cbytes + GG_KB - 1) / GG_KB;
-    fetch(0);
-    stash(0);
+    const int nfull = cbytes / GG_KB;  // slabs that lie entirely inside C
+    const int a_lds = (wm * 128 + l32) * GG_STRIDE + half * 16;
+    const int b_lds = GG_BM * GG_STRIDE + (wn * 128 + l32) * GG_STRIDE + half * 16;
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    fetch(0, I0{});
+#pragma unroll
+    for (int i = 0; i < GG_NLD; ++i) {
+        *reinterpret_cast<u32x4*>(smem + st_off + i * 32 * GG_STRIDE) = pa[0][i];
+        *reinterpret_cast<u32x4*>(smem + GG_BM * GG_STRIDE + st_off + i * 32 * GG_STRIDE) = pb[0][i];
+    }
+    fetch(GG_KB, I1{});  // slab 1 (all zero if there is none)
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const bool more = kt + 1 < nk;
-        if (more) fetch((kt + 1) * GG_KB);
-        const char* sA = smem + (kt & 1) * GG_STAGE + (wm * 128 + l32) * GG_STRIDE + half * 16;
-        const char* sB = smem + (kt & 1) * GG_STAGE + GG_BM * GG_STRIDE + (wn * 128 + l32) * GG_STRIDE + half * 16;
+    u32x4 fa[4], fb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        fa[i] = *reinterpret_cast<const u32x4*>(smem + a_lds + i * 32 * GG_STRIDE);
+        fb[i] = *reinterpret_cast<const u32x4*>(smem + b_lds + i * 32 * GG_STRIDE);
+    }
+    // One slab kt of the contraction, kt & 1 == PAR.  It always moves set PAR^1 (slab kt+1) to the other LDS
+    // stage and always requests slab kt+2 into set PAR; when those slabs do not exist the writes land in a
+    // stage nobody reads again and the loads are answered with zeros or stale in-range data nobody uses.
+    auto slab = [&](int kt, auto par_tag) {
+        constexpr int PAR = decltype(par_tag)::value;
+        const char* cur = smem + PAR * GG_STAGE;
+        char* nxt = smem + (PAR ^ 1) * GG_STAGE;
+        const int kbyte = (kt + 2) * GG_KB;
 #pragma unroll
         for (int c = 0; c < GG_NCH; ++c) {
-            u32x4 af[4], bf[4];
+            u32x4 nb[4];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const u32x4*>(sA + i * 32 * GG_STRIDE + c * 32);
+            for (int i = 0; i < 4; ++i) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bf[j] = *reinterpret_cast<const u32x4*>(sB + j * 32 * GG_STRIDE + c * 32);
+                for (int j = 0; j < 4; ++j) {
+                    const int q = i * 4 + j;  // position of this MFMA in the chunk
+                    mma_chunk<T>(acc[i][j], fa[i], fb[j]);
+                    // global loads and LDS writes are spread over the slab, one every third MFMA each: issued
+                    // back to back by all four waves they would outrun the vector-memory and LDS pipes
+                    const int g = c * 16 + q, slot = g / 3;
+                    if (g % 3 == 0 && slot < 16) {  // request piece `slot` of slab kt+2: A pieces first, then B pieces
+                        if (slot < 8) pa[PAR][slot] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)a_voff[slot], kbyte, 0);
+                        else pb[PAR][slot - 8] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff, kbyte + (slot - 8) * 32 * ldw_bytes, 0);
+                    }
+                    if (g % 3 == 1 && slot < 16) {  // move piece `slot` of slab kt+1 (requested during the previous slab) to LDS
+                        if (slot < 8) *reinterpret_cast<u32x4*>(nxt + st_off + slot * 32 * GG_STRIDE) = pa[PAR ^ 1][slot];
+                        else *reinterpret_cast<u32x4*>(nxt + GG_BM * GG_STRIDE + st_off + (slot - 8) * 32 * GG_STRIDE) = pb[PAR ^ 1][slot - 8];
+                    }
+                    if (c < GG_NCH - 1) {
+                        // fragments of the next chunk: row i of A is done after its fourth MFMA and is refilled in
+                        // place; the B fragments are live to the end of the chunk, so they go to a second set
+                        if (j == 3) fa[i] = *reinterpret_cast<const u32x4*>(cur + a_lds + i * 32 * GG_STRIDE + (c + 1) * 32);
+                        if (i == 2) nb[j] = *reinterpret_cast<const u32x4*>(cur + b_lds + j * 32 * GG_STRIDE + (c + 1) * 32);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if (c < GG_NCH - 1) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) mma_chunk<T>(acc[i][j], af[i], bf[j]);
+                for (int j = 0; j < 4; ++j) fb[j] = nb[j];
+            }
         }
-        if (more) stash((kt + 1) & 1);  // the other stage: last read before the barrier that ended iteration kt-1
         __syncthreads();
-    }
-
-    // epilogue: acc[i][j][r] is Y[m0 + wm*128 + i*32 + acc_row(r), n0 + wn*128 + j*32 + l32]
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int n = n0 + wn * 128 + j * 32 + l32;
-        float bv = 0.f;
-        if (bias && n < N) {
-            if constexpr (sizeof(T) == 2) bv = bf16_to_f32(reinterpret_cast<const uint16_t*>(bias)[n]);
-            else bv = reinterpret_cast<const float*>(bias)[n];
-        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const long long mbase = m0 + wm * 128 + i * 32;
-            if constexpr (sizeof(T) == 2) {
-                // neighbouring lanes hold neighbouring columns: trade one value so that each lane owns two
-                // adjacent columns of ONE row and can store 4 bytes (even lane: row r, odd lane: row r+1)
-                const bool odd = lane & 1;
-                const int n_even = n & ~1;
-                const bool pair_ok = ((ldy & 1) == 0) && ((reinterpret_cast<uintptr_t>(Y) & 3u) == 0);  // rows 4-byte aligned
+            fa[i] = *reinterpret_cast<const u32x4*>(nxt + a_lds + i * 32 * GG_STRIDE);
+            fb[i] = *reinterpret_cast<const u32x4*>(nxt + b_lds + i * 32 * GG_STRIDE);
+        }
+    };
+    // the ragged last slab (if any) is slab nfull; it must be fetched with zero fill once its register set is free
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        slab(kt, I0{});
+        if (kt + 2 == nfull && nfull < nk) fetch((kt + 2) * GG_KB, I0{});
+        slab(kt + 1, I1{});
+        if (kt + 3 == nfull && nfull < nk) fetch((kt + 3) * GG_KB, I1{});
+    }
+    if (kt < nk) slab(kt, I0{});
+
+    // epilogue: acc[i][j][r] is Y[m0 + wm*128 + i*32 + acc_row(r), n0 + wn*128 + j*32 + l32]
+    if constexpr (sizeof(T) == 2) {
+        // bf16: a lane holds ONE column of 16 rows, so storing from the accumulators would write 2-4 bytes per
+        // lane into many rows.  Each wave instead lays its 128 x 128 block out in LDS (its own region; the
+        // main loop's stages are dead after the last barrier) and writes whole 256-byte row segments.
+        constexpr int EP = 128 * 2 + 16;  // LDS pitch of one staged row
+        char* region = smem + wave * 128 * EP;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + wn * 128 + j * 32 + l32;
+            const float bv = (bias && n < N) ? bf16_to_f32(reinterpret_cast<const uint16_t*>(bias)[n]) : 0.f;
+            char* colp = region + (4 * half) * EP + (j * 32 + l32) * 2;  // this lane's column, first of its rows
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
-                    const float v0 = acc[i][j][r] + bv, v1 = acc[i][j][r + 1] + bv;
-                    const float got = swap_with_neighbour(odd ? v0 : v1);
-                    const long long m = mbase + acc_row(odd ? r + 1 : r, lane);
-                    const uint32_t word = odd ? pack_bf16x2(got, v1) : pack_bf16x2(v0, got);
-                    if (m < M) {
-                        uint16_t* dst = reinterpret_cast<uint16_t*>(Y) + m * ldy + n_even;
-                        if (pair_ok && n_even + 1 < N) {
-                            *reinterpret_cast<uint32_t*>(dst) = word;
-                        } else {  // odd row pitch or last column of an odd N: element stores
-                            if (n_even < N) dst[0] = (uint16_t)(word & 0xffffu);
-                            if (n_even + 1 < N) dst[1] = (uint16_t)(word >> 16);
-                        }
-                    }
+                    // registers r and r+1 are two consecutive rows of this lane's column: one conversion
+                    // instruction rounds both, the two halves go to the two rows
+                    const uint32_t word = pack_bf16x2_hw(acc[i][j][r] + bv, acc[i][j][r + 1] + bv);
+                    const int row = i * 32 + 8 * (r >> 2) + (r & 3);
+                    *reinterpret_cast<uint16_t*>(colp + row * EP) = (uint16_t)(word & 0xffffu);
+                    *reinterpret_cast<uint16_t*>(colp + (row + 1) * EP) = (uint16_t)(word >> 16);
                 }
-            } else {
+            }
+        }
+        // the region is private to the wave; its LDS writes are complete before its own reads (same wave, in order)
+        const bool vec_ok = ((ldy & 7) == 0) && ((reinterpret_cast<uintptr_t>(Y) & 15u) == 0);
+        const int piece = lane & 15, rsub = lane >> 4;
+        const int ncol = n0 + wn * 128 + piece * 8;
+#pragma unroll 4
+        for (int rr = 0; rr < 32; ++rr) {
+            const int row = rr * 4 + rsub;
+            const long long m = m0 + wm * 128 + row;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(region + row * EP + piece * 16);
+            if (m < M) {
+                uint16_t* dst = reinterpret_cast<uint16_t*>(Y) + m * ldy + ncol;
+                if (vec_ok && ncol + 8 <= N) {
+                    *reinterpret_cast<u32x4*>(dst) = v;
+                } else {  // ragged right edge or unaligned rows: element stores
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (ncol + e < N) dst[e] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + wn * 128 + j * 32 + l32;
+            const float bv = (bias && n < N) ? reinterpret_cast<const float*>(bias)[n] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const long long mbase = m0 + wm * 128 + i * 32;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const long long m = mbase + acc_row(r, lane);
@@ -170,8 +255,9 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
 }
 
 template <typename T>
-static int launch_gg_t(const void* X, long long ldx, const int* idx, long long M, const void* W, long long ldw,
+static int launch_gg_t(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W, long long ldw,
                        const void* bias, void* Y, long long ldy, int C, int N, hipStream_t st) {
+    const unsigned x_bytes = (unsigned)(((S - 1) * ldx + C) * (long long)sizeof(T));  // host checked: fits 32 bits
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
@@ -183,16 +269,15 @@ static int launch_gg_t(const void* X, long long ldx, const int* idx, long long M
     const int per_xcd = (tiles_m * tiles_n + NUM_XCD - 1) / NUM_XCD;
     hipLaunchKernelGGL((gather_gemm_kernel<T>), dim3((unsigned)(per_xcd * NUM_XCD)), dim3(GG_THREADS), GG_LDS, st,
                        static_cast<const T*>(X), ldx, idx, M, static_cast<const T*>(W), ldw, static_cast<const T*>(bias),
-                       static_cast<T*>(Y), ldy, C, N, tiles_m, tiles_n);
+                       static_cast<T*>(Y), ldy, C, N, tiles_m, tiles_n, x_bytes);
     return (int)hipGetLastError();
 }
 
 int launch_gather_gemm(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W, long long ldw,
                        const void* bias, void* Y, long long ldy, int C, int N, lemo_dtype_t dt, hipStream_t st) {
-    (void)S;
     if (M == 0) return 0;
-    if (dt == LEMO_BF16) return launch_gg_t<bf16_t>(X, ldx, idx, M, W, ldw, bias, Y, ldy, C, N, st);
-    return launch_gg_t<float>(X, ldx, idx, M, W, ldw, bias, Y, ldy, C, N, st);
+    if (dt == LEMO_BF16) return launch_gg_t<bf16_t>(X, S, ldx, idx, M, W, ldw, bias, Y, ldy, C, N, st);
+    return launch_gg_t<float>(X, S, ldx, idx, M, W, ldw, bias, Y, ldy, C, N, st);
 }
 
 }  // namespace lemo

@@ -181,6 +181,9 @@ int lemo_gather_gemm(const void* X, int64_t S, int64_t ldx, const int32_t* kept_
     if (!aligned16(X) || !aligned16(W) || ldx % e16 || ldw % e16) return LEMO_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(Y) % (dt == LEMO_BF16 ? 2 : 4)) return LEMO_ERR_ALIGN;  // Y: element alignment is enough
     if (kept_idx && (reinterpret_cast<uintptr_t>(kept_idx) & 3u)) return LEMO_ERR_ALIGN;
+    const int64_t esz = dt == LEMO_BF16 ? 2 : 4;
+    if (ldw * esz >= (1 << 23) || ldx * esz >= (1 << 23)) return LEMO_ERR_UNSUPPORTED;  // row pitch below 8 MiB
+    if (((S - 1) * ldx + C) * esz >= ((int64_t)1 << 32)) return LEMO_ERR_UNSUPPORTED;      // X is addressed with 32-bit offsets
     const int64_t tiles = ((M + 255) / 256) * (((int64_t)N + 255) / 256);
     if (tiles >= (int64_t)1 << 28) return LEMO_ERR_UNSUPPORTED;
     return launch_gather_gemm(X, S, ldx, kept_idx, M, W, ldw, bias, Y, ldy, C, N, dt, static_cast<hipStream_t>(stream)) == 0

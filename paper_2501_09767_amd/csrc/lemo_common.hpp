@@ -51,6 +51,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) { return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16); }
+// the same rounding done by the conversion instruction of gfx950 (v_cvt_pk_bf16_f32, nearest-even): one
+// instruction for two values, used where conversions are on the critical path
+__device__ __forceinline__ uint32_t pack_bf16x2_hw(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 
 // ---- parameter blocks -----------------------------------------------------------------------------
 struct ScoreParams {

@@ -304,9 +304,6 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
     extern __shared__ __attribute__((aligned(16))) char smem[];
     float* const sLbase = reinterpret_cast<float*>(smem + 2 * G::STAGE_BYTES);
 
-#ifdef LEMO_DEBUG_CLOCK
-    const long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
-#endif
     int h, kb;
     if (!decode_block(p.n_key_blocks, p.heads_per_xcd, p.H, h, kb)) return;
     const bool causal = (p.flags & LEMO_CAUSAL) != 0;
@@ -477,11 +474,6 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
     }
     col[1] += colsum_tile(carry, carry_nl, c2);
 
-#ifdef LEMO_DEBUG_CLOCK
-    if (threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == 8 * 64 || blockIdx.x == 8 * 120 || blockIdx.x == 8 * 127 || blockIdx.x == 8 * (128 * 3 + 100)))
-        printf("colsum block %d: clock64 %lld wall %lld -> %.0f MHz, stages %d\n", (int)blockIdx.x, clock64() - dbg_c0, wall_clock64() - dbg_w0,
-               (double)(clock64() - dbg_c0) / (double)(wall_clock64() - dbg_w0) * 100.0, t_hi - t_lo + 1);
-#endif
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
         const float c = col[kt] + __shfl_xor(col[kt], 32);
