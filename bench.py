@@ -78,7 +78,7 @@ def cpu_baseline(cfg, lay, wl, steps_note=""):
 
     import oracle
     group = cfg.H // cfg.H_kv
-    S1 = min(cfg.S, 8192)                                   # queries [0, S1): under the causal mask they only see keys < S1
+    S1 = min(cfg.S, 16384)                                  # queries [0, S1): under the causal mask they only see keys < S1
     H1 = max(group, min(cfg.H, 16) // group * group)        # a few whole GQA groups
     Q = wl.as_numpy(lay["Q"][:S1, :H1].cpu())
     K = wl.as_numpy(lay["K"][:S1, :max(1, H1 // group)].cpu())
@@ -91,7 +91,7 @@ def cpu_baseline(cfg, lay, wl, steps_note=""):
     t0 = time.perf_counter()
     kept = oracle.select_topk(scores_full, cfg.L, cfg.k)
     t_select = time.perf_counter() - t0
-    M1 = 48
+    M1 = min(len(kept), 512)
     X = wl.as_numpy(lay["X"].cpu())
     W = wl.as_numpy(lay["W"].cpu())
     t0 = time.perf_counter()
