@@ -321,6 +321,27 @@ def test_gather_gemm_llama_shape_sampled(lemo):
     assert_gemm_close(wl.to_bf16_bits(Y)[rows], want, wl.as_numpy(X)[idx[rows]], wl.as_numpy(W))
 
 
+@pytest.mark.parametrize("name", ["C4", "C5"])
+def test_gather_gemm_bench_shapes_sampled(lemo, name):
+    """The consumer GEMM at the sizes bench.py times (C4: M=8192 of 16384, N=14336; C5: M=9856 of 32768, N=11008;
+    C=4096), same launch configuration: sampled output rows, all columns, against the oracle; the rows around tile
+    edges and the ragged last tile are always in the sample."""
+    cfg = wl.CONFIGS[name]
+    say(f"[gemm] {name} shape: inputs")
+    rng = np.random.default_rng(cfg.seed + 100)
+    X = torch.from_numpy(rng.standard_normal((cfg.S, cfg.C), dtype=np.float32)).to(torch.bfloat16)
+    W = torch.from_numpy(rng.standard_normal((cfg.N, cfg.C), dtype=np.float32) * np.float32(0.02)).to(torch.bfloat16)
+    idx = oracle.select_topk(rng.random(cfg.S).astype(np.float32), cfg.L, cfg.k)
+    assert len(idx) == cfg.M
+    say(f"[gemm] {name} shape: GPU")
+    Y = lemo.lemo_gather_gemm(X.cuda(), torch.from_numpy(idx).cuda(), W.cuda())
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, cfg.M - 257, cfg.M - 256, cfg.M - 129, cfg.M - 1], rng.integers(0, cfg.M, 16)]))
+    say(f"[gemm] {name} shape: oracle on {len(rows)} rows")
+    want = oracle.gather_gemm(wl.as_numpy(X), idx[rows], wl.as_numpy(W))
+    assert_gemm_close(wl.to_bf16_bits(Y)[rows], want, wl.as_numpy(X)[idx[rows]], wl.as_numpy(W))
+
+
 # ------------------------------------------------------------------------------------ scatter-add
 
 @pytest.mark.parametrize("gdt,xdt", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32"), ("f32", "bf16")])
@@ -382,6 +403,43 @@ def test_scatter_config_C3_backward(lemo):
     Z = torch.zeros_like(R).cuda()
     lemo.lemo_scatter_grad(G.cuda(), idxd, Z, mode=1)
     assert torch.equal(Z[idxd.long()].cpu(), G)
+
+
+def test_scatter_config_C5_backward(lemo):
+    """C5's backward at full size (G [9856,4096] bf16 into dX [32768,4096]), the launch bench.py times: bit-exact."""
+    cfg = wl.CONFIGS["C5"]
+    say("[scatter] C5 backward")
+    rng = np.random.default_rng(cfg.seed + 7)
+    G = torch.from_numpy(rng.standard_normal((cfg.M, cfg.C), dtype=np.float32)).to(torch.bfloat16)
+    R = torch.from_numpy(rng.standard_normal((cfg.S, cfg.C), dtype=np.float32)).to(torch.bfloat16)
+    idx = oracle.select_topk(rng.random(cfg.S).astype(np.float32), cfg.L, cfg.k)
+    Dd = R.cuda()
+    lemo.lemo_scatter_grad(G.cuda(), torch.from_numpy(idx).cuda(), Dd)
+    torch.cuda.synchronize()
+    want = wl.as_numpy(R).copy()
+    oracle.scatter_add(wl.as_numpy(G), idx, want)
+    np.testing.assert_array_equal(wl.as_numpy(Dd), want)
+
+
+def test_error_codes_leave_outputs_untouched(lemo):
+    """Bad arguments are refused on the host: an exception with the library's code, nothing launched, outputs as before."""
+    say("[errors] refused calls")
+    X = torch.randn(64, 64, device="cuda").to(torch.bfloat16)
+    W = torch.randn(32, 64, device="cuda").to(torch.bfloat16)
+    Y = torch.full((10, 32), 7.0, device="cuda", dtype=torch.bfloat16)
+    bad_idx = torch.arange(10, device="cuda", dtype=torch.int32)
+    with pytest.raises(lemo.LemoError) as e:
+        lemo.lemo_gather_gemm(X[:, :60], bad_idx, W[:, :60], Y=Y)  # C = 60 is not a multiple of 8
+    assert e.value.code == -6
+    with pytest.raises(lemo.LemoError) as e:
+        lemo.lemo_select_topk(torch.zeros(100, device="cuda"), 10000, 5000)  # segment longer than the kernel supports
+    assert e.value.code == -6
+    Q = torch.randn(100, 2, 96, device="cuda").to(torch.bfloat16)
+    with pytest.raises(lemo.LemoError) as e:
+        lemo.lemo_score_segments(Q, Q, 64)  # head_dim 96 is not built
+    assert e.value.code == -6
+    torch.cuda.synchronize()
+    assert torch.all(Y == 7.0)
 
 
 # ------------------------------------------------------------------------------------ whole path
