@@ -138,7 +138,25 @@ __device__ __forceinline__ void rowstat_update(const f32x16& raw, float c2, floa
     rowstat_finish(st, m, l);
 }
 
-template <typename T, int D>
+// The same sum against a FROZEN reference m (no maximum search, no rescaling): exact for any finite m as long as
+// nothing overflows, which the caller checks at the end.  Slice c of NS covers elements [c*16/NS, (c+1)*16/NS).
+template <int NS>
+__device__ __forceinline__ void rowstat_frozen_slice(int c, const f32x16& raw, float c2, float neg_m, float& s0, float& s1) {
+    const int lo = c * 16 / NS, hi = (c + 1) * 16 / NS;
+#pragma unroll
+    for (int r = lo; r < hi; ++r) {
+        const float e = __builtin_amdgcn_exp2f(fmaf(raw[r], c2, neg_m));
+        if (r & 1) s1 += e; else s0 += e;
+    }
+}
+
+// FROZEN = true: the first launch.  The running maximum is tracked through the first stage (and through every
+// masked tile); from then on unmasked tiles add exp2(s*c2 - m) against the maximum frozen at that point, which
+// saves the maximum search and the rescale.  Should a later logit exceed the frozen reference by more than the
+// binary32 exponent range the sum overflows and lse2 comes out non-finite.
+// FROZEN = false: the second launch, same grid.  A workgroup whose 256 rows all have a finite lse2 exits at once;
+// otherwise it recomputes its rows with the running maximum everywhere.
+template <typename T, int D, bool FROZEN>
 __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kernel(ScoreParams p) {
     using G = Geo<T, D>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -156,6 +174,10 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kern
     const float c2 = p.c2;
     const int q0 = qb * SC_BLOCK;        // first query of the workgroup
     const int qw0 = q0 + wave * SC_RES;  // first query of this wave
+    if (!FROZEN) {
+        const bool bad = q0 + tid < S && !isfinite(p.lse2[(size_t)h * S + q0 + tid]);
+        if (!__syncthreads_or(bad)) return;
+    }
 
     // resident operand: this wave's 64 queries as MFMA B fragments
     u32x4 qf[2][G::NCH];
@@ -197,7 +219,44 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kern
         const bool skip = causal && k0 > qw0 + SC_RES - 1;  // every key lies after every query
         const bool clean = causal ? (k0 + G::TILE - 1 <= qw0) : (k0 + G::TILE <= S);
         const char* sbuf = smem + (t & 1) * G::STAGE_BYTES;
-        if (clean) {
+        if (clean && FROZEN && t > 0) {
+            // pipelined, frozen reference: exp/sum of the previous tile between the MFMAs of tile (ks, qt)
+#pragma unroll
+            for (int q = 0; q < 2; ++q) m[q] = m[q] == -INFINITY ? 0.f : m[q];  // nothing seen yet: take 0 as the reference
+            const float nm[2] = {-m[0], -m[1]};
+            u32x4 kf[G::NCH];
+#pragma unroll
+            for (int c = 0; c < G::NCH; ++c) kf[c] = *reinterpret_cast<const u32x4*>(&sbuf[l32 * G::STRIDE + c * 32 + half * 16]);
+#pragma unroll
+            for (int ks = 0; ks < G::NSUB; ++ks) {
+                f32x16 acc0 = {0}, acc1 = {0};
+                float s0 = 0.f, s1 = 0.f;
+                slot_fence();
+#pragma unroll
+                for (int c = 0; c < G::NCH; ++c) {  // tile (ks, 0) while the carried tile (query subtile 1) is summed
+                    rowstat_frozen_slice<G::NCH>(c, carry, c2, nm[1], s0, s1);
+                    mma_chunk<T>(acc0, kf[c], qf[0][c]);  // acc[key row][query col]
+                    slot_fence();
+                }
+                l[1] += s0 + s1;
+                s0 = 0.f;
+                s1 = 0.f;
+                u32x4 kn[G::NCH];
+#pragma unroll
+                for (int c = 0; c < G::NCH; ++c) {  // tile (ks, 1) while tile (ks, 0) is summed
+                    rowstat_frozen_slice<G::NCH>(c, acc0, c2, nm[0], s0, s1);
+                    mma_chunk<T>(acc1, kf[c], qf[1][c]);
+                    if (ks + 1 < G::NSUB) kn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((ks + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                    slot_fence();
+                }
+                l[0] += s0 + s1;
+                carry = acc1;
+                if (ks + 1 < G::NSUB) {
+#pragma unroll
+                    for (int c = 0; c < G::NCH; ++c) kf[c] = kn[c];
+                }
+            }
+        } else if (clean) {
             // pipelined: the statistics update of the previous tile is issued slice by slice between the
             // MFMAs of tile (ks, qt); fragments of the next key subtile are read while the last chain runs
             u32x4 kf[G::NCH];
@@ -510,14 +569,20 @@ static int launch_score_t(const ScoreParams& p, int which, hipStream_t st) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {  // both kernels use more dynamic LDS than the default limit
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&rowstats_kernel<T, D>),
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&rowstats_kernel<T, D, true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_ROWSTATS);
+        if (attr_err == hipSuccess)
+            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&rowstats_kernel<T, D, false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_ROWSTATS);
         if (attr_err == hipSuccess)
             attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&colsum_kernel<T, D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_COLSUM);
     });
     if (attr_err != hipSuccess) return (int)attr_err;
-    if (which & 1) hipLaunchKernelGGL((rowstats_kernel<T, D>), dim3(g1), dim3(SC_THREADS), G::LDS_ROWSTATS, st, p);
+    if (which & 1) {  // frozen-reference sweep, then the (normally empty) repair pass over rows that overflowed
+        hipLaunchKernelGGL((rowstats_kernel<T, D, true>), dim3(g1), dim3(SC_THREADS), G::LDS_ROWSTATS, st, p);
+        hipLaunchKernelGGL((rowstats_kernel<T, D, false>), dim3(g1), dim3(SC_THREADS), G::LDS_ROWSTATS, st, p);
+    }
     if (which & 2) hipLaunchKernelGGL((colsum_kernel<T, D>), dim3(g2), dim3(SC_THREADS), G::LDS_COLSUM, st, p);
     if (which & 4)
         hipLaunchKernelGGL(head_mean_kernel, dim3((p.S + 255) / 256), dim3(256), 0, st, p.colsum, p.diag, p.scores, p.S, p.H,

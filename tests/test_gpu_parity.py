@@ -165,6 +165,29 @@ def test_score_steps_compose_to_the_full_call(lemo):
             assert abs(float(lse2[h, i]) - want) < 1e-4 * max(1.0, abs(want))
 
 
+def test_score_reference_overflow_is_repaired(lemo):
+    """Sweep 1 freezes its reference maximum after the first stage of keys; a key far later whose logit exceeds that
+    reference by more than the binary32 exponent range overflows the frozen sum, and the repair pass must recompute
+    those rows with a running maximum.  Logits of ~360 nats against a first-stage maximum near 0 force that path."""
+    say("[score] frozen-reference overflow -> repair pass")
+    S, H, d = 700, 2, 128
+    rng = np.random.default_rng(123)
+    q = np.full((S, H, d), 4.0, dtype=np.float32)
+    q[:300] = rng.standard_normal((300, H, d)).astype(np.float32)      # ordinary rows as well
+    k = (rng.standard_normal((S, H, d)) * 0.05).astype(np.float32)
+    k[450] = 8.0                                                       # scale * <q, k> = 128*32/sqrt(128) = 362
+    k[611] = -8.0
+    Q = torch.from_numpy(q).to(torch.bfloat16)
+    K = torch.from_numpy(k).to(torch.bfloat16)
+    for flags in (3, 0):
+        got, col, dg = run_score(lemo, Q, K, 256, flags)
+        assert np.isfinite(got).all() and np.isfinite(col).all()
+        want, wcol, wdg = oracle.score(wl.as_numpy(Q), wl.as_numpy(K), flags=flags, per_head=True)
+        assert_scores_close(col.ravel(), wcol.ravel(), "colsum after repair")
+        assert_scores_close(got, want, "scores after repair")
+        assert want[450] > 100  # the dominant key really collects the later queries
+
+
 def test_score_config_C2_full(lemo):
     """Llama2-7B-shaped layer, S=4096, all 32 heads, against the full oracle."""
     cfg = wl.CONFIGS["C2"]
