@@ -28,12 +28,24 @@
 
 namespace lemo {
 
+// resident subtiles per wave for bf16, d = 128 (2 or 4; see Geo)
+#ifndef LEMO_NRT_BF16_128
+#define LEMO_NRT_BF16_128 2
+#endif
+
 constexpr int SC_THREADS = 256;  // 4 waves
 constexpr int SC_WAVES = 4;
-constexpr int SC_RES = 64;       // resident rows per wave (two 32-row MFMA subtiles)
-constexpr int SC_BLOCK = SC_WAVES * SC_RES;  // 256 resident rows per workgroup
 
-template <typename T, int D> struct Geo {
+// Geometry of one instantiation.  NRT = 32-row MFMA subtiles of the RESIDENT operand a wave keeps in registers:
+//   NRT = 2  64 resident rows per wave, 256 per workgroup, two workgroups per CU (two waves per SIMD)
+//   NRT = 4  128 resident rows per wave, 512 per workgroup, one workgroup per CU: every LDS fragment read feeds
+//            four MFMA chains instead of two (half the LDS traffic per flop), but a SIMD then has no second wave
+//            to run while the first waits at a barrier or on LDS
+// Measured on the 32K-token bf16 d=128 layer: NRT = 2 4.20 / 4.25 ms (sweep 1 / sweep 2), NRT = 4 4.45 / 4.57 ms.
+template <typename T, int D, int NRT_> struct Geo {
+    static constexpr int NRT = NRT_;
+    static constexpr int RES = 32 * NRT;             // resident rows per wave
+    static constexpr int BLOCK = SC_WAVES * RES;     // resident rows per workgroup
     static constexpr int ROWB = D * (int)sizeof(T);  // bytes per head row
     static constexpr int NCH = ROWB / 32;            // MFMA chunks per row
     static constexpr int CPR = ROWB / 16;            // 16-byte pieces per row
@@ -45,7 +57,7 @@ template <typename T, int D> struct Geo {
     static constexpr int STAGE_BYTES = TILE * STRIDE;
     static constexpr int LDS_ROWSTATS = 2 * STAGE_BYTES;
     static constexpr int LDS_COLSUM = 2 * STAGE_BYTES + 2 * TILE * (int)sizeof(float);
-    static constexpr int MIN_WG = ROWB > 256 ? 1 : 2;  // workgroups per CU the register budget is set for
+    static constexpr int MIN_WG = (ROWB > 256 || NRT > 2) ? 1 : 2;  // workgroups per CU the register budget is set for
     static_assert(TILE * CPR % SC_THREADS == 0, "tile must split evenly over the workgroup");
 };
 
@@ -86,6 +98,12 @@ template <typename G>
 __device__ __forceinline__ void stage_stash(const u32x4 (&pre)[G::NLOAD], char* lds_piece) {
 #pragma unroll
     for (int i = 0; i < G::NLOAD; ++i) *reinterpret_cast<u32x4*>(lds_piece + i * G::ROWS_PER_LOAD * G::STRIDE) = pre[i];
+}
+// the NCH fragments of one 32-row subtile of a stage
+template <typename G>
+__device__ __forceinline__ void read_frags(u32x4 (&f)[G::NCH], const char* sbuf, int sub, int l32, int half) {
+#pragma unroll
+    for (int c = 0; c < G::NCH; ++c) f[c] = *reinterpret_cast<const u32x4*>(&sbuf[(sub * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
 }
 
 // The scheduler may not move anything across this point: the source order of the pipeline slots below
@@ -137,7 +155,6 @@ __device__ __forceinline__ void rowstat_update(const f32x16& raw, float c2, floa
     for (int c = 0; c < 8; ++c) rowstat_slice<8>(c, raw, c2, m, st);
     rowstat_finish(st, m, l);
 }
-
 // The same sum against a FROZEN reference m (no maximum search, no rescaling): exact for any finite m as long as
 // nothing overflows, which the caller checks at the end.  Slice c of NS covers elements [c*16/NS, (c+1)*16/NS).
 template <int NS>
@@ -154,11 +171,11 @@ __device__ __forceinline__ void rowstat_frozen_slice(int c, const f32x16& raw, f
 // masked tile); from then on unmasked tiles add exp2(s*c2 - m) against the maximum frozen at that point, which
 // saves the maximum search and the rescale.  Should a later logit exceed the frozen reference by more than the
 // binary32 exponent range the sum overflows and lse2 comes out non-finite.
-// FROZEN = false: the second launch, same grid.  A workgroup whose 256 rows all have a finite lse2 exits at once;
+// FROZEN = false: the second launch, same grid.  A workgroup whose rows all have a finite lse2 exits at once;
 // otherwise it recomputes its rows with the running maximum everywhere.
-template <typename T, int D, bool FROZEN>
-__global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kernel(ScoreParams p) {
-    using G = Geo<T, D>;
+template <typename T, int D, int NRT, bool FROZEN>
+__global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats_kernel(ScoreParams p) {
+    using G = Geo<T, D, NRT>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     int h, qb;
@@ -172,29 +189,29 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kern
     const long long q_off = (long long)h * p.q_hs, k_off = (long long)g * p.k_hs;
     const int S = p.S;
     const float c2 = p.c2;
-    const int q0 = qb * SC_BLOCK;        // first query of the workgroup
-    const int qw0 = q0 + wave * SC_RES;  // first query of this wave
+    const int q0 = qb * G::BLOCK;        // first query of the workgroup
+    const int qw0 = q0 + wave * G::RES;  // first query of this wave
     if (!FROZEN) {
-        const bool bad = q0 + tid < S && !isfinite(p.lse2[(size_t)h * S + q0 + tid]);
+        bool bad = false;
+        for (int r = tid; r < G::BLOCK; r += SC_THREADS) bad |= q0 + r < S && !isfinite(p.lse2[(size_t)h * S + q0 + r]);
         if (!__syncthreads_or(bad)) return;
     }
 
-    // resident operand: this wave's 64 queries as MFMA B fragments
-    u32x4 qf[2][G::NCH];
+    // resident operand: this wave's queries as MFMA B fragments
+    u32x4 qf[NRT][G::NCH];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
+    for (int qt = 0; qt < NRT; ++qt)
 #pragma unroll
         for (int c = 0; c < G::NCH; ++c) qf[qt][c] = load_piece(Qb, p.q_ts, q_off, qw0 + qt * 32 + l32, S, c * 32 + half * 16);
 
-    const int my_q[2] = {qw0 + l32, qw0 + 32 + l32};  // the two queries this lane keeps statistics for
-    float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f};
+    float m[NRT], l[NRT];  // statistics of the queries qw0 + qt*32 + l32 this lane keeps
+#pragma unroll
+    for (int qt = 0; qt < NRT; ++qt) { m[qt] = -INFINITY; l[qt] = 0.f; }
 
-    // key tiles [0, ntile): under a causal mask only keys up to the block's last query matter
-    const int q_last = min(q0 + SC_BLOCK, S) - 1;
-    const int ntile = (causal ? q_last : S - 1) / G::TILE + 1;
+    // key stages [0, nstage): under a causal mask only keys up to the block's last query matter
+    const int q_last = min(q0 + G::BLOCK, S) - 1;
+    const int nstage = (causal ? q_last : S - 1) / G::TILE + 1;
 
-    // staging: thread owns piece (tid % CPR) of rows tid / CPR + i * ROWS_PER_LOAD.  Rows beyond the end
-    // are clamped to the last row: those keys are always masked (or belong to queries that are not stored).
     const int st_row = tid / G::CPR, st_cc = tid % G::CPR;
     const char* k_head = reinterpret_cast<const char*>(Kb + k_off);  // wave-uniform
     const int k_row_bytes = (int)p.k_ts * (int)sizeof(T);           // host guarantees < 2^24
@@ -202,104 +219,102 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kern
     const int st_off = st_row * G::STRIDE + st_cc * 16;
     u32x4 pre[G::NLOAD];
 
-    // carry: the last computed tile whose statistics have not been folded in yet (it belongs to query
-    // subtile 1); -inf means "none"
+    // carry: the last computed tile whose statistics have not been folded in yet (it belongs to the last
+    // query subtile); -inf means "none"
     f32x16 carry;
 #pragma unroll
     for (int r = 0; r < 16; ++r) carry[r] = -INFINITY;
 
     stage_fetch<G>(pre, k_head, k_row_bytes, 0, S, st_voff);
     stage_stash<G>(pre, smem + st_off);
-    for (int t = 0; t < ntile; ++t) {
+    for (int t = 0; t < nstage; ++t) {
         __syncthreads();  // stage t is complete; every wave is done reading stage t-1
-        const bool more = t + 1 < ntile;
+        const bool more = t + 1 < nstage;
         if (more) stage_fetch<G>(pre, k_head, k_row_bytes, (t + 1) * G::TILE, S, st_voff);
         const int k0 = t * G::TILE;
-        // wave-uniform classification of this tile of keys against the wave's queries [qw0, qw0+63]
-        const bool skip = causal && k0 > qw0 + SC_RES - 1;  // every key lies after every query
+        // wave-uniform classification of this stage of keys against the wave's queries [qw0, qw0+RES-1]
+        const bool skip = causal && k0 > qw0 + G::RES - 1;  // every key lies after every query
         const bool clean = causal ? (k0 + G::TILE - 1 <= qw0) : (k0 + G::TILE <= S);
         const char* sbuf = smem + (t & 1) * G::STAGE_BYTES;
         if (clean && FROZEN && t > 0) {
             // pipelined, frozen reference: exp/sum of the previous tile between the MFMAs of tile (ks, qt)
+            float nm[NRT];
 #pragma unroll
-            for (int q = 0; q < 2; ++q) m[q] = m[q] == -INFINITY ? 0.f : m[q];  // nothing seen yet: take 0 as the reference
-            const float nm[2] = {-m[0], -m[1]};
+            for (int q = 0; q < NRT; ++q) {
+                m[q] = m[q] == -INFINITY ? 0.f : m[q];  // nothing seen yet: take 0 as the reference
+                nm[q] = -m[q];
+            }
             u32x4 kf[G::NCH];
-#pragma unroll
-            for (int c = 0; c < G::NCH; ++c) kf[c] = *reinterpret_cast<const u32x4*>(&sbuf[l32 * G::STRIDE + c * 32 + half * 16]);
+            read_frags<G>(kf, sbuf, 0, l32, half);
 #pragma unroll
             for (int ks = 0; ks < G::NSUB; ++ks) {
-                f32x16 acc0 = {0}, acc1 = {0};
-                float s0 = 0.f, s1 = 0.f;
-                slot_fence();
-#pragma unroll
-                for (int c = 0; c < G::NCH; ++c) {  // tile (ks, 0) while the carried tile (query subtile 1) is summed
-                    rowstat_frozen_slice<G::NCH>(c, carry, c2, nm[1], s0, s1);
-                    mma_chunk<T>(acc0, kf[c], qf[0][c]);  // acc[key row][query col]
-                    slot_fence();
-                }
-                l[1] += s0 + s1;
-                s0 = 0.f;
-                s1 = 0.f;
                 u32x4 kn[G::NCH];
+                f32x16 prev = carry;
 #pragma unroll
-                for (int c = 0; c < G::NCH; ++c) {  // tile (ks, 1) while tile (ks, 0) is summed
-                    rowstat_frozen_slice<G::NCH>(c, acc0, c2, nm[0], s0, s1);
-                    mma_chunk<T>(acc1, kf[c], qf[1][c]);
-                    if (ks + 1 < G::NSUB) kn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((ks + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                for (int qt = 0; qt < NRT; ++qt) {  // tile (ks, qt) while the tile before it is summed
+                    const int pq = (qt + NRT - 1) % NRT;  // query subtile of the tile before
+                    f32x16 acc = {0};
+                    float s0 = 0.f, s1 = 0.f;
                     slot_fence();
+#pragma unroll
+                    for (int c = 0; c < G::NCH; ++c) {
+                        rowstat_frozen_slice<G::NCH>(c, prev, c2, nm[pq], s0, s1);
+                        mma_chunk<T>(acc, kf[c], qf[qt][c]);  // acc[key row][query col]
+                        if (qt == NRT - 1 && ks + 1 < G::NSUB)
+                            kn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((ks + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                        slot_fence();
+                    }
+                    l[pq] += s0 + s1;
+                    prev = acc;
                 }
-                l[0] += s0 + s1;
-                carry = acc1;
+                carry = prev;
                 if (ks + 1 < G::NSUB) {
 #pragma unroll
                     for (int c = 0; c < G::NCH; ++c) kf[c] = kn[c];
                 }
             }
         } else if (clean) {
-            // pipelined: the statistics update of the previous tile is issued slice by slice between the
-            // MFMAs of tile (ks, qt); fragments of the next key subtile are read while the last chain runs
+            // pipelined, running maximum: the statistics update of the previous tile is issued slice by slice
+            // between the MFMAs of tile (ks, qt); fragments of the next key subtile are read during the last chain
             u32x4 kf[G::NCH];
-#pragma unroll
-            for (int c = 0; c < G::NCH; ++c) kf[c] = *reinterpret_cast<const u32x4*>(&sbuf[l32 * G::STRIDE + c * 32 + half * 16]);
+            read_frags<G>(kf, sbuf, 0, l32, half);
 #pragma unroll
             for (int ks = 0; ks < G::NSUB; ++ks) {
-                RowStat st;
-                f32x16 acc0 = {0}, acc1 = {0};
-                slot_fence();
-#pragma unroll
-                for (int c = 0; c < G::NCH; ++c) {  // tile (ks, 0) while the carried tile (query subtile 1) is folded in
-                    rowstat_slice<G::NCH>(c, carry, c2, m[1], st);
-                    mma_chunk<T>(acc0, kf[c], qf[0][c]);  // acc[key row][query col]
-                    slot_fence();
-                }
-                rowstat_finish(st, m[1], l[1]);
                 u32x4 kn[G::NCH];
+                f32x16 prev = carry;
 #pragma unroll
-                for (int c = 0; c < G::NCH; ++c) {  // tile (ks, 1) while tile (ks, 0) is folded in
-                    rowstat_slice<G::NCH>(c, acc0, c2, m[0], st);
-                    mma_chunk<T>(acc1, kf[c], qf[1][c]);
-                    if (ks + 1 < G::NSUB) kn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((ks + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                for (int qt = 0; qt < NRT; ++qt) {
+                    const int pq = (qt + NRT - 1) % NRT;
+                    f32x16 acc = {0};
+                    RowStat st;
                     slot_fence();
+#pragma unroll
+                    for (int c = 0; c < G::NCH; ++c) {
+                        rowstat_slice<G::NCH>(c, prev, c2, m[pq], st);
+                        mma_chunk<T>(acc, kf[c], qf[qt][c]);
+                        if (qt == NRT - 1 && ks + 1 < G::NSUB)
+                            kn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((ks + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                        slot_fence();
+                    }
+                    rowstat_finish(st, m[pq], l[pq]);
+                    prev = acc;
                 }
-                rowstat_finish(st, m[0], l[0]);
-                carry = acc1;
+                carry = prev;
                 if (ks + 1 < G::NSUB) {
 #pragma unroll
                     for (int c = 0; c < G::NCH; ++c) kf[c] = kn[c];
                 }
             }
         } else if (!skip) {
-            rowstat_update(carry, c2, m[1], l[1]);  // drain the pipeline before the masked tiles
+            rowstat_update(carry, c2, m[NRT - 1], l[NRT - 1]);  // drain the pipeline before the masked tiles
 #pragma unroll
             for (int r = 0; r < 16; ++r) carry[r] = -INFINITY;
 #pragma unroll
             for (int ks = 0; ks < G::NSUB; ++ks) {
                 u32x4 kf[G::NCH];
+                read_frags<G>(kf, sbuf, ks, l32, half);
 #pragma unroll
-                for (int c = 0; c < G::NCH; ++c) kf[c] = *reinterpret_cast<const u32x4*>(&sbuf[(ks * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
-#pragma unroll
-                for (int qt = 0; qt < 2; ++qt) {
+                for (int qt = 0; qt < NRT; ++qt) {
                     // this 32x32 tile: keys [kmin, kmin+31] against queries [qmin, qmin+31] (wave-uniform tests)
                     const int kmin = k0 + ks * 32, qmin = qw0 + qt * 32;
                     if (causal && kmin > qmin + 31) continue;  // every key lies after every query
@@ -309,7 +324,7 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kern
                     const bool all_allowed = causal ? (kmin + 31 <= qmin) : (kmin + 31 < S);
                     if (!all_allowed) {
                         // key j may be used by query i iff j <= lim(i): i itself under the causal mask, S-1 otherwise
-                        const int lim = causal ? my_q[qt] : S - 1;
+                        const int lim = causal ? qmin + l32 : S - 1;
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int key = kmin + acc_row(r, lane);
@@ -322,16 +337,17 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void rowstats_kern
         }
         if (more) stage_stash<G>(pre, smem + ((t + 1) & 1) * G::STAGE_BYTES + st_off);
     }
-    rowstat_update(carry, c2, m[1], l[1]);
+    rowstat_update(carry, c2, m[NRT - 1], l[NRT - 1]);
 
     // the two half-waves hold disjoint key rows of the same queries: merge, then lse2 = m + log2(l)
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < NRT; ++qt) {
         const float mo = __shfl_xor(m[qt], 32), lo = __shfl_xor(l[qt], 32);
         const float mt = fmaxf(m[qt], mo);
         const float ms = mt == -INFINITY ? 0.f : mt;
         const float lt = l[qt] * __builtin_amdgcn_exp2f(m[qt] - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
-        if (half == 0 && my_q[qt] < S) p.lse2[(size_t)h * S + my_q[qt]] = mt + __builtin_amdgcn_logf(lt);
+        const int q = qw0 + qt * 32 + l32;
+        if (half == 0 && q < S) p.lse2[(size_t)h * S + q] = mt + __builtin_amdgcn_logf(lt);
     }
 }
 
@@ -356,10 +372,18 @@ __device__ __forceinline__ float colsum_tile(const f32x16& raw, const float (&nl
     for (int c = 0; c < 8; ++c) colsum_slice<8>(c, raw, nl, c2, s0, s1);
     return s0 + s1;
 }
+// -lse2 of the 16 query rows of subtile `sub` this lane meets (rows 8g + 4*half + 0..3)
+__device__ __forceinline__ void read_nl(float (&nl)[16], const float* lbuf, int sub, int half) {
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(&lbuf[sub * 32 + gq * 8 + half * 4]);
+        nl[gq * 4 + 0] = v[0]; nl[gq * 4 + 1] = v[1]; nl[gq * 4 + 2] = v[2]; nl[gq * 4 + 3] = v[3];
+    }
+}
 
-template <typename T, int D>
-__global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel(ScoreParams p) {
-    using G = Geo<T, D>;
+template <typename T, int D, int NRT>
+__global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void colsum_kernel(ScoreParams p) {
+    using G = Geo<T, D, NRT>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     float* const sLbase = reinterpret_cast<float*>(smem + 2 * G::STAGE_BYTES);
 
@@ -371,10 +395,10 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
     // key block -> (segment, block inside the segment); blocks never straddle a segment boundary
     const int seg = kb / p.blocks_per_seg, bis = kb - seg * p.blocks_per_seg;
     const long long seg0 = (long long)seg * p.L;
-    const long long key0_ll = seg0 + (long long)bis * SC_BLOCK;
+    const long long key0_ll = seg0 + (long long)bis * G::BLOCK;
     if (key0_ll >= S) return;
     const int key0 = (int)key0_ll;
-    const int kend = (int)min((long long)S, min(seg0 + p.L, key0_ll + SC_BLOCK));  // exclusive
+    const int kend = (int)min((long long)S, min(seg0 + p.L, key0_ll + G::BLOCK));  // exclusive
 
     const int g = (int)(((long long)h * p.H_kv) / p.H);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
@@ -382,24 +406,24 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
     const T* Kb = static_cast<const T*>(p.K);
     const long long q_off = (long long)h * p.q_hs, k_off = (long long)g * p.k_hs;
     const float* lse = p.lse2 + (size_t)h * S;
-    const int kw0 = key0 + wave * SC_RES;  // first key of this wave
+    const int kw0 = key0 + wave * G::RES;  // first key of this wave
 
-    // resident operand: this wave's 64 keys as MFMA B fragments (zero beyond the block's end)
-    u32x4 kf[2][G::NCH];
+    // resident operand: this wave's keys as MFMA B fragments (zero beyond the block's end)
+    u32x4 kf[NRT][G::NCH];
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+    for (int kt = 0; kt < NRT; ++kt)
 #pragma unroll
         for (int c = 0; c < G::NCH; ++c) kf[kt][c] = load_piece(Kb, p.k_ts, k_off, kw0 + kt * 32 + l32, kend, c * 32 + half * 16);
 
-    const int my_k[2] = {kw0 + l32, kw0 + 32 + l32};  // the two columns this lane accumulates
-    float col[2] = {0.f, 0.f}, dg[2] = {0.f, 0.f};
+    float col[NRT], dg[NRT];  // column kw0 + kt*32 + l32
+#pragma unroll
+    for (int kt = 0; kt < NRT; ++kt) { col[kt] = 0.f; dg[kt] = 0.f; }
 
-    // query tiles run from the end of the sequence DOWN to the first tile that can see this block, so
+    // query stages run from the end of the sequence DOWN to the first stage that can see this block, so
     // that all key blocks of a head walk the same query rows at about the same time (shared through L2)
     const int t_hi = (S - 1) / G::TILE;
     const int t_lo = causal ? key0 / G::TILE : 0;
 
-    // staging (see sweep 1).  Query rows beyond the end are clamped; their lse2 is +inf, so p = 0.
     const int st_row = tid / G::CPR, st_cc = tid % G::CPR;
     const char* q_head = reinterpret_cast<const char*>(Qb + q_off);  // wave-uniform
     const int q_row_bytes = (int)p.q_ts * (int)sizeof(T);           // host guarantees < 2^24
@@ -411,7 +435,7 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
     auto fetch_l = [&](int t) { return tid < G::TILE ? lse[min(t * G::TILE + tid, S - 1)] : 0.f; };
     auto fix_l = [&](int t, float v) { return t * G::TILE + tid < S ? -v : -INFINITY; };  // stored negated: p = exp2(s*c2 + nl)
 
-    // carry: last computed tile not yet summed (always a tile of key subtile 1); nl = -inf means "none"
+    // carry: last computed tile not yet summed (always a tile of the last key subtile); nl = -inf means "none"
     f32x16 carry = {0};
     float carry_nl[16];
 #pragma unroll
@@ -430,7 +454,7 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
             pre_l = fetch_l(t - 1);
         }
         const int i0 = t * G::TILE;
-        const bool on_diag = i0 <= kw0 + SC_RES - 1 && i0 + G::TILE - 1 >= kw0;  // tile meets the diagonal band of this wave
+        const bool on_diag = i0 <= kw0 + G::RES - 1 && i0 + G::TILE - 1 >= kw0;  // stage meets the diagonal band of this wave
         const bool skip = causal && i0 + G::TILE - 1 < kw0;                     // every query lies before every key
         const char* sbuf = smem + buf * G::STAGE_BYTES;
         const float* lbuf = sLbase + buf * G::TILE;
@@ -439,44 +463,37 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
             // (qs, kt); fragments and row statistics of the next query subtile are read during the last chain
             u32x4 qf[G::NCH];
             float nl[16];
-#pragma unroll
-            for (int c = 0; c < G::NCH; ++c) qf[c] = *reinterpret_cast<const u32x4*>(&sbuf[l32 * G::STRIDE + c * 32 + half * 16]);
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const f32x4 v = *reinterpret_cast<const f32x4*>(&lbuf[gq * 8 + half * 4]);
-                nl[gq * 4 + 0] = v[0]; nl[gq * 4 + 1] = v[1]; nl[gq * 4 + 2] = v[2]; nl[gq * 4 + 3] = v[3];
-            }
+            read_frags<G>(qf, sbuf, 0, l32, half);
+            read_nl(nl, lbuf, 0, half);
 #pragma unroll
             for (int qs = 0; qs < G::NSUB; ++qs) {
-                f32x16 acc0 = {0}, acc1 = {0};
-                float s0 = 0.f, s1 = 0.f;
-                slot_fence();
-#pragma unroll
-                for (int c = 0; c < G::NCH; ++c) {  // tile (qs, 0) while the carried tile (key subtile 1) is summed
-                    colsum_slice<G::NCH>(c, carry, carry_nl, c2, s0, s1);
-                    mma_chunk<T>(acc0, qf[c], kf[0][c]);  // acc[query row][key col]
-                    slot_fence();
-                }
-                col[1] += s0 + s1;
-                s0 = 0.f;
-                s1 = 0.f;
                 u32x4 qn[G::NCH];
                 float nn[16];
+                f32x16 prev = carry;
 #pragma unroll
-                for (int c = 0; c < G::NCH; ++c) {  // tile (qs, 1) while tile (qs, 0) is summed
-                    colsum_slice<G::NCH>(c, acc0, nl, c2, s0, s1);
-                    mma_chunk<T>(acc1, qf[c], kf[1][c]);
-                    if (qs + 1 < G::NSUB) {
-                        qn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((qs + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
-                        if (c < 4) {
-                            const f32x4 v = *reinterpret_cast<const f32x4*>(&lbuf[(qs + 1) * 32 + c * 8 + half * 4]);
-                            nn[c * 4 + 0] = v[0]; nn[c * 4 + 1] = v[1]; nn[c * 4 + 2] = v[2]; nn[c * 4 + 3] = v[3];
-                        }
-                    }
+                for (int kt = 0; kt < NRT; ++kt) {  // tile (qs, kt) while the tile before it is summed
+                    const int pk = (kt + NRT - 1) % NRT;  // key subtile of the tile before
+                    f32x16 acc = {0};
+                    float s0 = 0.f, s1 = 0.f;
                     slot_fence();
+#pragma unroll
+                    for (int c = 0; c < G::NCH; ++c) {
+                        if (kt == 0) colsum_slice<G::NCH>(c, prev, carry_nl, c2, s0, s1);  // the carried tile has its own rows
+                        else colsum_slice<G::NCH>(c, prev, nl, c2, s0, s1);
+                        mma_chunk<T>(acc, qf[c], kf[kt][c]);  // acc[query row][key col]
+                        if (kt == NRT - 1 && qs + 1 < G::NSUB) {
+                            qn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((qs + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                            if (c < 4) {
+                                const f32x4 v = *reinterpret_cast<const f32x4*>(&lbuf[(qs + 1) * 32 + c * 8 + half * 4]);
+                                nn[c * 4 + 0] = v[0]; nn[c * 4 + 1] = v[1]; nn[c * 4 + 2] = v[2]; nn[c * 4 + 3] = v[3];
+                            }
+                        }
+                        slot_fence();
+                    }
+                    col[pk] += s0 + s1;
+                    prev = acc;
                 }
-                col[0] += s0 + s1;
-                carry = acc1;
+                carry = prev;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) carry_nl[r] = nl[r];
                 if (qs + 1 < G::NSUB) {
@@ -487,22 +504,17 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
                 }
             }
         } else if (!skip) {
-            col[1] += colsum_tile(carry, carry_nl, c2);  // drain the pipeline before the masked tiles
+            col[NRT - 1] += colsum_tile(carry, carry_nl, c2);  // drain the pipeline before the masked tiles
 #pragma unroll
             for (int r = 0; r < 16; ++r) carry_nl[r] = -INFINITY;
 #pragma unroll
             for (int qs = 0; qs < G::NSUB; ++qs) {
                 u32x4 qf[G::NCH];
-#pragma unroll
-                for (int c = 0; c < G::NCH; ++c) qf[c] = *reinterpret_cast<const u32x4*>(&sbuf[(qs * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
                 float nl[16];
+                read_frags<G>(qf, sbuf, qs, l32, half);
+                read_nl(nl, lbuf, qs, half);
 #pragma unroll
-                for (int gq = 0; gq < 4; ++gq) {
-                    const f32x4 v = *reinterpret_cast<const f32x4*>(&lbuf[qs * 32 + gq * 8 + half * 4]);
-                    nl[gq * 4 + 0] = v[0]; nl[gq * 4 + 1] = v[1]; nl[gq * 4 + 2] = v[2]; nl[gq * 4 + 3] = v[3];
-                }
-#pragma unroll
-                for (int kt = 0; kt < 2; ++kt) {
+                for (int kt = 0; kt < NRT; ++kt) {
                     // this 32x32 tile: queries [qmin, qmin+31] against keys [kmin, kmin+31] (wave-uniform tests)
                     const int qmin = i0 + qs * 32, kmin = kw0 + kt * 32;
                     if (causal && qmin + 31 < kmin) continue;  // every query lies before every key
@@ -512,13 +524,14 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
                     if (qmin > kmin + 31 || qmin + 31 < kmin) {  // off the diagonal: nothing to mask, no self term
                         col[kt] += colsum_tile(acc, nl, c2);
                     } else {
+                        const int my_k = kmin + l32;
                         float part = 0.f;
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int q = qmin + acc_row(r, lane);
                             float pr = __builtin_amdgcn_exp2f(fmaf(acc[r], c2, nl[r]));
-                            if (causal && q < my_k[kt]) pr = 0.f;
-                            if (q == my_k[kt]) dg[kt] = pr;
+                            if (causal && q < my_k) pr = 0.f;
+                            if (q == my_k) dg[kt] = pr;
                             part += pr;
                         }
                         col[kt] += part;
@@ -531,15 +544,16 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D>::MIN_WG)) void colsum_kernel
             if (tid < G::TILE) sLbase[(buf ^ 1) * G::TILE + tid] = fix_l(t - 1, pre_l);
         }
     }
-    col[1] += colsum_tile(carry, carry_nl, c2);
+    col[NRT - 1] += colsum_tile(carry, carry_nl, c2);
 
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < NRT; ++kt) {
         const float c = col[kt] + __shfl_xor(col[kt], 32);
         const float dd = dg[kt] + __shfl_xor(dg[kt], 32);
-        if (half == 0 && my_k[kt] < kend) {
-            p.colsum[(size_t)h * S + my_k[kt]] = c;
-            p.diag[(size_t)h * S + my_k[kt]] = dd;
+        const int key = kw0 + kt * 32 + l32;
+        if (half == 0 && key < kend) {
+            p.colsum[(size_t)h * S + key] = c;
+            p.diag[(size_t)h * S + key] = dd;
         }
     }
 }
@@ -560,55 +574,60 @@ __global__ __launch_bounds__(256) void head_mean_kernel(const float* __restrict_
     scores[j] = acc / (float)H;
 }
 
-// which: bit 0 = sweep 1 (row statistics), bit 1 = sweep 2 (column sums), bit 2 = head mean
-template <typename T, int D>
-static int launch_score_t(const ScoreParams& p, int which, hipStream_t st) {
-    const unsigned g1 = (unsigned)(NUM_XCD * p.heads_per_xcd * p.n_query_blocks);
-    const unsigned g2 = (unsigned)(NUM_XCD * p.heads_per_xcd * p.n_key_blocks);
-    using G = Geo<T, D>;
+// which: bit 0 = sweep 1 (row statistics), bit 1 = sweep 2 (column sums)
+template <typename T, int D, int NRT>
+static int launch_sweeps(const ScoreParams& p_in, int which, hipStream_t st) {
+    using G = Geo<T, D, NRT>;
+    ScoreParams p = p_in;
+    p.n_query_blocks = (p.S + G::BLOCK - 1) / G::BLOCK;
+    // Key blocks never straddle a segment boundary.  Segments shorter than a block are grouped: a block
+    // then covers as many WHOLE segments as fit, which is the same as working with that longer unit.
+    long long Leff = p.L;
+    if (Leff < G::BLOCK) Leff = (G::BLOCK / Leff) * Leff;
+    if (Leff > p.S) Leff = p.S;
+    p.L = (int)Leff;
+    p.blocks_per_seg = (int)((Leff + G::BLOCK - 1) / G::BLOCK);
+    const long long nseg = ((long long)p.S + Leff - 1) / Leff;
+    p.n_key_blocks = (int)(nseg * p.blocks_per_seg);
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
-    std::call_once(once, [] {  // both kernels use more dynamic LDS than the default limit
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&rowstats_kernel<T, D, true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_ROWSTATS);
-        if (attr_err == hipSuccess)
-            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&rowstats_kernel<T, D, false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_ROWSTATS);
-        if (attr_err == hipSuccess)
-            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&colsum_kernel<T, D>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_COLSUM);
+    std::call_once(once, [] {  // the kernels use more dynamic LDS than the default limit
+        const void* ks[3] = {reinterpret_cast<const void*>(&rowstats_kernel<T, D, NRT, true>),
+                             reinterpret_cast<const void*>(&rowstats_kernel<T, D, NRT, false>),
+                             reinterpret_cast<const void*>(&colsum_kernel<T, D, NRT>)};
+        const int bytes[3] = {G::LDS_ROWSTATS, G::LDS_ROWSTATS, G::LDS_COLSUM};
+        for (int i = 0; i < 3 && attr_err == hipSuccess; ++i)
+            attr_err = hipFuncSetAttribute(ks[i], hipFuncAttributeMaxDynamicSharedMemorySize, bytes[i]);
     });
     if (attr_err != hipSuccess) return (int)attr_err;
+    const unsigned g1 = (unsigned)(NUM_XCD * p.heads_per_xcd * p.n_query_blocks);
+    const unsigned g2 = (unsigned)(NUM_XCD * p.heads_per_xcd * p.n_key_blocks);
     if (which & 1) {  // frozen-reference sweep, then the (normally empty) repair pass over rows that overflowed
-        hipLaunchKernelGGL((rowstats_kernel<T, D, true>), dim3(g1), dim3(SC_THREADS), G::LDS_ROWSTATS, st, p);
-        hipLaunchKernelGGL((rowstats_kernel<T, D, false>), dim3(g1), dim3(SC_THREADS), G::LDS_ROWSTATS, st, p);
+        hipLaunchKernelGGL((rowstats_kernel<T, D, NRT, true>), dim3(g1), dim3(SC_THREADS), G::LDS_ROWSTATS, st, p);
+        hipLaunchKernelGGL((rowstats_kernel<T, D, NRT, false>), dim3(g1), dim3(SC_THREADS), G::LDS_ROWSTATS, st, p);
     }
-    if (which & 2) hipLaunchKernelGGL((colsum_kernel<T, D>), dim3(g2), dim3(SC_THREADS), G::LDS_COLSUM, st, p);
-    if (which & 4)
-        hipLaunchKernelGGL(head_mean_kernel, dim3((p.S + 255) / 256), dim3(256), 0, st, p.colsum, p.diag, p.scores, p.S, p.H,
-                           (p.flags & LEMO_EXCLUDE_SELF) ? 1 : 0);
+    if (which & 2) hipLaunchKernelGGL((colsum_kernel<T, D, NRT>), dim3(g2), dim3(SC_THREADS), G::LDS_COLSUM, st, p);
     return (int)hipGetLastError();
 }
 
 int launch_score(const ScoreParams& p_in, lemo_dtype_t dt, int d, int which, hipStream_t st) {
     ScoreParams p = p_in;
     p.heads_per_xcd = (p.H + NUM_XCD - 1) / NUM_XCD;
-    p.n_query_blocks = (p.S + SC_BLOCK - 1) / SC_BLOCK;
-    // Key blocks never straddle a segment boundary.  Segments shorter than a block are grouped: a block
-    // then covers as many WHOLE segments as fit, which is the same as working with that longer unit.
-    long long Leff = p.L;
-    if (Leff < SC_BLOCK) Leff = (SC_BLOCK / Leff) * Leff;
-    if (Leff > p.S) Leff = p.S;
-    p.L = (int)Leff;
-    p.blocks_per_seg = (int)((Leff + SC_BLOCK - 1) / SC_BLOCK);
-    const long long nseg = ((long long)p.S + Leff - 1) / Leff;
-    p.n_key_blocks = (int)(nseg * p.blocks_per_seg);
-    if (which == 4) return launch_score_t<float, 64>(p, which, st);  // the head mean has no dtype
-    if (dt == LEMO_BF16 && d == 128) return launch_score_t<bf16_t, 128>(p, which, st);
-    if (dt == LEMO_BF16 && d == 64) return launch_score_t<bf16_t, 64>(p, which, st);
-    if (dt == LEMO_F32 && d == 128) return launch_score_t<float, 128>(p, which, st);
-    if (dt == LEMO_F32 && d == 64) return launch_score_t<float, 64>(p, which, st);
-    return (int)hipErrorInvalidValue;
+    int rc = 0;
+    if (which & 3) {
+        if (dt == LEMO_BF16 && d == 128) rc = launch_sweeps<bf16_t, 128, LEMO_NRT_BF16_128>(p, which, st);
+        else if (dt == LEMO_BF16 && d == 64) rc = launch_sweeps<bf16_t, 64, 2>(p, which, st);
+        else if (dt == LEMO_F32 && d == 128) rc = launch_sweeps<float, 128, 2>(p, which, st);
+        else if (dt == LEMO_F32 && d == 64) rc = launch_sweeps<float, 64, 2>(p, which, st);
+        else return (int)hipErrorInvalidValue;
+        if (rc) return rc;
+    }
+    if (which & 4) {
+        hipLaunchKernelGGL(head_mean_kernel, dim3((p.S + 255) / 256), dim3(256), 0, st, p.colsum, p.diag, p.scores, p.S, p.H,
+                           (p.flags & LEMO_EXCLUDE_SELF) ? 1 : 0);
+        rc = (int)hipGetLastError();
+    }
+    return rc;
 }
 
 }  // namespace lemo
