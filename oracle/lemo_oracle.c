@@ -15,6 +15,8 @@
  *                           each block are kept instead of thresholding).
  *   oracle_gather_gemm      Sec. 4.4 selective load (kept rows are read from the original input):
  *                           Y[m,:] = X[idx[m],:] . W^T (+ bias).
+ *   oracle_gather_gemm_add  Sec. 4.4, both halves fused: selective load on the way in, in-place add
+ *                           into the residual rows on the way out.
  *   oracle_scatter_add      Sec. 4.4 in-place add (padding and residual add in one step):
  *                           dX[idx[m],:] += G[m,:].
  *
@@ -302,6 +304,43 @@ int oracle_gather_gemm(const void* X, int64_t S, int64_t ldx, const int32_t* idx
             if (bias) acc += load_elem(bias, n, dtype);
             if (dtype == ORACLE_BF16) ((uint16_t*)Y)[m * ldy + n] = double_to_bf16_bits(acc);
             else ((float*)Y)[m * ldy + n] = (float)acc;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* Fused form of Sec. 4.4's token movement: the GEMM reads its rows through in_idx (selective load) and
+ * its result is added in place into the rows out_idx of the residual stream R, which completes the
+ * zero padding and the residual addition in one step:
+ *   R[out_idx[m],n] = round( R[out_idx[m],n] + sum_c X[in_idx[m],c] * W[n,c] + bias[n] ),
+ * everything in double, ONE rounding to the element type.  Rows of R that out_idx does not name stay
+ * untouched.  in_idx == NULL reads rows 0..M-1 of X; out_idx == NULL writes rows 0..M-1 of R.
+ * out_idx must be unique and within [0,S_out). */
+int oracle_gather_gemm_add(const void* X, int64_t S, int64_t ldx, const int32_t* in_idx, int64_t M,
+                           const void* W, int64_t ldw, const void* bias, void* R, int64_t ldr, int64_t S_out,
+                           const int32_t* out_idx, int32_t C, int32_t N, int dtype) {
+    if (!X || !W || !R || S <= 0 || S_out <= 0 || M < 0 || C <= 0 || N <= 0 || ldx < C || ldw < C || ldr < N) return ORACLE_ERR_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_ERR_ARG;
+    if (!out_idx && M > S_out) return ORACLE_ERR_ARG;
+    unsigned char* seen = (unsigned char*)calloc((size_t)S_out, 1);
+    if (!seen) return ORACLE_ERR_NOMEM;
+    for (int64_t m = 0; m < M; ++m) {
+        int64_t r = in_idx ? in_idx[m] : m, o = out_idx ? out_idx[m] : m;
+        if (r < 0 || r >= S || o < 0 || o >= S_out || seen[o]) { free(seen); return ORACLE_ERR_ARG; }
+        seen[o] = 1;
+    }
+    free(seen);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        int64_t r = in_idx ? in_idx[m] : m, o = out_idx ? out_idx[m] : m;
+        for (int32_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int32_t c = 0; c < C; ++c)
+                acc += load_elem(X, r * ldx + c, dtype) * load_elem(W, (int64_t)n * ldw + c, dtype);
+            if (bias) acc += load_elem(bias, n, dtype);
+            acc += load_elem(R, o * ldr + n, dtype);
+            if (dtype == ORACLE_BF16) ((uint16_t*)R)[o * ldr + n] = double_to_bf16_bits(acc);
+            else ((float*)R)[o * ldr + n] = (float)acc;
         }
     }
     return ORACLE_OK;

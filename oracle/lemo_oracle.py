@@ -51,6 +51,8 @@ def _load():
             lib.oracle_select_topk.argtypes = [vp, i64, i32, i32, vp]
             lib.oracle_gather_gemm.restype = ctypes.c_int
             lib.oracle_gather_gemm.argtypes = [vp, i64, i64, vp, i64, vp, i64, vp, vp, i64, i32, i32, ctypes.c_int]
+            lib.oracle_gather_gemm_add.restype = ctypes.c_int
+            lib.oracle_gather_gemm_add.argtypes = [vp, i64, i64, vp, i64, vp, i64, vp, vp, i64, i64, vp, i32, i32, ctypes.c_int]
             lib.oracle_scatter_add.restype = ctypes.c_int
             lib.oracle_scatter_add.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, ctypes.c_int, ctypes.c_int, ctypes.c_int]
             lib.oracle_num_threads.restype = ctypes.c_int
@@ -191,6 +193,35 @@ def gather_gemm(X: np.ndarray, idx, W: np.ndarray, bias=None) -> np.ndarray:
     _check(_load().oracle_gather_gemm(_ptr(X), S, C, _ptr(idx), M, _ptr(W), C, _ptr(bias), _ptr(Y), N, C, N, dt),
            "oracle_gather_gemm")
     return Y
+
+
+def gather_gemm_add(X: np.ndarray, in_idx, W: np.ndarray, R: np.ndarray, out_idx, bias=None) -> np.ndarray:
+    """In place: R[out_idx[m],:] += X[in_idx[m],:] @ W.T (+ bias), fp64, one rounding.  Returns R."""
+    X = np.ascontiguousarray(X)
+    W = np.ascontiguousarray(W)
+    dt = _dtype_code(X)
+    if _dtype_code(W) != dt or _dtype_code(R) != dt:
+        raise TypeError("X, W and R must share a dtype")
+    if not R.flags.c_contiguous:
+        raise ValueError("R must be C-contiguous (it is updated in place)")
+    S, C = X.shape
+    N = W.shape[0]
+    if W.shape[1] != C or R.shape[1] != N:
+        raise ValueError("W must be [N,C] and R [S_out,N]")
+    if in_idx is not None:
+        in_idx = np.ascontiguousarray(in_idx, dtype=np.int32)
+    if out_idx is not None:
+        out_idx = np.ascontiguousarray(out_idx, dtype=np.int32)
+    M = in_idx.shape[0] if in_idx is not None else (out_idx.shape[0] if out_idx is not None else S)
+    if out_idx is not None and out_idx.shape[0] != M:
+        raise ValueError("in_idx and out_idx must have the same length")
+    if bias is not None:
+        bias = np.ascontiguousarray(bias)
+        if _dtype_code(bias) != dt or bias.shape != (N,):
+            raise TypeError("bias must be [N] of the input dtype")
+    _check(_load().oracle_gather_gemm_add(_ptr(X), S, C, _ptr(in_idx), M, _ptr(W), C, _ptr(bias), _ptr(R), N, R.shape[0],
+                                          _ptr(out_idx), C, N, dt), "oracle_gather_gemm_add")
+    return R
 
 
 def scatter_add(G: np.ndarray, idx: np.ndarray, dX: np.ndarray, mode: int = SCATTER_ACCUMULATE) -> np.ndarray:

@@ -331,6 +331,72 @@ def test_gemm_random_within_one_ulp_and_identity_cases():
     np.testing.assert_array_equal(oracle.gather_gemm(X, idx, eye), X[idx])
 
 
+# ------------------------------------------------------------------------------ fused gather-GEMM + in-place add
+
+def test_gemm_add_exact_on_dyadic_grid():
+    """Sec. 4.4 in one step: on a dyadic grid every sum is exact, so the fused call must equal the naive chain
+    (gather rows, float64 matmul, zero-pad to the full sequence, add the residual), rounded once, bit for bit;
+    rows outside out_idx must keep their bits."""
+    rng = np.random.default_rng(15)
+    S, C, N, M = 50, 64, 24, 31
+    X = (rng.integers(-8, 9, (S, C)) / 4.0).astype(np.float32)
+    W = (rng.integers(-8, 9, (N, C)) / 8.0).astype(np.float32)
+    b = (rng.integers(-8, 9, N) / 2.0).astype(np.float32)
+    R = (rng.integers(-64, 65, (S, N)) / 4.0).astype(np.float32)
+    in_idx = rng.permutation(S)[:M].astype(np.int32)
+    out_idx = rng.permutation(S)[:M].astype(np.int32)  # a different, unsorted set of rows
+    padded = np.zeros((S, N))
+    padded[out_idx] = X[in_idx].astype(np.float64) @ W.astype(np.float64).T + b
+    want = R.astype(np.float64) + padded
+    got = oracle.gather_gemm_add(bf16_bits(X), in_idx, bf16_bits(W), bf16_bits(R), out_idx, bf16_bits(b))
+    np.testing.assert_array_equal(got, bf16_bits(want))
+    untouched = np.setdiff1d(np.arange(S), out_idx)
+    np.testing.assert_array_equal(got[untouched], bf16_bits(R)[untouched])
+    got32 = oracle.gather_gemm_add(X, in_idx, W, R.copy(), out_idx, b)
+    np.testing.assert_array_equal(got32, want.astype(np.float32))
+    # swapping the roles of the two index lists must change the answer (each is used on its own side)
+    assert not np.array_equal(oracle.gather_gemm_add(X, out_idx, W, R.copy(), in_idx, b), got32)
+
+
+def test_gemm_add_single_rounding_and_special_cases():
+    rng = np.random.default_rng(16)
+    S, C, N, M = 40, 96, 33, 25
+    X = bf16_bits(rng.standard_normal((S, C)))
+    W = bf16_bits(rng.standard_normal((N, C)) * 0.1)
+    R0 = bf16_bits(rng.standard_normal((S, N)))
+    idx = np.sort(rng.permutation(S)[:M]).astype(np.int32)
+    # against float64 numpy, rounded through float32 by torch: at most one step apart, almost always equal
+    want = widen(R0).astype(np.float64)
+    want[idx] += widen(X)[idx].astype(np.float64) @ widen(W).astype(np.float64).T
+    got = oracle.gather_gemm_add(X, idx, W, R0.copy(), idx)
+    wb = bf16_bits(want)
+    assert np.max(np.abs(got.astype(np.int32) - wb.astype(np.int32))) <= 1
+    assert np.mean(got == wb) > 0.999
+    # ONE rounding: the two-step chain (GEMM rounded to bf16, then added and rounded again) differs somewhere
+    two_step = R0.copy()
+    oracle.scatter_add(oracle.gather_gemm(X, idx, W), idx, two_step)
+    y = np.abs(widen(X)[idx].astype(np.float64) @ widen(W).astype(np.float64).T)
+    slack = np.zeros((S, N))
+    slack[idx] = 2.0 ** -8 * y  # the chain's extra rounding of Y, at most half a bf16 step of |Y|
+    assert np.all(np.abs(widen(got).astype(np.float64) - widen(two_step)) <= slack + 2.0 ** -8 * np.abs(widen(got)))
+    assert not np.array_equal(got, two_step)
+    # zero weights leave R as it was; a zero residual and identity weights give the zero-padded rows (token padding)
+    np.testing.assert_array_equal(oracle.gather_gemm_add(X, idx, np.zeros_like(W), R0.copy(), idx), R0)
+    eye = bf16_bits(np.eye(C))
+    pad = oracle.gather_gemm_add(X, idx, eye, np.zeros((S, C), dtype=np.uint16), idx)
+    np.testing.assert_array_equal(pad[idx], X[idx])
+    assert not pad[np.setdiff1d(np.arange(S), idx)].any()
+    # no index lists at all == dense GEMM with a residual
+    dense = oracle.gather_gemm_add(X, None, W, R0.copy(), None)
+    np.testing.assert_array_equal(dense, oracle.gather_gemm_add(X, np.arange(S, dtype=np.int32), W, R0.copy(), np.arange(S, dtype=np.int32)))
+    # duplicate or out-of-range output rows are refused
+    with pytest.raises(ValueError):
+        oracle.gather_gemm_add(X, idx, W, R0.copy(), np.full(M, 3, dtype=np.int32))
+    bad = idx.copy(); bad[0] = S
+    with pytest.raises(ValueError):
+        oracle.gather_gemm_add(X, idx, W, R0.copy(), bad)
+
+
 # ------------------------------------------------------------------------------ scatter-add
 
 @pytest.mark.parametrize("gdt,xdt", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32"), ("f32", "bf16")])
