@@ -115,6 +115,42 @@ def cpu_baseline(cfg, lay, wl, steps_note=""):
     }
 
 
+def measure_fused_output_projection(cfg, lemo, ev, stream, kept, reps=10):
+    """Outside the timed step: the attention block's output projection (C -> C) over the M kept rows, added into
+    the [S, C] residual stream at the kept positions (Sec. 4.4's in-place add).  Fused = one lemo_gather_gemm_add;
+    unfused = lemo_gather_gemm into a compact [M, C] buffer, then lemo_scatter_grad."""
+    import torch
+    S, C, M = cfg.S, cfg.C, cfg.M
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    g = torch.Generator(device="cuda").manual_seed(7)
+    A = torch.randn((M, C), device="cuda", dtype=torch.float32, generator=g).to(dt)
+    Wo = (torch.randn((C, C), device="cuda", dtype=torch.float32, generator=g) * 0.02).to(dt)
+    R = torch.randn((S, C), device="cuda", dtype=torch.float32, generator=g).to(dt)
+    Y = torch.empty((M, C), device="cuda", dtype=dt)
+
+    def timed(fn):
+        fn()
+        marks = [ev.create() for _ in range(reps + 1)]
+        ev.record(marks[0], stream)
+        for i in range(reps):
+            fn()
+            ev.record(marks[i + 1], stream)
+        torch.cuda.synchronize()
+        return sum(ev.elapsed_ms(marks[i], marks[i + 1]) for i in range(reps)) / reps
+
+    def unfused():
+        lemo.lemo_gather_gemm(A, None, Wo, Y=Y)
+        lemo.lemo_scatter_grad(Y, kept, R)
+
+    t_fused = timed(lambda: lemo.lemo_gather_gemm_add(A, None, Wo, R, kept))
+    t_unfused = timed(unfused)
+    flops = 2.0 * M * C * C
+    esz = 2 if cfg.dtype == "bf16" else 4
+    return {"what": f"output projection {C}->{C} over M={M} kept rows added into the [{S},{C}] residual rows",
+            "fused_ms": round(t_fused, 5), "fused_tflops": round(flops / t_fused * 1e-9, 2),
+            "unfused_ms": round(t_unfused, 5), "bytes_saved": 2.0 * M * C * esz}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -244,6 +280,7 @@ def main():
         "roofline": roof,
         "phases": report,
     }
+    out["fused_in_place_add"] = measure_fused_output_projection(cfg, lemo, ev, stream, kept)
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         out["cpu_baseline"] = cpu_baseline(cfg, lay, wl)

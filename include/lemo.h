@@ -163,6 +163,28 @@ int lemo_gather_gemm(const void* X, int64_t S, int64_t ldx, const int32_t* kept_
                      int32_t N, lemo_dtype_t dt, void* stream);
 
 /*
+ * Selective-load GEMM whose result is added in place into the residual stream (Sec. 4.4: the kept rows
+ * are read from the original input AND the block's output is added to the original rows, which does
+ * the zero padding and the residual addition in the GEMM's own store):
+ *
+ *     R[out_idx[m], n] += sum_c X[kept_idx[m], c] * W[n, c]  (+ bias[n])        m < M, n < N
+ *
+ *   X [S, C] row stride ldx, W [N, C] row stride ldw, bias [N] or NULL as for lemo_gather_gemm;
+ *   R [S_out, N] row stride ldr, read and written; all of dtype dt.
+ *   kept_idx [M] rows of X, or NULL for rows 0..M-1;  out_idx [M] rows of R, or NULL for rows 0..M-1.
+ *   out_idx must name each row at most once (two result rows adding into one row of R would race;
+ *   not checked); a value outside [0, S_out) drops that result row.  Rows of R that out_idx does not
+ *   name are not touched.  X and R may not overlap.  M == 0 is a no-op.
+ *
+ * binary32 accumulation; bias and then the residual are added in binary32; ONE rounding at the store.
+ * Same shape, stride and alignment rules as lemo_gather_gemm (R takes the place of Y); in addition R's
+ * row pitch must be below 8 MiB and R must span less than 4 GiB (LEMO_ERR_UNSUPPORTED otherwise).
+ */
+int lemo_gather_gemm_add(const void* X, int64_t S, int64_t ldx, const int32_t* kept_idx, int64_t M,
+                         const void* W, int64_t ldw, const void* bias, void* R, int64_t ldr, int64_t S_out,
+                         const int32_t* out_idx, int32_t C, int32_t N, lemo_dtype_t dt, void* stream);
+
+/*
  * In-place add at the kept positions (Sec. 4.4: zero padding and the residual add collapse into one
  * read-modify-write of the kept rows); also the backward of the selective load:
  *

@@ -30,13 +30,17 @@ __device__ __forceinline__ float swap_with_neighbour(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
 }
 
-template <typename T>
+// ADD = false: Y[m,:] = result row m.
+// ADD = true:  Y is the residual stream [out_rows, N]; result row m is ADDED in place to row oidx[m] (row m when
+//              oidx is null) -- the zero padding and the residual addition of Sec. 4.4 in one step, one rounding.
+template <typename T, bool ADD>
 __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __restrict__ X, long long ldx,
                                                                     const int* __restrict__ idx, long long M,
                                                                     const T* __restrict__ W, long long ldw,
                                                                     const T* __restrict__ bias, T* __restrict__ Y,
                                                                     long long ldy, int C, int N, int tiles_m, int tiles_n,
-                                                                    unsigned x_bytes) {
+                                                                    unsigned x_bytes, const int* __restrict__ oidx,
+                                                                    long long out_rows, unsigned r_bytes) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     // tile assignment: die x = b % 8 takes a contiguous run of tiles in grouped order (GROUP_M tile rows
@@ -190,8 +194,125 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
     }
     if (kt < nk) slab(kt, I0{});
 
+    // epilogue of the in-place-add form.  Output row of result row m: oidx[m] (m itself without a list); rows whose
+    // index falls outside [0, out_rows) are dropped.
+    auto add_epilogue = [&]() {
+        if constexpr (sizeof(T) == 2) {
+            // The wave's 128 x 128 block goes through LDS in two halves of 64 rows, as binary32 (the residual is
+            // added before the only rounding).  A lane then owns 8 consecutive columns of a row (16 lanes cover a
+            // row's 256 bytes): two 16-byte LDS reads, the residual's 16 bytes, one 16-byte store.  The residual
+            // rows are requested ahead -- half 0 before anything is staged, half 1 before half 0 is consumed -- so
+            // that their latency is covered by the staging.
+            constexpr int EPF = 128 * 4 + 16;  // LDS pitch of one staged row of 128 floats
+            char* region = smem + wave * 64 * EPF;
+            const bool vec_ok = ((ldy & 7) == 0) && ((reinterpret_cast<uintptr_t>(Y) & 15u) == 0);
+            const int piece = lane & 15, rsub = lane >> 4;
+            const int ncol = n0 + wn * 128 + piece * 8;
+            const bool col_vec = vec_ok && ncol + 8 <= N;
+            float bv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int n = n0 + wn * 128 + j * 32 + l32;
+                bv[j] = (bias && n < N) ? bf16_to_f32(reinterpret_cast<const uint16_t*>(bias)[n]) : 0.f;
+            }
+            // Byte offset in R of this lane's piece of row (ih*64 + rr*4 + rsub), or NONE if it is not to be written.
+            // All 32 row indices are fetched in one batch, and the residual is read through a range-checked buffer
+            // descriptor (a NONE offset lies past its end and reads as zero), so nothing here branches or waits
+            // between the loads.
+            const unsigned NONE = r_bytes;
+            const int ldy_bytes = (int)ldy * 2;
+            const __amdgpu_buffer_rsrc_t r_rsrc = __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<char*>(Y), 0, (int)r_bytes, 0x00020000);
+            int orow[2][16];
+#pragma unroll
+            for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr) {
+                    const long long m = min(m0 + wm * 128 + ih * 64 + rr * 4 + rsub, M - 1);
+                    orow[ih][rr] = oidx ? oidx[m] : (int)m;
+                }
+            unsigned roff[2][16];
+#pragma unroll
+            for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr) {
+                    const long long m = m0 + wm * 128 + ih * 64 + rr * 4 + rsub;
+                    const bool ok = (m < M) & (ncol < N) & (orow[ih][rr] >= 0) & (orow[ih][rr] < out_rows);  // no short circuit: no branches
+                    roff[ih][rr] = ok ? (unsigned)orow[ih][rr] * (unsigned)ldy_bytes + (unsigned)ncol * 2u : NONE;
+                }
+            auto prefetch = [&](int ih, u32x4 (&old)[16]) {
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr)
+                    old[rr] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, (int)(col_vec ? roff[ih][rr] : NONE), 0, 0);
+            };
+            auto stage = [&](int ih) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    char* colp = region + (4 * half) * EPF + (j * 32 + l32) * 4;
+#pragma unroll
+                    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            *reinterpret_cast<float*>(colp + (ii * 32 + 8 * (r >> 2) + (r & 3)) * EPF) = acc[ih * 2 + ii][j][r] + bv[j];
+                }
+            };
+            auto consume = [&](int ih, const u32x4 (&old)[16]) {
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr) {
+                    const int row = rr * 4 + rsub;
+                    const f32x4 lo = *reinterpret_cast<const f32x4*>(region + row * EPF + piece * 32);
+                    const f32x4 hi = *reinterpret_cast<const f32x4*>(region + row * EPF + piece * 32 + 16);
+                    if (roff[ih][rr] == NONE) continue;
+                    uint16_t* dst = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(Y) + roff[ih][rr]);
+                    const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    if (col_vec) {
+                        u32x4 out;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            out[e] = pack_bf16x2_hw(v[2 * e] + __uint_as_float(old[rr][e] << 16),
+                                                    v[2 * e + 1] + __uint_as_float(old[rr][e] & 0xffff0000u));
+                        *reinterpret_cast<u32x4*>(dst) = out;
+                    } else {  // ragged right edge or unaligned rows: element by element
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (ncol + e < N) dst[e] = (uint16_t)(pack_bf16x2_hw(v[e] + bf16_to_f32(dst[e]), 0.f) & 0xffffu);
+                    }
+                }
+            };
+            u32x4 old0[16], old1[16];
+            prefetch(0, old0);
+            stage(0);
+            prefetch(1, old1);
+            consume(0, old0);
+            stage(1);
+            consume(1, old1);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int n = n0 + wn * 128 + j * 32 + l32;
+                const float bv = (bias && n < N) ? reinterpret_cast<const float*>(bias)[n] : 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const long long mbase = m0 + wm * 128 + i * 32;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const long long m = mbase + acc_row(r, lane);
+                        if (m < M && n < N) {
+                            const long long orow = oidx ? (long long)oidx[m] : m;
+                            if (orow >= 0 && orow < out_rows) {
+                                float* dst = reinterpret_cast<float*>(Y) + orow * ldy + n;
+                                *dst = *dst + (acc[i][j][r] + bv);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    };
+
     // epilogue: acc[i][j][r] is Y[m0 + wm*128 + i*32 + acc_row(r), n0 + wn*128 + j*32 + l32]
-    if constexpr (sizeof(T) == 2) {
+    if constexpr (ADD) {
+        add_epilogue();
+    } else if constexpr (sizeof(T) == 2) {
         // bf16: a lane holds ONE column of 16 rows, so storing from the accumulators would write 2-4 bytes per
         // lane into many rows.  Each wave instead lays its 128 x 128 block out in LDS (its own region; the
         // main loop's stages are dead after the last barrier) and writes whole 256-byte row segments.
@@ -254,30 +375,39 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
     }
 }
 
-template <typename T>
+template <typename T, bool ADD>
 static int launch_gg_t(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W, long long ldw,
-                       const void* bias, void* Y, long long ldy, int C, int N, hipStream_t st) {
+                       const void* bias, void* Y, long long ldy, int C, int N, const int* oidx, long long out_rows, hipStream_t st) {
     const unsigned x_bytes = (unsigned)(((S - 1) * ldx + C) * (long long)sizeof(T));  // host checked: fits 32 bits
+    const unsigned r_bytes = ADD ? (unsigned)(((out_rows - 1) * ldy + N) * (long long)sizeof(T)) : 0u;  // likewise
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_gemm_kernel<T>),
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_gemm_kernel<T, ADD>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, GG_LDS);
     });
     if (attr_err != hipSuccess) return (int)attr_err;
     const int tiles_m = (int)((M + GG_BM - 1) / GG_BM), tiles_n = (N + GG_BN - 1) / GG_BN;
     const int per_xcd = (tiles_m * tiles_n + NUM_XCD - 1) / NUM_XCD;
-    hipLaunchKernelGGL((gather_gemm_kernel<T>), dim3((unsigned)(per_xcd * NUM_XCD)), dim3(GG_THREADS), GG_LDS, st,
+    hipLaunchKernelGGL((gather_gemm_kernel<T, ADD>), dim3((unsigned)(per_xcd * NUM_XCD)), dim3(GG_THREADS), GG_LDS, st,
                        static_cast<const T*>(X), ldx, idx, M, static_cast<const T*>(W), ldw, static_cast<const T*>(bias),
-                       static_cast<T*>(Y), ldy, C, N, tiles_m, tiles_n, x_bytes);
+                       static_cast<T*>(Y), ldy, C, N, tiles_m, tiles_n, x_bytes, oidx, out_rows, r_bytes);
     return (int)hipGetLastError();
 }
 
 int launch_gather_gemm(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W, long long ldw,
                        const void* bias, void* Y, long long ldy, int C, int N, lemo_dtype_t dt, hipStream_t st) {
     if (M == 0) return 0;
-    if (dt == LEMO_BF16) return launch_gg_t<bf16_t>(X, S, ldx, idx, M, W, ldw, bias, Y, ldy, C, N, st);
-    return launch_gg_t<float>(X, S, ldx, idx, M, W, ldw, bias, Y, ldy, C, N, st);
+    if (dt == LEMO_BF16) return launch_gg_t<bf16_t, false>(X, S, ldx, idx, M, W, ldw, bias, Y, ldy, C, N, nullptr, 0, st);
+    return launch_gg_t<float, false>(X, S, ldx, idx, M, W, ldw, bias, Y, ldy, C, N, nullptr, 0, st);
+}
+
+int launch_gather_gemm_add(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W, long long ldw,
+                           const void* bias, void* R, long long ldr, long long out_rows, const int* oidx, int C, int N,
+                           lemo_dtype_t dt, hipStream_t st) {
+    if (M == 0) return 0;
+    if (dt == LEMO_BF16) return launch_gg_t<bf16_t, true>(X, S, ldx, idx, M, W, ldw, bias, R, ldr, C, N, oidx, out_rows, st);
+    return launch_gg_t<float, true>(X, S, ldx, idx, M, W, ldw, bias, R, ldr, C, N, oidx, out_rows, st);
 }
 
 }  // namespace lemo

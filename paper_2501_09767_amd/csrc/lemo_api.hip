@@ -190,6 +190,32 @@ int lemo_gather_gemm(const void* X, int64_t S, int64_t ldx, const int32_t* kept_
                ? LEMO_OK : LEMO_ERR_HIP;
 }
 
+int lemo_gather_gemm_add(const void* X, int64_t S, int64_t ldx, const int32_t* kept_idx, int64_t M, const void* W, int64_t ldw,
+                         const void* bias, void* R, int64_t ldr, int64_t S_out, const int32_t* out_idx, int32_t C, int32_t N,
+                         lemo_dtype_t dt, void* stream) {
+    if (!valid_dtype(dt)) return LEMO_ERR_DTYPE;
+    if (M == 0) return LEMO_OK;  // nothing to add
+    if (!X || !W || !R) return LEMO_ERR_NULL;
+    if (S <= 0 || S_out <= 0 || M < 0 || C <= 0 || N <= 0 || ldx < C || ldw < C || ldr < N) return LEMO_ERR_SHAPE;
+    if ((!kept_idx && M > S) || M > S_out) return LEMO_ERR_SHAPE;  // unique output rows cannot outnumber the rows of R
+    if (M >= (int64_t)1 << 31 || S >= (int64_t)1 << 31 || S_out >= (int64_t)1 << 31) return LEMO_ERR_SHAPE;
+    const int e16 = elems_per_16B(dt);
+    if (C % e16) return LEMO_ERR_UNSUPPORTED;
+    if (!aligned16(X) || !aligned16(W) || ldx % e16 || ldw % e16) return LEMO_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(R) % (dt == LEMO_BF16 ? 2 : 4)) return LEMO_ERR_ALIGN;
+    if ((kept_idx && (reinterpret_cast<uintptr_t>(kept_idx) & 3u)) || (out_idx && (reinterpret_cast<uintptr_t>(out_idx) & 3u)))
+        return LEMO_ERR_ALIGN;
+    const int64_t esz = dt == LEMO_BF16 ? 2 : 4;
+    if (ldw * esz >= (1 << 23) || ldx * esz >= (1 << 23)) return LEMO_ERR_UNSUPPORTED;  // row pitch below 8 MiB
+    if (((S - 1) * ldx + C) * esz >= ((int64_t)1 << 32)) return LEMO_ERR_UNSUPPORTED;      // X is addressed with 32-bit offsets
+    if (ldr * esz >= (1 << 23) || ((S_out - 1) * ldr + N) * esz >= ((int64_t)1 << 32) - 16) return LEMO_ERR_UNSUPPORTED;  // so is R
+    const int64_t tiles = ((M + 255) / 256) * (((int64_t)N + 255) / 256);
+    if (tiles >= (int64_t)1 << 28) return LEMO_ERR_UNSUPPORTED;
+    return launch_gather_gemm_add(X, S, ldx, kept_idx, M, W, ldw, bias, R, ldr, S_out, out_idx, C, N, dt,
+                                  static_cast<hipStream_t>(stream)) == 0
+               ? LEMO_OK : LEMO_ERR_HIP;
+}
+
 int lemo_scatter_grad(const void* G, int64_t ldg, const int32_t* kept_idx, int64_t M, void* dX, int64_t lddx, int64_t S,
                       int32_t C, lemo_dtype_t g_dt, lemo_dtype_t dx_dt, int32_t mode, void* stream) {
     if (!dX || (M > 0 && (!G || !kept_idx))) return LEMO_ERR_NULL;

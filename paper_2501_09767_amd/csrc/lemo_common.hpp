@@ -87,5 +87,8 @@ int launch_scatter(const void* G, long long ldg, const int* idx, long long M, vo
 int launch_gather_gemm(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W,
                        long long ldw, const void* bias, void* Y, long long ldy, int C, int N, lemo_dtype_t dt,
                        hipStream_t st);
+int launch_gather_gemm_add(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W,
+                           long long ldw, const void* bias, void* R, long long ldr, long long out_rows, const int* oidx,
+                           int C, int N, lemo_dtype_t dt, hipStream_t st);
 
 }  // namespace lemo

@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_HERE, "liblemo_hip.so")
 
 EXPORTS = ("lemo_strerror", "lemo_keep_k", "lemo_kept_count", "lemo_score_workspace_bytes",
            "lemo_score_segments", "lemo_score_rowstats", "lemo_score_colsums", "lemo_score_head_mean",
-           "lemo_select_topk", "lemo_gather_gemm", "lemo_scatter_grad")
+           "lemo_select_topk", "lemo_gather_gemm", "lemo_gather_gemm_add", "lemo_scatter_grad")
 
 
 class LemoError(RuntimeError):
@@ -58,6 +58,8 @@ def _load() -> ctypes.CDLL:
     lib.lemo_select_topk.argtypes = [vp, i64, i32, i32, vp, vp]
     lib.lemo_gather_gemm.restype = ctypes.c_int
     lib.lemo_gather_gemm.argtypes = [vp, i64, i64, vp, i64, vp, i64, vp, vp, i64, i32, i32, ctypes.c_int, vp]
+    lib.lemo_gather_gemm_add.restype = ctypes.c_int
+    lib.lemo_gather_gemm_add.argtypes = [vp, i64, i64, vp, i64, vp, i64, vp, vp, i64, i64, vp, i32, i32, ctypes.c_int, vp]
     lib.lemo_scatter_grad.restype = ctypes.c_int
     lib.lemo_scatter_grad.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, ctypes.c_int, ctypes.c_int, i32, vp]
     return lib
@@ -234,6 +236,34 @@ def lemo_gather_gemm(X: torch.Tensor, kept_idx: Optional[torch.Tensor], W: torch
     _check(_lib.lemo_gather_gemm(_ptr(X), S, X.stride(0), _ptr(kept_idx), M, _ptr(W), W.stride(0), _ptr(bias), _ptr(Y),
                                  Y.stride(0) if M > 0 else N, C, N, _dt(X), _stream()), "lemo_gather_gemm")
     return Y
+
+
+def lemo_gather_gemm_add(X: torch.Tensor, kept_idx: Optional[torch.Tensor], W: torch.Tensor, R: torch.Tensor,
+                         out_idx: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
+                         M: Optional[int] = None) -> torch.Tensor:
+    """In place: R[out_idx[m],:] += X[kept_idx[m],:] @ W.T (+ bias).  X [S,C], W [N,C], R [S_out,N], rows contiguous."""
+    _dev(X, kept_idx, W, bias, R, out_idx)
+    if X.dim() != 2 or W.dim() != 2 or X.stride(1) != 1 or W.stride(1) != 1 or X.shape[1] != W.shape[1] or _dt(X) != _dt(W):
+        raise ValueError("X must be [S,C], W [N,C], same dtype, rows contiguous")
+    S, C = X.shape
+    N = W.shape[0]
+    for name, ix in (("kept_idx", kept_idx), ("out_idx", out_idx)):
+        if ix is not None:
+            if ix.dtype != torch.int32 or ix.dim() != 1 or not ix.is_contiguous():
+                raise ValueError(f"{name} must be contiguous int32 [M]")
+            if M is None:
+                M = ix.numel()
+            elif ix.numel() < M:
+                raise ValueError(f"{name} is shorter than M")
+    if M is None:
+        M = S
+    if bias is not None and (bias.dtype != X.dtype or tuple(bias.shape) != (N,) or not bias.is_contiguous()):
+        raise ValueError("bias must be [N] of the input dtype")
+    if R.dtype != X.dtype or R.dim() != 2 or R.shape[1] != N or R.stride(1) != 1:
+        raise ValueError("R must be [S_out,N] of the input dtype, rows contiguous")
+    _check(_lib.lemo_gather_gemm_add(_ptr(X), S, X.stride(0), _ptr(kept_idx), M, _ptr(W), W.stride(0), _ptr(bias), _ptr(R),
+                                     R.stride(0), R.shape[0], _ptr(out_idx), C, N, _dt(X), _stream()), "lemo_gather_gemm_add")
+    return R
 
 
 def lemo_scatter_grad(G: torch.Tensor, kept_idx: torch.Tensor, dX: torch.Tensor, mode: int = SCATTER_ACCUMULATE) -> torch.Tensor:

@@ -365,6 +365,130 @@ def test_gather_gemm_bench_shapes_sampled(lemo, name):
     assert_gemm_close(wl.to_bf16_bits(Y)[rows], want, wl.as_numpy(X)[idx[rows]], wl.as_numpy(W))
 
 
+# ------------------------------------------------------------------------------------ fused gather-GEMM + in-place add
+
+def assert_gemm_add_close(got_bits, want_bits, before_bits, Xrows, W, out_rows, bias=None):
+    """Rows named by out_rows: same bar as the plain GEMM with the residual's magnitude added to the accumulation
+    bound.  Every other row must keep its bits."""
+    untouched = np.setdiff1d(np.arange(got_bits.shape[0]), out_rows)
+    np.testing.assert_array_equal(got_bits[untouched], before_bits[untouched])
+    g = widen(got_bits[out_rows]).astype(np.float64)
+    o = widen(want_bits[out_rows]).astype(np.float64)
+    C = Xrows.shape[1]
+    mag = np.abs(widen(Xrows).astype(np.float64)) @ np.abs(widen(W).astype(np.float64)).T + np.abs(widen(before_bits[out_rows]))
+    if bias is not None:
+        mag = mag + np.abs(widen(bias).astype(np.float64))
+    ulp = np.maximum(np.abs(g), np.abs(o))
+    ulp = np.where(ulp > 0, 2.0 ** (np.floor(np.log2(np.maximum(ulp, 1e-300))) - 7), 0.0)
+    tol = ulp + 2 * 4 * np.sqrt(C) * 2.0 ** -24 * mag
+    bad = np.abs(g - o) > tol
+    assert not bad.any(), f"{bad.sum()} of {bad.size} outputs beyond one bf16 step + accumulation bound"
+    assert (got_bits[out_rows] == want_bits[out_rows]).mean() > 0.98
+
+
+@pytest.mark.parametrize("S,S_out,C,N,M,bias,pad", [(300, 300, 64, 40, 130, False, 0), (1000, 700, 256, 304, 517, True, 8),
+                                                    (513, 513, 1000, 257, 513, False, 3), (64, 9, 8, 2, 1, True, 0),
+                                                    (700, 900, 4096, 512, 300, False, 0)])
+def test_gather_gemm_add_bf16(lemo, S, S_out, C, N, M, bias, pad):
+    say(f"[gemm+add] bf16 S={S} S_out={S_out} C={C} N={N} M={M} bias={bias} pad={pad}")
+    rng = np.random.default_rng(S + C + N + 1)
+    X = torch.from_numpy(rng.standard_normal((S, C)).astype(np.float32)).to(torch.bfloat16)
+    W = torch.from_numpy((rng.standard_normal((N, C)) * 0.02).astype(np.float32)).to(torch.bfloat16)
+    b = torch.from_numpy(rng.standard_normal(N).astype(np.float32)).to(torch.bfloat16) if bias else None
+    R = torch.from_numpy(rng.standard_normal((S_out, N)).astype(np.float32)).to(torch.bfloat16)
+    in_idx = rng.permutation(S)[:M].astype(np.int32)
+    out_idx = rng.permutation(S_out)[:M].astype(np.int32)  # unsorted, unrelated to in_idx
+    Rbig = torch.full((S_out, N + pad), 7.0, dtype=torch.bfloat16, device="cuda")  # padded leading dimension
+    Rd = Rbig[:, :N]
+    Rd.copy_(R)
+    lemo.lemo_gather_gemm_add(X.cuda(), torch.from_numpy(in_idx).cuda(), W.cuda(), Rd, torch.from_numpy(out_idx).cuda(),
+                              b.cuda() if bias else None)
+    torch.cuda.synchronize()
+    assert (Rbig[:, N:] == 7.0).all()
+    before = wl.as_numpy(R)
+    want = oracle.gather_gemm_add(wl.as_numpy(X), in_idx, wl.as_numpy(W), before.copy(), out_idx, wl.as_numpy(b) if bias else None)
+    assert_gemm_add_close(wl.to_bf16_bits(Rd.contiguous()), want, before, wl.as_numpy(X)[in_idx], wl.as_numpy(W), out_idx,
+                          wl.as_numpy(b) if bias else None)
+
+
+def test_gather_gemm_add_exact_cases(lemo):
+    """Values on a dyadic grid (every partial sum representable in binary32): bit-exact against the oracle, bf16 and
+    fp32, with and without the index lists; zero residual + identity weights = zero-padded rows (token padding)."""
+    say("[gemm+add] exact cases")
+    rng = np.random.default_rng(21)
+    S, C, N, M = 400, 128, 264, 290
+    Xf = (rng.integers(-8, 9, (S, C)) / 4.0).astype(np.float32)
+    Wf = (rng.integers(-8, 9, (N, C)) / 8.0).astype(np.float32)
+    Rf = (rng.integers(-64, 65, (S, N)) / 4.0).astype(np.float32)
+    bf = (rng.integers(-8, 9, N) / 2.0).astype(np.float32)
+    in_idx = rng.permutation(S)[:M].astype(np.int32)
+    out_idx = rng.permutation(S)[:M].astype(np.int32)
+    for dtype in (torch.bfloat16, torch.float32):
+        X, W, R, b = (torch.from_numpy(a).to(dtype) for a in (Xf, Wf, Rf, bf))
+        for ii, oi in ((in_idx, out_idx), (None, out_idx), (in_idx, None), (None, None)):
+            got = lemo.lemo_gather_gemm_add(X.cuda(), None if ii is None else torch.from_numpy(ii).cuda(), W.cuda(), R.clone().cuda(),
+                                            None if oi is None else torch.from_numpy(oi).cuda(), b.cuda(), M=M)
+            torch.cuda.synchronize()
+            want = oracle.gather_gemm_add(wl.as_numpy(X), np.arange(M, dtype=np.int32) if ii is None else ii, wl.as_numpy(W),
+                                          wl.as_numpy(R).copy(), np.arange(M, dtype=np.int32) if oi is None else oi, wl.as_numpy(b))
+            np.testing.assert_array_equal(wl.as_numpy(got.cpu()), want)
+    X = torch.from_numpy(rng.standard_normal((S, C)).astype(np.float32)).to(torch.bfloat16)
+    idx = np.sort(in_idx)
+    pad = lemo.lemo_gather_gemm_add(X.cuda(), torch.from_numpy(idx).cuda(), torch.eye(C, dtype=torch.bfloat16).cuda(),
+                                    torch.zeros((S, C), dtype=torch.bfloat16, device="cuda"), torch.from_numpy(idx).cuda())
+    torch.cuda.synchronize()
+    padn = wl.to_bf16_bits(pad)
+    np.testing.assert_array_equal(padn[idx], wl.to_bf16_bits(X)[idx])
+    assert not padn[np.setdiff1d(np.arange(S), idx)].any()
+    # out-of-range output rows are dropped, M == 0 is a no-op
+    R0 = torch.from_numpy(Rf).to(torch.bfloat16).cuda()
+    oob = out_idx.copy(); oob[::3] = S + 5; oob[1::3] = -2
+    got = lemo.lemo_gather_gemm_add(torch.from_numpy(Xf).to(torch.bfloat16).cuda(), torch.from_numpy(in_idx).cuda(),
+                                    torch.from_numpy(Wf).to(torch.bfloat16).cuda(), R0.clone(), torch.from_numpy(oob).cuda())
+    keep = np.arange(M)[2::3]
+    want = oracle.gather_gemm_add(bf16(Xf), in_idx[keep], bf16(Wf), wl.to_bf16_bits(R0).copy(), out_idx[keep])
+    np.testing.assert_array_equal(wl.to_bf16_bits(got), want)
+    same = lemo.lemo_gather_gemm_add(X.cuda(), torch.empty(0, dtype=torch.int32, device="cuda"), torch.eye(C, dtype=torch.bfloat16).cuda(),
+                                     R0[:, :C].contiguous(), torch.empty(0, dtype=torch.int32, device="cuda"))
+    np.testing.assert_array_equal(wl.to_bf16_bits(same), wl.to_bf16_bits(R0[:, :C].contiguous()))
+
+
+def bf16(x):
+    return wl.to_bf16_bits(torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16))
+
+
+def test_gather_gemm_add_output_projection_shape_sampled(lemo):
+    """The attention block's output projection at the 32K-token configuration (Sec. 4.4): M = 9856 kept rows,
+    C = N = 4096, added into the [32768, 4096] residual stream at the kept positions.  Sampled rows against the
+    oracle (all columns), every row that is not kept must keep its bits."""
+    cfg = wl.CONFIGS["C5"]
+    say("[gemm+add] C5 output projection: inputs")
+    rng = np.random.default_rng(cfg.seed + 200)
+    A = torch.from_numpy(rng.standard_normal((cfg.M, cfg.C), dtype=np.float32)).to(torch.bfloat16)       # compact block output
+    W = torch.from_numpy(rng.standard_normal((cfg.C, cfg.C), dtype=np.float32) * np.float32(0.02)).to(torch.bfloat16)
+    R = torch.from_numpy(rng.standard_normal((cfg.S, cfg.C), dtype=np.float32)).to(torch.bfloat16)
+    idx = oracle.select_topk(rng.random(cfg.S).astype(np.float32), cfg.L, cfg.k)
+    say("[gemm+add] C5 output projection: GPU")
+    Rd = R.cuda()
+    lemo.lemo_gather_gemm_add(A.cuda(), None, W.cuda(), Rd, torch.from_numpy(idx).cuda())
+    torch.cuda.synchronize()
+    got = wl.to_bf16_bits(Rd)
+    before = wl.as_numpy(R)
+    mask = np.ones(cfg.S, dtype=bool); mask[idx] = False
+    np.testing.assert_array_equal(got[mask], before[mask])
+    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, cfg.M - 257, cfg.M - 129, cfg.M - 1], rng.integers(0, cfg.M, 16)]))
+    say(f"[gemm+add] C5 output projection: oracle on {len(rows)} rows")
+    want = oracle.gather_gemm_add(wl.as_numpy(A), rows.astype(np.int32), wl.as_numpy(W), before.copy(), idx[rows])
+    sel = idx[rows]
+    g, o = got[sel], want[sel]
+    mag = np.abs(widen(wl.as_numpy(A)[rows]).astype(np.float64)) @ np.abs(widen(wl.as_numpy(W)).astype(np.float64)).T + np.abs(widen(before[sel]))
+    gv, ov = widen(g).astype(np.float64), widen(o).astype(np.float64)
+    ulp = np.maximum(np.abs(gv), np.abs(ov))
+    ulp = np.where(ulp > 0, 2.0 ** (np.floor(np.log2(np.maximum(ulp, 1e-300))) - 7), 0.0)
+    assert np.all(np.abs(gv - ov) <= ulp + 8 * np.sqrt(cfg.C) * 2.0 ** -24 * mag)
+    assert (g == o).mean() > 0.98
+
+
 # ------------------------------------------------------------------------------------ scatter-add
 
 @pytest.mark.parametrize("gdt,xdt", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32"), ("f32", "bf16")])
