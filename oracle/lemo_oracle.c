@@ -10,6 +10,10 @@
  *                           self excluded) with the head mean of Eq. 2; attention scores are the
  *                           softmax probabilities (Sec. 4.2 states that the scores pass through a softmax).
  *   oracle_score_bruteforce same quantity through a materialised S x S matrix (tiny S only).
+ *   oracle_score_blocks     Sec. 4.2 Eq. 2 (maximum of the head-aggregated score over a b x b score block)
+ *                           and the token-block sums B^T_n of "Layer-specific Threshold".
+ *   oracle_select_threshold keep the token blocks whose score reaches a threshold (Sec. 4.2);
+ *   oracle_threshold_init   Alg. 1 step 1, the average token-block score.
  *   oracle_select_topk      per-segment top-k at a keep ratio (the selection unit is the paper's
  *                           token block, Sec. 4.2 "Layer-specific Threshold"; here the k best of
  *                           each block are kept instead of thresholding).
@@ -197,6 +201,105 @@ int oracle_score(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_k
     free(col);
     free(dg);
     return ORACLE_OK;
+}
+
+/* Block-wise informativeness (Sec. 4.2 "Block-wise Elimination", Eq. 2, and the token-block sum of
+ * "Layer-specific Threshold"):
+ *   mean[i][j]   = (1/H) * sum over heads h with S^h_ij > 0 of S^h_ij        (head aggregation, positive terms only)
+ *   I(B^S_mn)    = max of mean[i][j] over the b x b score block  i in [m*b,(m+1)*b), j in [n*b,(n+1)*b)
+ *   B^T_n        = sum over m of I(B^S_mn)                                    (token-block score)
+ * S^h_ij is the softmax probability of Eq. 1's reading (mode 0: always positive, so the condition is
+ * vacuous) or the scaled pre-softmax logit scale * <Q_i, K_j> (mode 1: the literal "only positive
+ * scores" rule).  Pairs a causal mask forbids (j > i), and the pair i == j when EXCLUDE_SELF is set,
+ * take no part in the maximum; a block with no admissible pair scores 0.  Ragged last blocks are
+ * simply shorter.  score_blocks ([nb,nb] doubles, row m, column n; may be NULL) and token_blocks
+ * ([nb] floats, one rounding from double), nb = ceil(S / b). */
+int oracle_score_blocks(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, int dtype,
+                        int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                        double scale, uint32_t flags, int32_t b, int mode, double* score_blocks, float* token_blocks) {
+    if (!Q || !K || !token_blocks || S <= 0 || H <= 0 || H_kv <= 0 || d <= 0 || H % H_kv || b <= 0) return ORACLE_ERR_ARG;
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || (mode != 0 && mode != 1)) return ORACLE_ERR_ARG;
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)d);
+    const int causal = (flags & ORACLE_CAUSAL) != 0;
+    const int excl = (flags & ORACLE_EXCLUDE_SELF) != 0;
+    const int64_t nb = (S + b - 1) / b;
+    const int nthr = omp_get_max_threads();
+    double** Qh = (double**)calloc((size_t)H, sizeof(double*));
+    double** Kh = (double**)calloc((size_t)H_kv, sizeof(double*));
+    double* best = (double*)calloc((size_t)nb * (size_t)nb, sizeof(double));
+    double* work = (double*)malloc(sizeof(double) * 2 * (size_t)nthr * (size_t)S);
+    int ok = Qh && Kh && best && work;
+    for (int h = 0; ok && h < H; ++h) ok = (Qh[h] = widen_head(Q, S, d, dtype, q_tok_stride, (int64_t)h * q_head_stride)) != NULL;
+    for (int g = 0; ok && g < H_kv; ++g) ok = (Kh[g] = widen_head(K, S, d, dtype, k_tok_stride, (int64_t)g * k_head_stride)) != NULL;
+    if (ok) {
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthr)
+        for (int64_t m = nb - 1; m >= 0; --m) { /* block rows are independent; late rows are the long ones */
+            double* mean = work + 2 * (size_t)omp_get_thread_num() * (size_t)S;
+            double* row = mean + S;
+            int64_t i_end = (m + 1) * b < S ? (m + 1) * b : S;
+            for (int64_t i = m * b; i < i_end; ++i) {
+                int64_t nk = causal ? i + 1 : S;
+                for (int64_t j = 0; j < nk; ++j) mean[j] = 0.0;
+                for (int h = 0; h < H; ++h) {
+                    const double* q = Qh[h] + i * d;
+                    const double* kk = Kh[(int)(((int64_t)h * H_kv) / H)];
+                    double mx = -INFINITY;
+                    for (int64_t j = 0; j < nk; ++j) {
+                        double dot = 0.0;
+                        for (int c = 0; c < d; ++c) dot += q[c] * kk[j * d + c];
+                        row[j] = scale * dot;
+                        if (row[j] > mx) mx = row[j];
+                    }
+                    if (mode == 0) {
+                        double den = 0.0;
+                        for (int64_t j = 0; j < nk; ++j) { row[j] = exp(row[j] - mx); den += row[j]; }
+                        for (int64_t j = 0; j < nk; ++j) row[j] /= den;
+                    }
+                    for (int64_t j = 0; j < nk; ++j)
+                        if (row[j] > 0.0) mean[j] += row[j];
+                }
+                for (int64_t j = 0; j < nk; ++j) {
+                    if (excl && j == i) continue;
+                    double v = mean[j] / (double)H;
+                    double* slot = best + m * nb + j / b;
+                    if (v > *slot) *slot = v;
+                }
+            }
+        }
+        for (int64_t n = 0; n < nb; ++n) {
+            double acc = 0.0;
+            for (int64_t m = 0; m < nb; ++m) acc += best[m * nb + n];
+            token_blocks[n] = (float)acc;
+        }
+        if (score_blocks) memcpy(score_blocks, best, sizeof(double) * (size_t)nb * (size_t)nb);
+    }
+    for (int h = 0; Qh && h < H; ++h) free(Qh[h]);
+    for (int g = 0; Kh && g < H_kv; ++g) free(Kh[g]);
+    free(Qh); free(Kh); free(best); free(work);
+    return ok ? ORACLE_OK : ORACLE_ERR_NOMEM;
+}
+
+/* Selection by threshold (Sec. 4.2 "Layer-specific Threshold"): a token block is kept iff its score
+ * B^T_n >= T; the tokens of kept blocks are listed in ascending order.  Returns the number of kept
+ * tokens (kept_idx must have room for S), or a negative error. */
+int64_t oracle_select_threshold(const float* token_blocks, int64_t S, int32_t b, double T, int32_t* kept_idx) {
+    if (!token_blocks || !kept_idx || S <= 0 || b <= 0) return ORACLE_ERR_ARG;
+    int64_t nb = (S + b - 1) / b, out = 0;
+    for (int64_t n = 0; n < nb; ++n) {
+        if (!((double)token_blocks[n] >= T)) continue;
+        int64_t end = (n + 1) * b < S ? (n + 1) * b : S;
+        for (int64_t j = n * b; j < end; ++j) kept_idx[out++] = (int32_t)j;
+    }
+    return out;
+}
+
+/* Step 1 of Alg. 1: the initial layer threshold is the average score of the layer's token blocks
+ * (sum in double, in index order). */
+double oracle_threshold_init(const float* token_blocks, int64_t nb) {
+    if (!token_blocks || nb <= 0) return NAN;
+    double acc = 0.0;
+    for (int64_t n = 0; n < nb; ++n) acc += (double)token_blocks[n];
+    return acc / (double)nb;
 }
 
 /* The same scores through the full S x S probability matrix of each head: all logits first, then a

@@ -47,6 +47,12 @@ def _load():
             lib.oracle_score.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, dbl, u32, vp, vp, vp]
             lib.oracle_score_bruteforce.restype = ctypes.c_int
             lib.oracle_score_bruteforce.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, dbl, u32, vp]
+            lib.oracle_score_blocks.restype = ctypes.c_int
+            lib.oracle_score_blocks.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, dbl, u32, i32, ctypes.c_int, vp, vp]
+            lib.oracle_select_threshold.restype = i64
+            lib.oracle_select_threshold.argtypes = [vp, i64, i32, dbl, vp]
+            lib.oracle_threshold_init.restype = dbl
+            lib.oracle_threshold_init.argtypes = [vp, i64]
             lib.oracle_select_topk.restype = ctypes.c_int
             lib.oracle_select_topk.argtypes = [vp, i64, i32, i32, vp]
             lib.oracle_gather_gemm.restype = ctypes.c_int
@@ -155,6 +161,42 @@ def score_bruteforce(Q: np.ndarray, K: np.ndarray, flags: int = CAUSAL | EXCLUDE
     _check(_load().oracle_score_bruteforce(_ptr(Q), _ptr(K), S, H, Hkv, d, dt, qts, qhs, kts, khs, float(scale),
                                            flags, _ptr(scores)), "oracle_score_bruteforce")
     return scores
+
+
+PROBABILITIES, POSITIVE_LOGITS = 0, 1
+
+
+def score_blocks(Q: np.ndarray, K: np.ndarray, b: int, flags: int = CAUSAL | EXCLUDE_SELF, scale: float = 0.0,
+                 mode: int = PROBABILITIES):
+    """Block-wise informativeness (Sec. 4.2 Eq. 2) -> (score_blocks float64 [nb,nb], token_blocks float32 [nb])."""
+    S, H, Hkv, d, qts, qhs, kts, khs = _qk_layout(Q, K)
+    dt = _dtype_code(Q)
+    if _dtype_code(K) != dt:
+        raise TypeError("Q and K must share a dtype")
+    nb = (S + b - 1) // b
+    sb = np.empty((nb, nb), dtype=np.float64)
+    tb = np.empty(nb, dtype=np.float32)
+    _check(_load().oracle_score_blocks(_ptr(Q), _ptr(K), S, H, Hkv, d, dt, qts, qhs, kts, khs, float(scale), flags, b, mode,
+                                       _ptr(sb), _ptr(tb)), "oracle_score_blocks")
+    return sb, tb
+
+
+def select_threshold(token_blocks: np.ndarray, S: int, b: int, T: float) -> np.ndarray:
+    """Tokens of the token blocks whose score is >= T, ascending -> int32 [M]."""
+    token_blocks = np.ascontiguousarray(token_blocks, dtype=np.float32)
+    if token_blocks.shape != ((S + b - 1) // b,):
+        raise ValueError("token_blocks must be [ceil(S/b)]")
+    out = np.empty(S, dtype=np.int32)
+    n = _load().oracle_select_threshold(_ptr(token_blocks), S, b, float(T), _ptr(out))
+    if n < 0:
+        raise ValueError(f"oracle_select_threshold failed with oracle error {n}")
+    return out[:n].copy()
+
+
+def threshold_init(token_blocks: np.ndarray) -> float:
+    """Alg. 1 step 1: the mean token-block score."""
+    token_blocks = np.ascontiguousarray(token_blocks, dtype=np.float32)
+    return float(_load().oracle_threshold_init(_ptr(token_blocks), token_blocks.shape[0]))
 
 
 def select_topk(scores: np.ndarray, L: int, k: int) -> np.ndarray:

@@ -293,6 +293,130 @@ def test_keep_k_and_kept_count():
     assert oracle.kept_count(10, 4, 5) == -1
 
 
+# ------------------------------------------------------------------------------ block-wise informativeness, thresholds
+
+def dense_blocks(Q, K, b, flags, scale=None, mode=0):
+    """Dense numpy statement of Eq. 2 and the token-block sum (Sec. 4.2): per-head scores, positive terms summed over
+    heads and divided by the head count, zero where a pair is not admitted, padded to whole blocks, maximum over every
+    b x b block, column sums of the block matrix.  Q [S,H,d], K [S,H_kv,d] float64."""
+    S, H, d = Q.shape
+    Hkv = K.shape[1]
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    i, j = np.meshgrid(np.arange(S), np.arange(S), indexing="ij")
+    allowed = (j <= i) if flags & CAUSAL else np.ones((S, S), dtype=bool)
+    mean = np.zeros((S, S))
+    for h in range(H):
+        logits = scale * (Q[:, h, :] @ K[:, h * Hkv // H, :].T)
+        if mode == 0:
+            z = np.where(allowed, logits, -np.inf)
+            e = np.exp(z - z.max(axis=1, keepdims=True))
+            sc = e / e.sum(axis=1, keepdims=True)
+        else:
+            sc = logits
+        mean += np.where(allowed & (sc > 0), sc, 0.0)
+    mean /= H
+    admitted = allowed & ~((i == j) if flags & EXCLUDE_SELF else np.zeros((S, S), dtype=bool))
+    mean = np.where(admitted, mean, 0.0)
+    nb = -(-S // b)
+    padded = np.zeros((nb * b, nb * b))
+    padded[:S, :S] = mean
+    blocks = padded.reshape(nb, b, nb, b).max(axis=(1, 3))
+    return blocks, blocks.sum(axis=0)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("flags", [0, CAUSAL, EXCLUDE_SELF, CAUSAL | EXCLUDE_SELF])
+@pytest.mark.parametrize("S,H,Hkv,d,b,dtype", [(37, 2, 2, 8, 8, "f32"), (64, 4, 2, 16, 16, "bf16"), (50, 3, 1, 4, 7, "f32"),
+                                               (33, 1, 1, 8, 32, "bf16"), (20, 2, 1, 8, 1, "f32")])
+def test_blocks_against_dense_numpy(S, H, Hkv, d, b, dtype, flags, mode):
+    rng = np.random.default_rng(S * 7 + b)
+    Q = rng.standard_normal((S, H, d)).astype(np.float32)
+    K = (rng.standard_normal((S, Hkv, d)) * 1.5).astype(np.float32)
+    if dtype == "bf16":
+        Qin, Kin = bf16_bits(Q), bf16_bits(K)
+        Q, K = widen(Qin), widen(Kin)
+    else:
+        Qin, Kin = Q, K
+    want_sb, want_tb = dense_blocks(Q.astype(np.float64), K.astype(np.float64), b, flags, mode=mode)
+    sb, tb = oracle.score_blocks(Qin, Kin, b, flags=flags, mode=mode)
+    np.testing.assert_allclose(sb, want_sb, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(tb, want_tb, rtol=1e-6, atol=1e-12)
+    if mode == 1:  # a scale argument multiplies the logit variant through
+        sb2, _ = oracle.score_blocks(Qin, Kin, b, flags=flags, mode=1, scale=0.5)
+        np.testing.assert_allclose(sb2, want_sb * 0.5 * math.sqrt(d), rtol=1e-12, atol=1e-15)
+
+
+def test_blocks_golden_four_token_example():
+    """Hand-derived example (tests/golden/score_blocks_four_tokens.txt): zero queries, causal, one head, b = 2."""
+    rows = {l.split()[0]: [float(x) for x in l.split()[1:]]
+            for l in open(os.path.join(GOLDEN, "score_blocks_four_tokens.txt")) if l.strip() and not l.startswith("#")}
+    Q = np.zeros((4, 1, 4), dtype=np.float32)
+    K = np.random.default_rng(1).standard_normal((4, 1, 4)).astype(np.float32)
+    sb, tb = oracle.score_blocks(Q, K, 2, flags=CAUSAL)
+    np.testing.assert_allclose(sb.ravel(), rows["score_blocks_causal"], rtol=1e-15)
+    np.testing.assert_allclose(tb, rows["token_blocks_causal"], rtol=1e-7)
+    sb, tb = oracle.score_blocks(Q, K, 2, flags=CAUSAL | EXCLUDE_SELF)
+    np.testing.assert_allclose(sb.ravel(), rows["score_blocks_causal_exclude_self"], rtol=1e-15)
+    np.testing.assert_allclose(tb, rows["token_blocks_causal_exclude_self"], rtol=1e-7)
+    for flags in (0, EXCLUDE_SELF):
+        np.testing.assert_allclose(oracle.score_blocks(Q, K, 2, flags=flags)[1], rows["token_blocks_full"], rtol=1e-7)
+
+
+def test_blocks_special_cases():
+    rng = np.random.default_rng(31)
+    S, H, d = 96, 4, 16
+    Q = rng.standard_normal((S, H, d)).astype(np.float32)
+    K = rng.standard_normal((S, 2, d)).astype(np.float32)
+    for flags in (0, CAUSAL, CAUSAL | EXCLUDE_SELF):
+        # blocks of one token: the token-block score is Eq. 1's column sum (head mean), already pinned above
+        np.testing.assert_allclose(oracle.score_blocks(Q, K, 1, flags=flags)[1], oracle.score(Q, K, flags=flags), rtol=1e-6, atol=1e-9)
+        # one block holding everything: its score is the largest admitted head-mean probability
+        sb, tb = oracle.score_blocks(Q, K, S, flags=flags)
+        assert sb.shape == (1, 1) and np.float32(sb[0, 0]) == tb[0]
+        assert sb[0, 0] == pytest.approx(dense_blocks(Q.astype(np.float64), K.astype(np.float64), 1, flags)[0].max(), rel=1e-12)
+    # closed form for constant logits under a causal mask: row i holds 1/(i+1) on its allowed keys, so a score block
+    # below the diagonal is worth 1/(m*b+1), the diagonal one 1/(n*b+1) (1/(n*b+2) once self pairs are left out)
+    b, nb = 8, S // 8
+    Z = np.zeros_like(Q)
+    _, tb = oracle.score_blocks(Z, K, b, flags=CAUSAL)
+    want = [sum(1.0 / (m * b + 1) for m in range(n, nb)) for n in range(nb)]
+    np.testing.assert_allclose(tb, want, rtol=1e-6)
+    _, tb = oracle.score_blocks(Z, K, b, flags=CAUSAL | EXCLUDE_SELF)
+    want = [1.0 / (n * b + 2) + sum(1.0 / (m * b + 1) for m in range(n + 1, nb)) for n in range(nb)]
+    np.testing.assert_allclose(tb, want, rtol=1e-6)
+    # logit variant: only positive logits count, so negating K flips which pairs contribute; all-negative logits give 0
+    Qp, Kp = np.abs(Q), np.abs(K)
+    assert not oracle.score_blocks(Qp, -Kp, b, flags=0, mode=1)[1].any()
+    assert (oracle.score_blocks(Qp, Kp, b, flags=0, mode=1)[1] > 0).all()
+    # head order does not matter; a KV head shared by two query heads is the same as two equal KV heads
+    perm = [2, 3, 0, 1]
+    np.testing.assert_allclose(oracle.score_blocks(Q[:, perm], K[:, [1, 0]], b)[1], oracle.score_blocks(Q, K, b)[1], rtol=1e-6)
+    np.testing.assert_array_equal(oracle.score_blocks(Q, np.repeat(K, 2, axis=1), b)[1], oracle.score_blocks(Q, K, b)[1])
+
+
+def test_threshold_selection_and_initial_threshold():
+    rng = np.random.default_rng(32)
+    for S, b in ((100, 8), (64, 16), (7, 32), (33, 1)):
+        nb = -(-S // b)
+        tb = rng.random(nb).astype(np.float32)
+        T = float(np.sort(tb)[nb // 2])  # a value that occurs: equality keeps the block
+        want = np.nonzero(np.repeat(tb >= np.float32(T), b)[:S])[0]
+        got = oracle.select_threshold(tb, S, b, T)
+        np.testing.assert_array_equal(got, want)
+        assert got.dtype == np.int32
+        assert len(oracle.select_threshold(tb, S, b, -np.inf)) == S
+        assert len(oracle.select_threshold(tb, S, b, np.inf)) == 0
+        assert oracle.threshold_init(tb) == pytest.approx(float(np.mean(tb.astype(np.float64))), rel=1e-12)
+    # Alg. 1 step 1 on real block scores: the mean threshold keeps some blocks and drops some
+    Q = rng.standard_normal((128, 2, 8)).astype(np.float32)
+    K = rng.standard_normal((128, 2, 8)).astype(np.float32)
+    K[40:48] *= 4.0
+    _, tb = oracle.score_blocks(Q, K, 8)
+    kept = oracle.select_threshold(tb, 128, 8, oracle.threshold_init(tb))
+    assert 0 < len(kept) < 128 and len(kept) % 8 == 0
+    assert set(range(40, 48)) <= set(kept.tolist())  # the block with the strong keys survives
+
+
 # ------------------------------------------------------------------------------ gather-GEMM
 
 def test_gemm_exact_on_dyadic_grid():
