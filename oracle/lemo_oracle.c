@@ -214,6 +214,40 @@ int oracle_score(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_k
  * take no part in the maximum; a block with no admissible pair scores 0.  Ragged last blocks are
  * simply shorter.  score_blocks ([nb,nb] doubles, row m, column n; may be NULL) and token_blocks
  * ([nb] floats, one rounding from double), nb = ceil(S / b). */
+/* One query i of the block-wise score: the head aggregate mean[j] over the allowed keys, folded into the
+ * running maxima best[j / b] of the query's block row.  Qh[h] / Kh[g] are the heads widened to double; Qh
+ * rows are indexed from q_first (a caller may have widened only the rows it needs).  `mean` and `row` are
+ * O(S) buffers. */
+static void score_block_query(double* const* Qh, int64_t q_first, double* const* Kh, int64_t S, int32_t H, int32_t H_kv,
+                              int32_t d, double scale, int causal, int excl, int32_t b, int mode, int64_t i, double* mean,
+                              double* row, double* best) {
+    int64_t nk = causal ? i + 1 : S;
+    for (int64_t j = 0; j < nk; ++j) mean[j] = 0.0;
+    for (int h = 0; h < H; ++h) {
+        const double* q = Qh[h] + (i - q_first) * d;
+        const double* kk = Kh[(int)(((int64_t)h * H_kv) / H)];
+        double mx = -INFINITY;
+        for (int64_t j = 0; j < nk; ++j) {
+            double dot = 0.0;
+            for (int c = 0; c < d; ++c) dot += q[c] * kk[j * d + c];
+            row[j] = scale * dot;
+            if (row[j] > mx) mx = row[j];
+        }
+        if (mode == 0) { /* softmax probabilities */
+            double den = 0.0;
+            for (int64_t j = 0; j < nk; ++j) { row[j] = exp(row[j] - mx); den += row[j]; }
+            for (int64_t j = 0; j < nk; ++j) row[j] /= den;
+        }
+        for (int64_t j = 0; j < nk; ++j)
+            if (row[j] > 0.0) mean[j] += row[j]; /* only positive scores are aggregated */
+    }
+    for (int64_t j = 0; j < nk; ++j) {
+        if (excl && j == i) continue;
+        double v = mean[j] / (double)H;
+        if (v > best[j / b]) best[j / b] = v;
+    }
+}
+
 int oracle_score_blocks(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, int dtype,
                         int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
                         double scale, uint32_t flags, int32_t b, int mode, double* score_blocks, float* token_blocks) {
@@ -235,36 +269,9 @@ int oracle_score_blocks(const void* Q, const void* K, int64_t S, int32_t H, int3
 #pragma omp parallel for schedule(dynamic, 1) num_threads(nthr)
         for (int64_t m = nb - 1; m >= 0; --m) { /* block rows are independent; late rows are the long ones */
             double* mean = work + 2 * (size_t)omp_get_thread_num() * (size_t)S;
-            double* row = mean + S;
             int64_t i_end = (m + 1) * b < S ? (m + 1) * b : S;
-            for (int64_t i = m * b; i < i_end; ++i) {
-                int64_t nk = causal ? i + 1 : S;
-                for (int64_t j = 0; j < nk; ++j) mean[j] = 0.0;
-                for (int h = 0; h < H; ++h) {
-                    const double* q = Qh[h] + i * d;
-                    const double* kk = Kh[(int)(((int64_t)h * H_kv) / H)];
-                    double mx = -INFINITY;
-                    for (int64_t j = 0; j < nk; ++j) {
-                        double dot = 0.0;
-                        for (int c = 0; c < d; ++c) dot += q[c] * kk[j * d + c];
-                        row[j] = scale * dot;
-                        if (row[j] > mx) mx = row[j];
-                    }
-                    if (mode == 0) {
-                        double den = 0.0;
-                        for (int64_t j = 0; j < nk; ++j) { row[j] = exp(row[j] - mx); den += row[j]; }
-                        for (int64_t j = 0; j < nk; ++j) row[j] /= den;
-                    }
-                    for (int64_t j = 0; j < nk; ++j)
-                        if (row[j] > 0.0) mean[j] += row[j];
-                }
-                for (int64_t j = 0; j < nk; ++j) {
-                    if (excl && j == i) continue;
-                    double v = mean[j] / (double)H;
-                    double* slot = best + m * nb + j / b;
-                    if (v > *slot) *slot = v;
-                }
-            }
+            for (int64_t i = m * b; i < i_end; ++i)
+                score_block_query(Qh, 0, Kh, S, H, H_kv, d, scale, causal, excl, b, mode, i, mean, mean + S, best + m * nb);
         }
         for (int64_t n = 0; n < nb; ++n) {
             double acc = 0.0;
@@ -276,6 +283,54 @@ int oracle_score_blocks(const void* Q, const void* K, int64_t S, int32_t H, int3
     for (int h = 0; Qh && h < H; ++h) free(Qh[h]);
     for (int g = 0; Kh && g < H_kv; ++g) free(Kh[g]);
     free(Qh); free(Kh); free(best); free(work);
+    return ok ? ORACLE_OK : ORACLE_ERR_NOMEM;
+}
+
+/* The score blocks I(B^S_mn), n < nb, of the listed block rows only (row_out is [n_rows, nb]): the same
+ * arithmetic as oracle_score_blocks, for spot checks at sizes where the whole matrix would take hours. */
+int oracle_score_block_rows(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, int dtype,
+                            int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                            double scale, uint32_t flags, int32_t b, int mode, const int64_t* rows, int32_t n_rows, double* row_out) {
+    if (!Q || !K || !rows || !row_out || S <= 0 || H <= 0 || H_kv <= 0 || d <= 0 || H % H_kv || b <= 0 || n_rows < 0) return ORACLE_ERR_ARG;
+    if ((dtype != ORACLE_F32 && dtype != ORACLE_BF16) || (mode != 0 && mode != 1)) return ORACLE_ERR_ARG;
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)d);
+    const int64_t nb = (S + b - 1) / b;
+    for (int32_t t = 0; t < n_rows; ++t)
+        if (rows[t] < 0 || rows[t] >= nb) return ORACLE_ERR_ARG;
+    double** Qh = (double**)calloc((size_t)H, sizeof(double*));
+    double** Kh = (double**)calloc((size_t)H_kv, sizeof(double*));
+    int ok = Qh && Kh;
+    for (int g = 0; ok && g < H_kv; ++g) ok = (Kh[g] = widen_head(K, S, d, dtype, k_tok_stride, (int64_t)g * k_head_stride)) != NULL;
+    memset(row_out, 0, sizeof(double) * (size_t)n_rows * (size_t)nb);
+    for (int32_t t = 0; ok && t < n_rows; ++t) {
+        const int64_t m = rows[t], first = m * b, len = ((m + 1) * b < S ? (m + 1) * b : S) - first;
+        for (int h = 0; ok && h < H; ++h) /* only this block row's queries are widened */
+            ok = (Qh[h] = widen_head(Q, len, d, dtype, q_tok_stride, first * q_tok_stride + (int64_t)h * q_head_stride)) != NULL;
+        if (ok) {
+            /* the queries of the row are independent: each thread keeps its own maxima, merged afterwards */
+            const int nthr = omp_get_max_threads();
+            const size_t per = (size_t)(2 * S + nb);
+            double* work = (double*)calloc((size_t)nthr * per, sizeof(double));
+            if (!work) ok = 0;
+            if (ok) {
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthr)
+                for (int64_t i = first; i < first + len; ++i) {
+                    double* mine = work + (size_t)omp_get_thread_num() * per;
+                    score_block_query(Qh, first, Kh, S, H, H_kv, d, scale, (flags & ORACLE_CAUSAL) != 0,
+                                      (flags & ORACLE_EXCLUDE_SELF) != 0, b, mode, i, mine + nb, mine + nb + S, mine);
+                }
+                for (int th = 0; th < nthr; ++th)
+                    for (int64_t n = 0; n < nb; ++n) {
+                        double v = work[(size_t)th * per + n];
+                        if (v > row_out[(size_t)t * nb + n]) row_out[(size_t)t * nb + n] = v;
+                    }
+            }
+            free(work);
+        }
+        for (int h = 0; h < H; ++h) { free(Qh[h]); Qh[h] = NULL; }
+    }
+    for (int g = 0; Kh && g < H_kv; ++g) free(Kh[g]);
+    free(Qh); free(Kh);
     return ok ? ORACLE_OK : ORACLE_ERR_NOMEM;
 }
 

@@ -49,6 +49,8 @@ def _load():
             lib.oracle_score_bruteforce.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, dbl, u32, vp]
             lib.oracle_score_blocks.restype = ctypes.c_int
             lib.oracle_score_blocks.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, dbl, u32, i32, ctypes.c_int, vp, vp]
+            lib.oracle_score_block_rows.restype = ctypes.c_int
+            lib.oracle_score_block_rows.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, dbl, u32, i32, ctypes.c_int, vp, i32, vp]
             lib.oracle_select_threshold.restype = i64
             lib.oracle_select_threshold.argtypes = [vp, i64, i32, dbl, vp]
             lib.oracle_threshold_init.restype = dbl
@@ -179,6 +181,18 @@ def score_blocks(Q: np.ndarray, K: np.ndarray, b: int, flags: int = CAUSAL | EXC
     _check(_load().oracle_score_blocks(_ptr(Q), _ptr(K), S, H, Hkv, d, dt, qts, qhs, kts, khs, float(scale), flags, b, mode,
                                        _ptr(sb), _ptr(tb)), "oracle_score_blocks")
     return sb, tb
+
+
+def score_block_rows(Q: np.ndarray, K: np.ndarray, b: int, rows, flags: int = CAUSAL | EXCLUDE_SELF, scale: float = 0.0,
+                     mode: int = PROBABILITIES) -> np.ndarray:
+    """Rows `rows` of the score-block matrix only -> float64 [len(rows), nb] (spot checks at large S)."""
+    S, H, Hkv, d, qts, qhs, kts, khs = _qk_layout(Q, K)
+    dt = _dtype_code(Q)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    out = np.empty((len(rows), (S + b - 1) // b), dtype=np.float64)
+    _check(_load().oracle_score_block_rows(_ptr(Q), _ptr(K), S, H, Hkv, d, dt, qts, qhs, kts, khs, float(scale), flags, b, mode,
+                                           _ptr(rows), len(rows), _ptr(out)), "oracle_score_block_rows")
+    return out
 
 
 def select_threshold(token_blocks: np.ndarray, S: int, b: int, T: float) -> np.ndarray:

@@ -341,6 +341,8 @@ def test_blocks_against_dense_numpy(S, H, Hkv, d, b, dtype, flags, mode):
     sb, tb = oracle.score_blocks(Qin, Kin, b, flags=flags, mode=mode)
     np.testing.assert_allclose(sb, want_sb, rtol=1e-12, atol=1e-15)
     np.testing.assert_allclose(tb, want_tb, rtol=1e-6, atol=1e-12)
+    rows = [0, sb.shape[0] - 1, sb.shape[0] // 2]  # the spot-check routine is the same arithmetic, row by row
+    np.testing.assert_array_equal(oracle.score_block_rows(Qin, Kin, b, rows, flags=flags, mode=mode), sb[rows])
     if mode == 1:  # a scale argument multiplies the logit variant through
         sb2, _ = oracle.score_blocks(Qin, Kin, b, flags=flags, mode=1, scale=0.5)
         np.testing.assert_allclose(sb2, want_sb * 0.5 * math.sqrt(d), rtol=1e-12, atol=1e-15)
