@@ -151,6 +151,40 @@ def measure_fused_output_projection(cfg, lemo, ev, stream, kept, reps=10):
             "unfused_ms": round(t_unfused, 5), "bytes_saved": 2.0 * M * C * esz}
 
 
+def measure_block_scoring(cfg, lemo, ev, stream, Q, K, lse2, flags, b=64, reps=5):
+    """Outside the timed step: the paper's own criterion (Sec. 4.2 Eq. 2): block-wise informativeness with b x b score
+    blocks from the row statistics sweep 1 already produced, then the initial threshold of Alg. 1 and the threshold
+    selection.  Same flop count as one sweep of the token-wise score (every allowed pair, every head, once)."""
+    import torch
+    S, H = cfg.S, cfg.H
+    nb = (S + b - 1) // b
+    tb = torch.empty(nb, dtype=torch.float32, device="cuda")
+    ws = torch.empty(lemo.lemo_score_blocks_workspace_bytes(S, H), dtype=torch.uint8, device="cuda")
+    T0 = torch.empty(1, dtype=torch.float32, device="cuda")
+    kept = torch.empty(S, dtype=torch.int32, device="cuda")
+    count = torch.empty(1, dtype=torch.int32, device="cuda")
+
+    def run(marks=None):
+        if marks: ev.record(marks[0], stream)
+        lemo.lemo_score_blocks(Q, K, b, flags=flags, lse2=lse2, want_score_blocks=False, token_blocks=tb, workspace=ws)
+        if marks: ev.record(marks[1], stream)
+        lemo.lemo_threshold_init(tb, T0)
+        lemo.lemo_select_threshold(tb, S, b, T0, kept_idx=kept, kept_count=count)
+        if marks: ev.record(marks[2], stream)
+
+    run()
+    marks = [[ev.create() for _ in range(3)] for _ in range(reps)]
+    for i in range(reps):
+        run(marks[i])
+    torch.cuda.synchronize()
+    t_blocks = sum(ev.elapsed_ms(m[0], m[1]) for m in marks) / reps
+    t_sel = sum(ev.elapsed_ms(m[1], m[2]) for m in marks) / reps
+    flops = 2.0 * cfg.d * H * S * (S + 1) / 2
+    return {"what": f"block-wise informativeness, {b}x{b} score blocks, all {H} heads, then mean threshold + threshold selection",
+            "score_blocks_ms": round(t_blocks, 5), "score_blocks_tflops": round(flops / t_blocks * 1e-9, 2),
+            "threshold_select_ms": round(t_sel, 5), "kept_tokens": int(count.item())}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -281,6 +315,7 @@ def main():
         "phases": report,
     }
     out["fused_in_place_add"] = measure_fused_output_projection(cfg, lemo, ev, stream, kept)
+    out["block_wise"] = measure_block_scoring(cfg, lemo, ev, stream, Q, K, lse2, flags)
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         out["cpu_baseline"] = cpu_baseline(cfg, lay, wl)

@@ -143,6 +143,54 @@ int lemo_score_head_mean(const float* colsum_per_head, const float* diag_per_hea
 int lemo_select_topk(const float* scores, int64_t S, int32_t L, int32_t k, int32_t* kept_idx, void* stream);
 
 /*
+ * Block-wise informativeness (Sec. 4.2 "Block-wise Elimination", Eq. 2, and the token-block scores of
+ * "Layer-specific Threshold"):
+ *
+ *     mean[i][j]        = (1/H) * sum over heads h with S^h_ij > 0 of S^h_ij
+ *     score_blocks[m,n] = max of mean[i][j] over i in [m*b,(m+1)*b), j in [n*b,(n+1)*b)      I(B^S_mn)
+ *     token_blocks[n]   = sum over m of score_blocks[m,n]                                     B^T_n
+ *
+ * mode LEMO_BLOCKS_PROBABILITIES:   S^h_ij is the softmax probability (the reading of Eq. 1 used by
+ *                                   lemo_score_segments; the positivity condition is then vacuous);
+ * mode LEMO_BLOCKS_POSITIVE_LOGITS: S^h_ij = scale * <Q_i, K_j>, pre-softmax, positive terms only.
+ * Pairs the causal mask forbids (LEMO_CAUSAL: j > i) and, with LEMO_EXCLUDE_SELF, the pairs i == j take
+ * no part in the maximum; a block without an admitted pair scores 0.  nb = ceil(S / b); a ragged last
+ * block is shorter.
+ *
+ *   Q, K, strides, scale, flags: as for lemo_score_segments.
+ *   b: score-block edge in tokens, a multiple of 32 (LEMO_ERR_UNSUPPORTED otherwise).
+ *   lse2 [H,S] or NULL: the row statistics lemo_score_rowstats produced for the same Q, K, scale and
+ *        flags.  NULL (probabilities mode) makes this call compute them first.  Ignored for logits.
+ *   score_blocks [nb,nb] fp32, row m = query block, or NULL;  token_blocks [nb] fp32.
+ *   workspace: at least lemo_score_blocks_workspace_bytes(S,H) bytes, 256-byte aligned, device memory.
+ *
+ * fp32 arithmetic; deterministic and repeatable.  Same tolerance against an fp64 evaluation as the
+ * token-wise scores (2e-3 relative).
+ */
+enum { LEMO_BLOCKS_PROBABILITIES = 0, LEMO_BLOCKS_POSITIVE_LOGITS = 1 };
+int lemo_score_blocks_workspace_bytes(int64_t S, int32_t H, size_t* bytes);
+int lemo_score_blocks(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt,
+                      int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                      float scale, int32_t b, uint32_t flags, int32_t mode, const float* lse2, float* score_blocks,
+                      float* token_blocks, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Selection by threshold (Sec. 4.2 "Layer-specific Threshold"): token block n is kept iff
+ * token_blocks[n] >= T; the indices of all tokens of the kept blocks are written in ascending order to
+ * kept_idx[0 .. count) and count to *kept_count (both device memory; kept_idx must have room for S
+ * entries, entries past count are left as they were).  T is `threshold`, or, when threshold_dev is not
+ * NULL, the float it points to in device memory (so that lemo_threshold_init can feed it without a
+ * host round trip).  The number of kept rows is data dependent: read *kept_count back before sizing
+ * the consumer call.  Supported: ceil(S / b) <= 16384.  Bit-exact and deterministic.
+ *
+ * lemo_threshold_init: step 1 of Alg. 1, the layer's initial threshold = the mean of its token-block
+ * scores, written to *threshold (device memory).
+ */
+int lemo_threshold_init(const float* token_blocks, int64_t nb, float* threshold, void* stream);
+int lemo_select_threshold(const float* token_blocks, int64_t S, int32_t b, float threshold, const float* threshold_dev,
+                          int32_t* kept_idx, int32_t* kept_count, void* stream);
+
+/*
  * Selective-load GEMM (Sec. 4.4, permutation-free token movement: the consumer reads the kept rows
  * from the original [S,C] input; no compacted copy of X is made):
  *

@@ -168,6 +168,72 @@ int lemo_select_topk(const float* scores, int64_t S, int32_t L, int32_t k, int32
     return launch_select(scores, (int)S, L, k, kept_idx, static_cast<hipStream_t>(stream)) == 0 ? LEMO_OK : LEMO_ERR_HIP;
 }
 
+int lemo_score_blocks_workspace_bytes(int64_t S, int32_t H, size_t* bytes) {
+    if (!bytes) return LEMO_ERR_NULL;
+    if (S <= 0 || S >= (int64_t)1 << 31 || H <= 0) return LEMO_ERR_SHAPE;
+    const size_t nt32 = (size_t)((S + 31) / 32);
+    *bytes = round_up((size_t)H * (size_t)S * sizeof(float), 256) + round_up(nt32 * nt32 * sizeof(float), 256);
+    return LEMO_OK;
+}
+
+int lemo_score_blocks(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt,
+                      int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride, float scale,
+                      int32_t b, uint32_t flags, int32_t mode, const float* lse2, float* score_blocks, float* token_blocks,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    ScoreParams sp;
+    const int rc = check_qk(Q, K, S, H, H_kv, d, dt, q_tok_stride, q_head_stride, k_tok_stride, k_head_stride, scale, flags, sp);
+    if (rc != LEMO_OK) return rc;
+    if (!token_blocks || !workspace) return LEMO_ERR_NULL;
+    if (mode != LEMO_BLOCKS_PROBABILITIES && mode != LEMO_BLOCKS_POSITIVE_LOGITS) return LEMO_ERR_SHAPE;
+    if (b <= 0) return LEMO_ERR_SHAPE;
+    if (b % 32) return LEMO_ERR_UNSUPPORTED;
+    size_t need = 0;
+    lemo_score_blocks_workspace_bytes(S, H, &need);
+    if (workspace_bytes < need) return LEMO_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return LEMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* lse_ws = static_cast<float*>(workspace);
+    float* tiles = reinterpret_cast<float*>(static_cast<char*>(workspace) + round_up((size_t)H * (size_t)S * sizeof(float), 256));
+    if (mode == LEMO_BLOCKS_PROBABILITIES && !lse2) {  // sweep 1 of the token-wise score supplies the row statistics
+        sp.lse2 = lse_ws;
+        if (launch_score(sp, dt, d, 1, st) != 0) return LEMO_ERR_HIP;
+        lse2 = lse_ws;
+    }
+    BlockParams p{};
+    p.Q = Q;
+    p.K = K;
+    p.S = (int)S;
+    p.H = H;
+    p.H_kv = H_kv;
+    p.q_ts = q_tok_stride;
+    p.q_hs = q_head_stride;
+    p.k_ts = k_tok_stride;
+    p.k_hs = k_head_stride;
+    p.c2 = sp.c2;
+    const double sc = scale > 0.f ? (double)scale : 1.0 / std::sqrt((double)d);
+    p.out_scale = mode == LEMO_BLOCKS_PROBABILITIES ? (float)(1.0 / H) : (float)(sc / H);
+    p.flags = flags;
+    p.lse2 = lse2;
+    p.tilemax = tiles;
+    return hip_rc(launch_score_blocks(p, dt, d, mode, b, score_blocks, token_blocks, st));
+}
+
+int lemo_threshold_init(const float* token_blocks, int64_t nb, float* threshold, void* stream) {
+    if (!token_blocks || !threshold) return LEMO_ERR_NULL;
+    if (nb <= 0 || nb >= (int64_t)1 << 31) return LEMO_ERR_SHAPE;
+    return hip_rc(launch_block_mean(token_blocks, (int)nb, threshold, static_cast<hipStream_t>(stream)));
+}
+
+int lemo_select_threshold(const float* token_blocks, int64_t S, int32_t b, float threshold, const float* threshold_dev,
+                          int32_t* kept_idx, int32_t* kept_count, void* stream) {
+    if (!token_blocks || !kept_idx || !kept_count) return LEMO_ERR_NULL;
+    if (S <= 0 || S >= (int64_t)1 << 31 || b <= 0) return LEMO_ERR_SHAPE;
+    if (!threshold_dev && std::isnan(threshold)) return LEMO_ERR_SHAPE;
+    if ((S + b - 1) / b > 16384) return LEMO_ERR_UNSUPPORTED;
+    return hip_rc(launch_select_threshold(token_blocks, (int)S, b, threshold, threshold_dev, kept_idx, kept_count,
+                                          static_cast<hipStream_t>(stream)));
+}
+
 int lemo_gather_gemm(const void* X, int64_t S, int64_t ldx, const int32_t* kept_idx, int64_t M, const void* W, int64_t ldw,
                      const void* bias, void* Y, int64_t ldy, int32_t C, int32_t N, lemo_dtype_t dt, void* stream) {
     if (!valid_dtype(dt)) return LEMO_ERR_DTYPE;

@@ -79,9 +79,29 @@ struct ScoreParams {
     float* scores;  // [S]
 };
 
+struct BlockParams {
+    const void* Q;
+    const void* K;
+    int S, H, H_kv;
+    long long q_ts, q_hs, k_ts, k_hs;  // element strides
+    float c2;           // probabilities: scale * log2(e)
+    float out_scale;    // probabilities: 1/H;  positive logits: scale / H
+    unsigned flags;
+    const float* lse2;  // [H,S] row statistics (probabilities only)
+    float* tilemax;     // [nt32, nt32] maxima of the 32 x 32 tiles
+    int nt32;           // ceil(S / 32)
+    int nt;             // rectangles per side
+    int nsp;            // super-patches per side
+};
+
 // kernel launchers (defined next to their kernels; return hipError_t as int)
 int launch_score(const ScoreParams& p, lemo_dtype_t dt, int d, int which, hipStream_t st);  // which: 1 row stats | 2 column sums | 4 head mean
+int launch_score_blocks(const BlockParams& p, lemo_dtype_t dt, int d, int mode, int b, float* score_blocks, float* token_blocks,
+                        hipStream_t st);  // mode 0: probabilities (p.lse2 filled), 1: positive logits
 int launch_select(const float* scores, int S, int L, int k, int* kept, hipStream_t st);
+int launch_block_mean(const float* token_blocks, int nb, float* out, hipStream_t st);
+int launch_select_threshold(const float* token_blocks, int S, int b, float t_host, const float* t_dev, int* kept, int* kept_count,
+                            hipStream_t st);
 int launch_scatter(const void* G, long long ldg, const int* idx, long long M, void* dX, long long lddx, long long S,
                    int C, lemo_dtype_t g_dt, lemo_dtype_t dx_dt, int mode, hipStream_t st);
 int launch_gather_gemm(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W,

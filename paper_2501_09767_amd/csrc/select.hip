@@ -105,6 +105,75 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Threshold selection over token blocks (Sec. 4.2 "Layer-specific Threshold"; Alg. 1 step 1).
+// ------------------------------------------------------------------------------------------------
+
+// mean of the token-block scores: one workgroup, per-thread partial sums in index order, fixed-order tree
+__global__ __launch_bounds__(256) void block_mean_kernel(const float* __restrict__ token_blocks, int nb, float* __restrict__ out) {
+    __shared__ float part[256];
+    const int tid = threadIdx.x;
+    float s = 0.f;
+    for (int n = tid; n < nb; n += 256) s += token_blocks[n];
+    part[tid] = s;
+    __syncthreads();
+    for (int k = 128; k >= 1; k >>= 1) {
+        if (tid < k) part[tid] += part[tid + k];
+        __syncthreads();
+    }
+    if (tid == 0) out[0] = part[0] / (float)nb;
+}
+
+// One workgroup.  Phase 1: start[n] = number of kept tokens in blocks before n (prefix sum over the kept blocks'
+// lengths, carried from chunk to chunk of 1024 blocks).  Phase 2: every token of a kept block writes its own index.
+constexpr int THR_THREADS = 1024;
+__global__ __launch_bounds__(THR_THREADS) void select_threshold_kernel(const float* __restrict__ token_blocks, int S, int b, int nb,
+                                                                       float t_host, const float* __restrict__ t_dev,
+                                                                       int* __restrict__ kept, int* __restrict__ kept_count) {
+    extern __shared__ int start[];  // [nb]; -1 marks a dropped block
+    __shared__ int scan[THR_THREADS];
+    __shared__ int base;
+    const int tid = threadIdx.x;
+    const float T = t_dev ? t_dev[0] : t_host;
+    if (tid == 0) base = 0;
+    __syncthreads();
+    for (int n0 = 0; n0 < nb; n0 += THR_THREADS) {
+        const int n = n0 + tid;
+        int len = 0;
+        if (n < nb && token_blocks[n] >= T) len = min(b, S - n * b);
+        scan[tid] = len;
+        __syncthreads();
+        for (int off = 1; off < THR_THREADS; off <<= 1) {
+            const int v = tid >= off ? scan[tid - off] : 0;
+            __syncthreads();
+            scan[tid] += v;
+            __syncthreads();
+        }
+        if (n < nb) start[n] = len ? base + scan[tid] - len : -1;
+        __syncthreads();
+        if (tid == 0) base += scan[THR_THREADS - 1];
+        __syncthreads();
+    }
+    if (tid == 0) kept_count[0] = base;
+    for (int j = tid; j < S; j += THR_THREADS) {
+        const int n = j / b;
+        if (start[n] >= 0) kept[start[n] + (j - n * b)] = j;
+    }
+}
+
+int launch_block_mean(const float* token_blocks, int nb, float* out, hipStream_t st) {
+    hipLaunchKernelGGL(block_mean_kernel, dim3(1), dim3(256), 0, st, token_blocks, nb, out);
+    return (int)hipGetLastError();
+}
+
+int launch_select_threshold(const float* token_blocks, int S, int b, float t_host, const float* t_dev, int* kept, int* kept_count,
+                            hipStream_t st) {
+    const int nb = (S + b - 1) / b;  // host checked: nb <= 16384, the offsets fit the default dynamic LDS limit
+    hipLaunchKernelGGL(select_threshold_kernel, dim3(1), dim3(THR_THREADS), (size_t)nb * sizeof(int), st, token_blocks, S, b, nb, t_host,
+                       t_dev, kept, kept_count);
+    return (int)hipGetLastError();
+}
+
 int launch_select(const float* scores, int S, int L, int k, int* kept, hipStream_t st) {
     const int Leff = L < S ? L : S;
     const int nseg = (S + L - 1) / L;  // L <= 8192 here (keys of one segment live in LDS), no overflow

@@ -22,7 +22,8 @@ LIB_PATH = os.path.join(_HERE, "liblemo_hip.so")
 
 EXPORTS = ("lemo_strerror", "lemo_keep_k", "lemo_kept_count", "lemo_score_workspace_bytes",
            "lemo_score_segments", "lemo_score_rowstats", "lemo_score_colsums", "lemo_score_head_mean",
-           "lemo_select_topk", "lemo_gather_gemm", "lemo_gather_gemm_add", "lemo_scatter_grad")
+           "lemo_select_topk", "lemo_gather_gemm", "lemo_gather_gemm_add", "lemo_scatter_grad",
+           "lemo_score_blocks_workspace_bytes", "lemo_score_blocks", "lemo_threshold_init", "lemo_select_threshold")
 
 
 class LemoError(RuntimeError):
@@ -54,6 +55,15 @@ def _load() -> ctypes.CDLL:
     lib.lemo_score_colsums.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, f32, i32, u32, vp, vp, vp, vp]
     lib.lemo_score_head_mean.restype = ctypes.c_int
     lib.lemo_score_head_mean.argtypes = [vp, vp, i64, i32, u32, vp, vp]
+    lib.lemo_score_blocks_workspace_bytes.restype = ctypes.c_int
+    lib.lemo_score_blocks_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.lemo_score_blocks.restype = ctypes.c_int
+    lib.lemo_score_blocks.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, f32, i32, u32, i32,
+                                      vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.lemo_threshold_init.restype = ctypes.c_int
+    lib.lemo_threshold_init.argtypes = [vp, i64, vp, vp]
+    lib.lemo_select_threshold.restype = ctypes.c_int
+    lib.lemo_select_threshold.argtypes = [vp, i64, i32, f32, vp, vp, vp, vp]
     lib.lemo_select_topk.restype = ctypes.c_int
     lib.lemo_select_topk.argtypes = [vp, i64, i32, i32, vp, vp]
     lib.lemo_gather_gemm.restype = ctypes.c_int
@@ -193,6 +203,85 @@ def lemo_score_head_mean(colsum_per_head: torch.Tensor, diag_per_head: torch.Ten
         raise ValueError("scores must be contiguous float32 [S] on the GPU")
     _check(_lib.lemo_score_head_mean(_ptr(col), _ptr(dg), S, H, int(flags), _ptr(scores), _stream()), "lemo_score_head_mean")
     return scores
+
+
+BLOCKS_PROBABILITIES, BLOCKS_POSITIVE_LOGITS = 0, 1
+
+
+def lemo_score_blocks_workspace_bytes(S: int, H: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.lemo_score_blocks_workspace_bytes(S, H, ctypes.byref(n)), "lemo_score_blocks_workspace_bytes")
+    return int(n.value)
+
+
+def lemo_score_blocks(Q: torch.Tensor, K: torch.Tensor, b: int, flags: int = CAUSAL | EXCLUDE_SELF, scale: float = 0.0,
+                      mode: int = BLOCKS_PROBABILITIES, lse2: Optional[torch.Tensor] = None, want_score_blocks: bool = True,
+                      score_blocks: Optional[torch.Tensor] = None, token_blocks: Optional[torch.Tensor] = None,
+                      workspace: Optional[torch.Tensor] = None):
+    """Block-wise informativeness -> (score_blocks [nb,nb] float32 or None, token_blocks [nb] float32), nb = ceil(S/b)."""
+    a = _qk_args(Q, K)
+    S, H = a[2], a[3]
+    nb = (S + b - 1) // b if b > 0 else 0
+    if lse2 is not None:
+        lse2 = _plane(lse2, H, S, Q.device)
+    if score_blocks is None and want_score_blocks:
+        score_blocks = torch.empty((nb, nb), dtype=torch.float32, device=Q.device)
+    if token_blocks is None:
+        token_blocks = torch.empty(nb, dtype=torch.float32, device=Q.device)
+    for o, shape in ((score_blocks, (nb, nb)), (token_blocks, (nb,))):
+        if o is not None:
+            _dev(o)
+            if o.dtype != torch.float32 or tuple(o.shape) != shape or not o.is_contiguous():
+                raise ValueError("score_blocks / token_blocks must be contiguous float32 [nb,nb] / [nb]")
+    if workspace is None:
+        workspace = torch.empty(lemo_score_blocks_workspace_bytes(S, H), dtype=torch.uint8, device=Q.device)
+    _dev(workspace)
+    _check(_lib.lemo_score_blocks(*a, float(scale), int(b), int(flags), int(mode), _ptr(lse2), _ptr(score_blocks), _ptr(token_blocks),
+                                  _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()), "lemo_score_blocks")
+    return score_blocks, token_blocks
+
+
+def lemo_threshold_init(token_blocks: torch.Tensor, threshold: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Mean token-block score (Alg. 1 step 1) -> float32 [1] on the GPU."""
+    _dev(token_blocks, threshold)
+    if token_blocks.dtype != torch.float32 or token_blocks.dim() != 1 or not token_blocks.is_contiguous():
+        raise ValueError("token_blocks must be contiguous float32 [nb]")
+    if threshold is None:
+        threshold = torch.empty(1, dtype=torch.float32, device=token_blocks.device)
+    elif threshold.dtype != torch.float32 or threshold.numel() != 1:
+        raise ValueError("threshold must be one float32")
+    _check(_lib.lemo_threshold_init(_ptr(token_blocks), token_blocks.numel(), _ptr(threshold), _stream()), "lemo_threshold_init")
+    return threshold
+
+
+def lemo_select_threshold(token_blocks: torch.Tensor, S: int, b: int, threshold, kept_idx: Optional[torch.Tensor] = None,
+                          kept_count: Optional[torch.Tensor] = None):
+    """Tokens of the blocks with score >= threshold (a float, or a float32 GPU tensor of one element)
+    -> (kept_idx int32 [S], of which the first kept_count[0] entries are valid, kept_count int32 [1])."""
+    _dev(token_blocks, kept_idx, kept_count)
+    if token_blocks.dtype != torch.float32 or token_blocks.dim() != 1 or not token_blocks.is_contiguous() \
+            or (b > 0 and token_blocks.numel() != (S + b - 1) // b):
+        raise ValueError("token_blocks must be contiguous float32 [ceil(S/b)]")
+    if kept_idx is None:
+        kept_idx = torch.empty(S, dtype=torch.int32, device=token_blocks.device)
+    elif kept_idx.dtype != torch.int32 or kept_idx.numel() < S or not kept_idx.is_contiguous():
+        raise ValueError("kept_idx must be contiguous int32 with room for S entries")
+    if kept_count is None:
+        kept_count = torch.empty(1, dtype=torch.int32, device=token_blocks.device)
+    elif kept_count.dtype != torch.int32 or kept_count.numel() != 1:
+        raise ValueError("kept_count must be one int32")
+    t_dev = None
+    t_host = 0.0
+    if isinstance(threshold, torch.Tensor):
+        _dev(threshold)
+        if threshold.dtype != torch.float32 or threshold.numel() != 1:
+            raise ValueError("a device threshold must be one float32")
+        t_dev = threshold
+    else:
+        t_host = float(threshold)
+    _check(_lib.lemo_select_threshold(_ptr(token_blocks), int(S), int(b), t_host, _ptr(t_dev), _ptr(kept_idx), _ptr(kept_count),
+                                      _stream()), "lemo_select_threshold")
+    return kept_idx, kept_count
 
 
 def lemo_select_topk(scores: torch.Tensor, L: int, k: int, kept_idx: Optional[torch.Tensor] = None) -> torch.Tensor:

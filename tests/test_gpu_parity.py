@@ -6,6 +6,8 @@ GPU's scores; gather bit-exact and the GEMM within one bf16 step plus the binary
 """
 import sys
 
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -249,6 +251,150 @@ def test_select_all_equal_and_extremes(lemo):
     for k in (1, 17, 64, 128):
         got = lemo.lemo_select_topk(torch.from_numpy(ext).cuda(), 128, k).cpu().numpy()
         np.testing.assert_array_equal(got, oracle.select_topk(ext, 128, k))
+
+
+# ------------------------------------------------------------------------------------ block-wise informativeness, thresholds
+
+def assert_blocks_close(got, want, what="", atol=1e-6):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, what
+    assert np.isfinite(got).all(), what
+    bad = np.abs(got - want) > 2e-3 * np.abs(want) + atol
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} beyond tolerance, worst {np.abs(got - want).max():.3e}"
+
+
+BLOCK_CASES = [(300, 4, 2, 64, "bf16", 32), (257, 2, 2, 128, "bf16", 64), (1000, 8, 2, 128, "bf16", 128), (129, 2, 1, 64, "f32", 32),
+               (200, 2, 2, 128, "f32", 64), (2100, 4, 4, 128, "bf16", 96), (31, 1, 1, 64, "bf16", 32)]
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+@pytest.mark.parametrize("S,H,Hkv,d,dtype,b", BLOCK_CASES)
+def test_score_blocks_small_shapes(lemo, S, H, Hkv, d, dtype, b, flags, mode):
+    say(f"[blocks] S={S} H={H}/{Hkv} d={d} {dtype} b={b} flags={flags} mode={mode}")
+    Q, K = wl.tiny_qk(S, H, Hkv, d, dtype, seed=S + b)
+    sb, tb = lemo.lemo_score_blocks(Q.cuda(), K.cuda(), b, flags=flags, mode=mode)
+    torch.cuda.synchronize()
+    want_sb, want_tb = oracle.score_blocks(wl.as_numpy(Q), wl.as_numpy(K), b, flags=flags, mode=mode)
+    atol = 1e-6 if mode == 0 else 1e-5
+    assert_blocks_close(sb.cpu().numpy(), want_sb, "score blocks", atol)
+    assert_blocks_close(tb.cpu().numpy(), want_tb, "token blocks", atol)
+
+
+def test_score_blocks_options_and_determinism(lemo):
+    say("[blocks] options")
+    Q, K = wl.tiny_qk(700, 4, 2, 128, "bf16", seed=5)
+    Qd, Kd = Q.cuda(), K.cuda()
+    sb, tb = lemo.lemo_score_blocks(Qd, Kd, 64)
+    # row statistics handed in == computed inside; no score-block matrix wanted; run twice == same bits
+    lse2 = lemo.lemo_score_rowstats(Qd, Kd)
+    sb2, tb2 = lemo.lemo_score_blocks(Qd, Kd, 64, lse2=lse2)
+    none, tb3 = lemo.lemo_score_blocks(Qd, Kd, 64, want_score_blocks=False)
+    torch.cuda.synchronize()
+    assert none is None
+    assert torch.equal(sb, sb2) and torch.equal(tb, tb2) and torch.equal(tb, tb3)
+    # strided views (a fused QKV buffer) and an explicit scale
+    qkv = torch.zeros((700, 8, 128), dtype=torch.bfloat16, device="cuda")
+    qkv[:, :4] = Qd
+    qkv[:, 4:6] = Kd
+    _, tb4 = lemo.lemo_score_blocks(qkv[:, :4], qkv[:, 4:6], 64, scale=1.0 / math.sqrt(128))
+    assert_blocks_close(tb4.cpu().numpy(), tb.cpu().numpy(), "strided", 1e-7)
+    # b must be a multiple of 32
+    with pytest.raises(lemo.LemoError) as e:
+        lemo.lemo_score_blocks(Qd, Kd, 48)
+    assert e.value.code == -6
+
+
+def test_score_blocks_config_C1_fp32(lemo):
+    cfg = wl.CONFIGS["C1"]
+    lay = wl.make_layer(cfg, want_gemm=False)
+    say("[blocks] C1")
+    for flags in (0, 3):
+        sb, tb = lemo.lemo_score_blocks(lay["Q"].cuda(), lay["K"].cuda(), 64, flags=flags)
+        want_sb, want_tb = oracle.score_blocks(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), 64, flags=flags)
+        assert_blocks_close(sb.cpu().numpy(), want_sb, "C1 score blocks")
+        assert_blocks_close(tb.cpu().numpy(), want_tb, "C1 token blocks")
+
+
+def test_score_blocks_config_C2_heads_subset(lemo):
+    """4096 tokens, 8 of the 32 heads (the oracle's cost is linear in the head count), b = 64: every score block."""
+    cfg = wl.CONFIGS["C2"]
+    lay = wl.make_layer(cfg, want_gemm=False, heads=list(range(8)), device="cuda")
+    say("[blocks] C2, 8 heads: GPU")
+    sb, tb = lemo.lemo_score_blocks(lay["Q"].cuda(), lay["K"].cuda(), 64)
+    torch.cuda.synchronize()
+    say("[blocks] C2, 8 heads: oracle")
+    want_sb, want_tb = oracle.score_blocks(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), 64)
+    assert_blocks_close(sb.cpu().numpy(), want_sb, "C2 score blocks")
+    assert_blocks_close(tb.cpu().numpy(), want_tb, "C2 token blocks")
+
+
+def test_score_blocks_full_size_sampled_rows(lemo):
+    """The 32K-token, 32-head configuration in the launch shape the bench times (b = 64): sampled block rows against the
+    oracle, plus what holds for every entry: blocks above the diagonal are 0, every other block lies in (0, 1], and the
+    token-block scores are the column sums of the matrix."""
+    cfg = wl.CONFIGS["C5"]
+    lay = wl.make_layer(cfg, want_gemm=False, device="cuda")
+    say("[blocks] C5: GPU")
+    sb, tb = lemo.lemo_score_blocks(lay["Q"].cuda(), lay["K"].cuda(), 64)
+    torch.cuda.synchronize()
+    sbn, tbn = sb.cpu().numpy(), tb.cpu().numpy()
+    nb = cfg.S // 64
+    assert sbn.shape == (nb, nb)
+    assert not np.triu(sbn, 1).any()
+    low = sbn[np.tril_indices(nb)]
+    assert (low > 0).all() and (low <= 1.0 + 1e-6).all()
+    np.testing.assert_allclose(tbn, sbn.astype(np.float64).sum(axis=0), rtol=1e-5)
+    rows = [0, 1, 200, nb - 1]
+    say(f"[blocks] C5: oracle on block rows {rows}")
+    want = oracle.score_block_rows(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), 64, rows)
+    assert_blocks_close(sbn[rows], want, "C5 sampled block rows")
+
+
+@pytest.mark.parametrize("S,b", [(1000, 32), (4096, 64), (40000, 32), (77, 128), (32768, 1024)])
+def test_select_threshold_bit_exact(lemo, S, b):
+    say(f"[threshold] S={S} b={b}")
+    rng = np.random.default_rng(S + b)
+    nb = -(-S // b)
+    tb = rng.random(nb).astype(np.float32)
+    tbd = torch.from_numpy(tb).cuda()
+    for T in (float(np.sort(tb)[nb // 2]), -np.inf, np.inf, 0.25):
+        kept, count = lemo.lemo_select_threshold(tbd, S, b, T)
+        want = oracle.select_threshold(tb, S, b, T)
+        n = int(count.item())
+        assert n == len(want)
+        np.testing.assert_array_equal(kept.cpu().numpy()[:n], want)
+    # Alg. 1 step 1 on the device feeding the selection without a host round trip
+    T0 = lemo.lemo_threshold_init(tbd)
+    kept, count = lemo.lemo_select_threshold(tbd, S, b, T0)
+    t0 = float(T0.item())
+    assert t0 == pytest.approx(oracle.threshold_init(tb), rel=1e-5)
+    want = oracle.select_threshold(tb, S, b, t0)
+    assert int(count.item()) == len(want)
+    np.testing.assert_array_equal(kept.cpu().numpy()[:len(want)], want)
+
+
+def test_threshold_path_feeds_the_consumer(lemo):
+    """Block scores -> initial threshold -> kept tokens -> selective-load GEMM with the data-dependent row count."""
+    say("[threshold] whole path")
+    cfg = wl.scaled(wl.CONFIGS["C2"], S=2048, H=4, H_kv=4, C=256, N=320)
+    lay = wl.make_layer(cfg)
+    Qd, Kd = lay["Q"].cuda(), lay["K"].cuda()
+    _, tb = lemo.lemo_score_blocks(Qd, Kd, 64, want_score_blocks=False)
+    T0 = lemo.lemo_threshold_init(tb)
+    kept, count = lemo.lemo_select_threshold(tb, cfg.S, 64, T0)
+    M = int(count.item())
+    assert 0 < M < cfg.S and M % 64 == 0
+    Y = lemo.lemo_gather_gemm(lay["X"].cuda(), kept[:M].contiguous(), lay["W"].cuda())
+    torch.cuda.synchronize()
+    # the GPU's block scores are close to the oracle's; its selection is exact on its own scores
+    _, want_tb = oracle.score_blocks(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), 64)
+    assert_blocks_close(tb.cpu().numpy(), want_tb, "token blocks")
+    idx = oracle.select_threshold(tb.cpu().numpy(), cfg.S, 64, float(T0.item()))
+    np.testing.assert_array_equal(kept.cpu().numpy()[:M], idx)
+    want = oracle.gather_gemm(wl.as_numpy(lay["X"]), idx, wl.as_numpy(lay["W"]))
+    assert_gemm_close(wl.to_bf16_bits(Y), want, wl.as_numpy(lay["X"])[idx], wl.as_numpy(lay["W"]))
 
 
 # ------------------------------------------------------------------------------------ gather-GEMM
