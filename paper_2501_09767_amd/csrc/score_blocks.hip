@@ -13,13 +13,13 @@
 // head brings its own Q and K rows), so the kernel leans on the caches: the 256 workgroups in flight form a 16 x 16
 // super-patch of rectangles (32 operand tiles for 256 rectangles), and each die works on a 4 x 8 sub-patch of it.
 #include <mutex>
+#include <type_traits>
 
 #include "lemo_common.hpp"
 
 namespace lemo {
 
-constexpr int SB_THREADS = 256;  // 4 waves: 2 (query halves) x 2 (key halves) of the rectangle
-constexpr int SB_PATCH = 16;     // super-patch edge, in rectangles
+constexpr int SB_PATCH = 16;  // super-patch edge, in rectangles
 
 template <typename T, int D> struct BGeo {
     static constexpr int ROWB = D * (int)sizeof(T);  // bytes per head row
@@ -27,8 +27,14 @@ template <typename T, int D> struct BGeo {
     static constexpr int CPR = ROWB / 16;            // 16-byte pieces per row
     static constexpr int STRIDE = ROWB + 16;         // LDS row pitch (16 consecutive rows -> 16 distinct bank groups)
     static constexpr int TT = ROWB > 256 ? 64 : 128; // rectangle edge (queries and keys)
-    static constexpr int NS = TT / 64;               // 32-row subtiles per wave and side
-    static constexpr int ROWS_PER_LOAD = SB_THREADS / CPR;
+    // Waves: 2 along the queries x NWK along the keys.  The LDS only reaches its bandwidth with two waves per SIMD
+    // (measured: 114 B/clk/CU with four waves reading, 220 with eight), and this kernel moves 5 LDS bytes per 1000
+    // flops, so the 128-row rectangle is worked by eight waves of 64 x 32.
+    static constexpr int NWK = TT == 128 ? 4 : 2;
+    static constexpr int THREADS = 2 * NWK * 64;
+    static constexpr int NSQ = TT / 2 / 32;          // 32-row query subtiles per wave
+    static constexpr int NSK = TT / NWK / 32;        // 32-row key subtiles per wave
+    static constexpr int ROWS_PER_LOAD = THREADS / CPR;
     static constexpr int NLOAD = TT / ROWS_PER_LOAD; // 16-byte loads per thread, head and operand
     static constexpr int STAGE_BYTES = 2 * TT * STRIDE + TT * (int)sizeof(float);  // Q rows, K rows, -lse2 of the Q rows
     static constexpr int LDS = 2 * STAGE_BYTES;
@@ -39,9 +45,9 @@ __device__ __forceinline__ void sb_fence() { __builtin_amdgcn_sched_barrier(0); 
 
 // MODE 0: probabilities exp2(s * c2 - lse2_i);  MODE 1: positive part of the raw dot product (scaled at the end)
 template <typename T, int D, int MODE>
-__global__ __launch_bounds__(SB_THREADS, 1) void tilemax_kernel(BlockParams p) {
+__global__ __launch_bounds__((BGeo<T, D>::THREADS), 1) void tilemax_kernel(BlockParams p) {
     using G = BGeo<T, D>;
-    constexpr int NS = G::NS;
+    constexpr int NSQ = G::NSQ, NSK = G::NSK;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     // rectangle of this workgroup
@@ -65,7 +71,7 @@ __global__ __launch_bounds__(SB_THREADS, 1) void tilemax_kernel(BlockParams p) {
     const int S = p.S;
     const int q0 = tq * G::TT, k0 = tk * G::TT;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
-    const int wq = wave >> 1, wk = wave & 1;
+    const int wq = wave / G::NWK, wk = wave % G::NWK;
     const float c2 = p.c2;
     const T* Qb = static_cast<const T*>(p.Q);
     const T* Kb = static_cast<const T*>(p.K);
@@ -104,12 +110,12 @@ __global__ __launch_bounds__(SB_THREADS, 1) void tilemax_kernel(BlockParams p) {
         if (MODE == 0 && tid < G::TT) reinterpret_cast<float*>(s + 2 * G::TT * G::STRIDE)[tid] = q0 + tid < S ? -pre_l : -INFINITY;
     };
 
-    // head sums of this wave's NS x NS tiles: sbar[qs][ks][r] = element (row acc_row(r), column l32) of tile (qs, ks)
-    f32x16 sbar[NS][NS];
+    // head sums of this wave's NSQ x NSK tiles: sbar[qs][ks][r] = element (row acc_row(r), column l32) of tile (qs, ks)
+    f32x16 sbar[NSQ][NSK];
 #pragma unroll
-    for (int a = 0; a < NS; ++a)
+    for (int a = 0; a < NSQ; ++a)
 #pragma unroll
-        for (int b = 0; b < NS; ++b) sbar[a][b] = f32x16{0};
+        for (int b = 0; b < NSK; ++b) sbar[a][b] = f32x16{0};
 
     // add the tile `raw` (unscaled dot products) into its accumulator; slice c of NSL covers elements [c*16/NSL, ...)
     auto accumulate = [&](f32x16& dst, const f32x16& raw, const float (&nl)[16], int c, int nsl) {
@@ -138,35 +144,35 @@ __global__ __launch_bounds__(SB_THREADS, 1) void tilemax_kernel(BlockParams p) {
         const char* sq = smem + (h & 1) * G::STAGE_BYTES;
         const char* sk = sq + G::TT * G::STRIDE;
         const float* sl = reinterpret_cast<const float*>(sq + 2 * G::TT * G::STRIDE);
-        u32x4 qf[NS][G::NCH], kf[NS][G::NCH];
-        float nl[NS][16] = {};
+        u32x4 qf[NSQ][G::NCH], kf[NSK][G::NCH];
+        float nl[NSQ][16] = {};
 #pragma unroll
-        for (int s = 0; s < NS; ++s)
+        for (int c = 0; c < G::NCH; ++c) {
 #pragma unroll
-            for (int c = 0; c < G::NCH; ++c) {
-                qf[s][c] = *reinterpret_cast<const u32x4*>(&sq[((wq * NS + s) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
-                kf[s][c] = *reinterpret_cast<const u32x4*>(&sk[((wk * NS + s) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
-            }
+            for (int s = 0; s < NSQ; ++s) qf[s][c] = *reinterpret_cast<const u32x4*>(&sq[((wq * NSQ + s) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+#pragma unroll
+            for (int s = 0; s < NSK; ++s) kf[s][c] = *reinterpret_cast<const u32x4*>(&sk[((wk * NSK + s) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+        }
         if (MODE == 0) {
 #pragma unroll
-            for (int s = 0; s < NS; ++s)
+            for (int s = 0; s < NSQ; ++s)
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {  // rows 8*gq + 4*half + 0..3 of query subtile s
-                    const f32x4 v = *reinterpret_cast<const f32x4*>(&sl[(wq * NS + s) * 32 + gq * 8 + half * 4]);
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(&sl[(wq * NSQ + s) * 32 + gq * 8 + half * 4]);
                     nl[s][gq * 4 + 0] = v[0]; nl[s][gq * 4 + 1] = v[1]; nl[s][gq * 4 + 2] = v[2]; nl[s][gq * 4 + 3] = v[3];
                 }
         }
         if (have_carry) {  // vector work that covers the LDS latency of the reads above
 #pragma unroll
-            for (int c = 0; c < 4; ++c) accumulate(sbar[NS - 1][NS - 1], carry, carry_nl, c, 4);
+            for (int c = 0; c < 4; ++c) accumulate(sbar[NSQ - 1][NSK - 1], carry, carry_nl, c, 4);
         }
         // tiles of this head in the order (0,0), (0,1), ..: the accumulation of one tile is issued slice by slice
         // between the MFMAs of the next
         f32x16 prev = {0};
 #pragma unroll
-        for (int t = 0; t < NS * NS; ++t) {
-            const int qs = t / NS, ks = t % NS;
-            const int pq = (t + NS * NS - 1) % (NS * NS) / NS, pk = (t + NS * NS - 1) % (NS * NS) % NS;  // the tile before
+        for (int t = 0; t < NSQ * NSK; ++t) {
+            const int qs = t / NSK, ks = t % NSK;
+            const int pq = (t + NSQ * NSK - 1) % (NSQ * NSK) / NSK, pk = (t + NSQ * NSK - 1) % (NSQ * NSK) % NSK;  // the tile before
             f32x16 acc = {0};
             sb_fence();
 #pragma unroll
@@ -179,20 +185,20 @@ __global__ __launch_bounds__(SB_THREADS, 1) void tilemax_kernel(BlockParams p) {
         }
         carry = prev;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) carry_nl[r] = nl[NS - 1][r];
+        for (int r = 0; r < 16; ++r) carry_nl[r] = nl[NSQ - 1][r];
         have_carry = true;
         if (more) stash((h + 1) & 1);
     }
 #pragma unroll
-    for (int c = 0; c < 4; ++c) accumulate(sbar[NS - 1][NS - 1], carry, carry_nl, c, 4);
+    for (int c = 0; c < 4; ++c) accumulate(sbar[NSQ - 1][NSK - 1], carry, carry_nl, c, 4);
 
     // maximum of every 32 x 32 tile over the pairs that are admitted
     const bool excl = (p.flags & LEMO_EXCLUDE_SELF) != 0;
 #pragma unroll
-    for (int qs = 0; qs < NS; ++qs)
+    for (int qs = 0; qs < NSQ; ++qs)
 #pragma unroll
-        for (int ks = 0; ks < NS; ++ks) {
-            const int i0 = q0 + (wq * NS + qs) * 32, j = k0 + (wk * NS + ks) * 32 + l32;
+        for (int ks = 0; ks < NSK; ++ks) {
+            const int i0 = q0 + (wq * NSQ + qs) * 32, j = k0 + (wk * NSK + ks) * 32 + l32;
             float m = 0.f;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -202,7 +208,7 @@ __global__ __launch_bounds__(SB_THREADS, 1) void tilemax_kernel(BlockParams p) {
             }
 #pragma unroll
             for (int sh = 32; sh >= 1; sh >>= 1) m = fmaxf(m, __shfl_xor(m, sh));
-            const int ti = i0 / 32, tj = (k0 + (wk * NS + ks) * 32) / 32;
+            const int ti = i0 / 32, tj = (k0 + (wk * NSK + ks) * 32) / 32;
             if (lane == 0 && ti < p.nt32 && tj < p.nt32) p.tilemax[(size_t)ti * p.nt32 + tj] = m * p.out_scale;
         }
 }
@@ -247,7 +253,7 @@ static int launch_tilemax_t(BlockParams p, hipStream_t st) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS);
     });
     if (attr_err != hipSuccess) return (int)attr_err;
-    hipLaunchKernelGGL((tilemax_kernel<T, D, MODE>), dim3((unsigned)(nsp_total * SB_PATCH * SB_PATCH)), dim3(SB_THREADS), G::LDS, st, p);
+    hipLaunchKernelGGL((tilemax_kernel<T, D, MODE>), dim3((unsigned)(nsp_total * SB_PATCH * SB_PATCH)), dim3(G::THREADS), G::LDS, st, p);
     return (int)hipGetLastError();
 }
 
