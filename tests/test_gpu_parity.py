@@ -599,6 +599,25 @@ def test_gather_gemm_add_exact_cases(lemo):
     np.testing.assert_array_equal(wl.to_bf16_bits(same), wl.to_bf16_bits(R0[:, :C].contiguous()))
 
 
+def test_gather_gemm_add_as_backward_of_the_selective_load(lemo):
+    """Backward of Y = X[idx] W^T with respect to X: dX[idx[m],:] += dY[m,:] W.  With the weight's transpose stored as a
+    [C,N] matrix this is the same call (compact rows in, indexed rows out); checked against numpy float64 on a dyadic grid."""
+    say("[gemm+add] backward form")
+    rng = np.random.default_rng(23)
+    S, C, N, M = 300, 96, 160, 120
+    dY = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32)
+    W = (rng.integers(-8, 9, (N, C)) / 8.0).astype(np.float32)
+    dX = (rng.integers(-64, 65, (S, C)) / 4.0).astype(np.float32)
+    idx = np.sort(rng.permutation(S)[:M]).astype(np.int32)
+    want = dX.astype(np.float64)
+    want[idx] += dY.astype(np.float64) @ W.astype(np.float64)
+    Wt = torch.from_numpy(W).to(torch.bfloat16).t().contiguous().cuda()  # [C,N]
+    got = lemo.lemo_gather_gemm_add(torch.from_numpy(dY).to(torch.bfloat16).cuda(), None, Wt,
+                                    torch.from_numpy(dX).to(torch.bfloat16).cuda(), torch.from_numpy(idx).cuda())
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(wl.to_bf16_bits(got), bf16(want))
+
+
 def bf16(x):
     return wl.to_bf16_bits(torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16))
 
