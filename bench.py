@@ -151,6 +151,35 @@ def measure_fused_output_projection(cfg, lemo, ev, stream, kept, reps=10):
             "unfused_ms": round(t_unfused, 5), "bytes_saved": 2.0 * M * C * esz}
 
 
+def measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, Y, reps=10):
+    """Outside the timed step: what folding the gather into the GEMM's A-tile load saves (Sec. 4.4, "directly loads the
+    selected tokens from original inputs").  Unfolded = materialise the kept rows (torch.index_select, one read and one
+    write of M x C) and run the same GEMM kernel on the compact copy."""
+    import torch
+    kept64 = kept.long()
+    Xc = torch.empty((cfg.M, cfg.C), dtype=X.dtype, device=X.device)
+
+    def timed(fn):
+        fn()
+        marks = [ev.create() for _ in range(reps + 1)]
+        ev.record(marks[0], stream)
+        for i in range(reps):
+            fn()
+            ev.record(marks[i + 1], stream)
+        torch.cuda.synchronize()
+        return sum(ev.elapsed_ms(marks[i], marks[i + 1]) for i in range(reps)) / reps
+
+    def unfolded():
+        torch.index_select(X, 0, kept64, out=Xc)
+        lemo.lemo_gather_gemm(Xc, None, W, Y=Y)
+
+    t_fold = timed(lambda: lemo.lemo_gather_gemm(X, kept, W, Y=Y))
+    t_unf = timed(unfolded)
+    esz = 2 if cfg.dtype == "bf16" else 4
+    return {"what": "consumer GEMM reading the kept rows in place vs torch.index_select into a compact copy + the same GEMM",
+            "folded_ms": round(t_fold, 5), "unfolded_ms": round(t_unf, 5), "bytes_saved": 2.0 * cfg.M * cfg.C * esz}
+
+
 def measure_block_scoring(cfg, lemo, ev, stream, Q, K, lse2, flags, b=64, reps=5):
     """Outside the timed step: the paper's own criterion (Sec. 4.2 Eq. 2): block-wise informativeness with b x b score
     blocks from the row statistics sweep 1 already produced, then the initial threshold of Alg. 1 and the threshold
@@ -265,15 +294,17 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     work = algorithmic_work(cfg)
-    phase_ms = {}
+    phase_ms, phase_min, phase_med = {}, {}, {}
     for pi, name in enumerate(phases):
-        phase_ms[name] = sum(ev.elapsed_ms(marks[i][pi], marks[i][pi + 1]) for i in range(args.steps)) / args.steps
+        ts = sorted(ev.elapsed_ms(marks[i][pi], marks[i][pi + 1]) for i in range(args.steps))
+        phase_ms[name] = sum(ts) / len(ts)
+        phase_min[name], phase_med[name] = ts[0], ts[len(ts) // 2]
     peak_tflops = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS
     report = {}
     for name in phases:
         ms = phase_ms[name]
         w = work[name]
-        r = {"ms": round(ms, 5)}
+        r = {"ms": round(ms, 5), "ms_median": round(phase_med[name], 5), "ms_min": round(phase_min[name], 5)}
         if "flops" in w:
             r["tflops"] = round(w["flops"] / (ms * 1e-3) * 1e-12, 2)
             r["frac_mfma_peak"] = round(r["tflops"] / peak_tflops, 4)
@@ -314,6 +345,7 @@ def main():
         "roofline": roof,
         "phases": report,
     }
+    out["gather_fold"] = measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, Y)
     out["fused_in_place_add"] = measure_fused_output_projection(cfg, lemo, ev, stream, kept)
     out["block_wise"] = measure_block_scoring(cfg, lemo, ev, stream, Q, K, lse2, flags)
     if not args.no_cpu_baseline:
