@@ -21,6 +21,7 @@
  *                           Y[m,:] = X[idx[m],:] . W^T (+ bias).
  *   oracle_gather_gemm_add  Sec. 4.4, both halves fused: selective load on the way in, in-place add
  *                           into the residual rows on the way out.
+ *   oracle_kept_attention   Sec. 4.4: the attention block computed over the kept tokens, read in place.
  *   oracle_scatter_add      Sec. 4.4 in-place add (padding and residual add in one step):
  *                           dX[idx[m],:] += G[m,:].
  *
@@ -502,6 +503,69 @@ int oracle_gather_gemm_add(const void* X, int64_t S, int64_t ldx, const int32_t*
         }
     }
     return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------- attention over the kept tokens */
+
+/* The attention block on the kept tokens only (Sec. 4.4: the block reads the selected tokens straight
+ * from the original inputs; what it returns is the compact result that the in-place add then puts back):
+ *   O[m,h,:] = sum_n softmax_n( scale * <Q[idx[m],h,:], K[idx[n],g,:]> ) * V[idx[n],g,:],   g = floor(h*H_kv/H),
+ * n running over the kept tokens the mask allows: all of them, or with CAUSAL those whose position idx[n]
+ * is not after idx[m].  Everything in double, ONE rounding to the element type.  Q [S,H,d], K and V
+ * [S,H_kv,d] with element strides (d contiguous); O [M,H,d] with strides o_tok, o_head.  idx == NULL
+ * means the first M tokens. */
+int oracle_kept_attention(const void* Q, const void* K, const void* V, int64_t S, int32_t H, int32_t H_kv, int32_t d, int dtype,
+                          int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                          int64_t v_tok_stride, int64_t v_head_stride, const int32_t* idx, int64_t M, double scale,
+                          uint32_t flags, void* O, int64_t o_tok_stride, int64_t o_head_stride) {
+    if (!Q || !K || !V || !O || S <= 0 || M < 0 || H <= 0 || H_kv <= 0 || d <= 0 || H % H_kv) return ORACLE_ERR_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_ERR_ARG;
+    if (!idx && M > S) return ORACLE_ERR_ARG;
+    for (int64_t m = 0; m < M; ++m) {
+        int64_t r = idx ? idx[m] : m;
+        if (r < 0 || r >= S) return ORACLE_ERR_ARG;
+    }
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)d);
+    const int causal = (flags & ORACLE_CAUSAL) != 0;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t m = M - 1; m >= 0; --m) {
+        double* w = (double*)malloc(sizeof(double) * (size_t)(M > 0 ? M : 1));
+        double* out = (double*)malloc(sizeof(double) * (size_t)d);
+        if (!w || !out) { fail = 1; free(w); free(out); continue; }
+        int64_t pm = idx ? idx[m] : m;
+        for (int h = 0; h < H; ++h) {
+            int g = (int)(((int64_t)h * H_kv) / H);
+            double mx = -INFINITY;
+            for (int64_t n = 0; n < M; ++n) {
+                int64_t pn = idx ? idx[n] : n;
+                if (causal && pn > pm) { w[n] = -INFINITY; continue; }
+                double dot = 0.0;
+                for (int c = 0; c < d; ++c)
+                    dot += load_elem(Q, pm * q_tok_stride + h * q_head_stride + c, dtype) *
+                           load_elem(K, pn * k_tok_stride + g * k_head_stride + c, dtype);
+                w[n] = scale * dot;
+                if (w[n] > mx) mx = w[n];
+            }
+            double den = 0.0;
+            for (int64_t n = 0; n < M; ++n) { w[n] = (w[n] == -INFINITY) ? 0.0 : exp(w[n] - mx); den += w[n]; }
+            for (int c = 0; c < d; ++c) out[c] = 0.0;
+            for (int64_t n = 0; n < M; ++n) {
+                if (w[n] == 0.0) continue;
+                int64_t pn = idx ? idx[n] : n;
+                double p = w[n] / den;
+                for (int c = 0; c < d; ++c) out[c] += p * load_elem(V, pn * v_tok_stride + g * v_head_stride + c, dtype);
+            }
+            for (int c = 0; c < d; ++c) {
+                int64_t o = m * o_tok_stride + h * o_head_stride + c;
+                if (dtype == ORACLE_BF16) ((uint16_t*)O)[o] = double_to_bf16_bits(out[c]);
+                else ((float*)O)[o] = (float)out[c];
+            }
+        }
+        free(w);
+        free(out);
+    }
+    return fail ? ORACLE_ERR_NOMEM : ORACLE_OK;
 }
 
 /* ---------------------------------------------------------------- scatter-add */

@@ -524,6 +524,90 @@ def test_gemm_add_single_rounding_and_special_cases():
         oracle.gather_gemm_add(X, idx, W, R0.copy(), bad)
 
 
+# ------------------------------------------------------------------------------ attention over the kept tokens
+
+def dense_attention(Q, K, V, idx, causal, scale=None):
+    """Textbook attention on the gathered rows, float64 numpy: gather, logits, mask by token position, softmax, P @ V."""
+    S, H, d = Q.shape
+    Hkv = K.shape[1]
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    q, k, v = Q[idx].astype(np.float64), K[idx].astype(np.float64), V[idx].astype(np.float64)
+    out = np.zeros((len(idx), H, d))
+    allowed = (idx[None, :] <= idx[:, None]) if causal else np.ones((len(idx), len(idx)), dtype=bool)
+    for h in range(H):
+        g = h * Hkv // H
+        z = np.where(allowed, scale * (q[:, h] @ k[:, g].T), -np.inf)
+        e = np.exp(z - z.max(axis=1, keepdims=True))
+        out[:, h] = (e / e.sum(axis=1, keepdims=True)) @ v[:, g]
+    return out
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("S,H,Hkv,d,M,dtype", [(40, 2, 2, 8, 17, "f32"), (64, 4, 2, 16, 64, "bf16"), (50, 3, 1, 4, 1, "f32"),
+                                                (33, 4, 4, 8, 20, "bf16")])
+def test_kept_attention_against_dense_numpy_and_torch(S, H, Hkv, d, M, dtype, causal):
+    rng = np.random.default_rng(S + M)
+    Q = rng.standard_normal((S, H, d)).astype(np.float32)
+    K = (rng.standard_normal((S, Hkv, d)) * 1.5).astype(np.float32)
+    V = rng.standard_normal((S, Hkv, d)).astype(np.float32)
+    idx = np.sort(rng.permutation(S)[:M]).astype(np.int32)
+    if dtype == "bf16":
+        Qin, Kin, Vin = bf16_bits(Q), bf16_bits(K), bf16_bits(V)
+        Q, K, V = widen(Qin), widen(Kin), widen(Vin)
+    else:
+        Qin, Kin, Vin = Q, K, V
+    want = dense_attention(Q, K, V, idx, causal)
+    got = oracle.kept_attention(Qin, Kin, Vin, idx, flags=CAUSAL if causal else 0)
+    if dtype == "bf16":
+        wb = bf16_bits(want)  # through float32: at most one step from the single rounding
+        assert np.max(np.abs(got.astype(np.int32) - wb.astype(np.int32))) <= 1 and np.mean(got == wb) > 0.99
+        got = widen(got)
+    else:
+        np.testing.assert_allclose(got, want, rtol=1e-6, atol=1e-7)
+    # the library routine on the same gathered rows (ascending positions make the position mask the usual triangle)
+    rep = H // Hkv
+    tq = torch.from_numpy(Q[idx]).double().permute(1, 0, 2)
+    tk = torch.from_numpy(np.repeat(K[idx], rep, axis=1)).double().permute(1, 0, 2)
+    tv = torch.from_numpy(np.repeat(V[idx], rep, axis=1)).double().permute(1, 0, 2)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=causal).permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(got, ref, rtol=2e-2 if dtype == "bf16" else 1e-6, atol=1e-2 if dtype == "bf16" else 1e-7)
+
+
+def test_kept_attention_special_cases():
+    rng = np.random.default_rng(41)
+    S, H, Hkv, d, M = 60, 4, 2, 8, 25
+    Q = rng.standard_normal((S, H, d)).astype(np.float32)
+    K = rng.standard_normal((S, Hkv, d)).astype(np.float32)
+    V = rng.standard_normal((S, Hkv, d)).astype(np.float32)
+    idx = np.sort(rng.permutation(S)[:M]).astype(np.int32)
+    # zero queries: every allowed key weighs the same, so the output is a mean of V rows (running mean under the mask)
+    Z = np.zeros_like(Q)
+    got = oracle.kept_attention(Z, K, V, idx, flags=CAUSAL)
+    for h in range(H):
+        want = np.cumsum(V[idx, h * Hkv // H].astype(np.float64), axis=0) / np.arange(1, M + 1)[:, None]
+        np.testing.assert_allclose(got[:, h], want, rtol=1e-6, atol=1e-7)
+    got = oracle.kept_attention(Z, K, V, idx, flags=0)
+    np.testing.assert_allclose(got[3, 1], V[idx, 0].astype(np.float64).mean(axis=0), rtol=1e-6, atol=1e-7)
+    # no index list == the first M tokens; all tokens kept == ordinary attention; first kept token attends to itself only
+    np.testing.assert_array_equal(oracle.kept_attention(Q, K, V, None), oracle.kept_attention(Q, K, V, np.arange(S, dtype=np.int32)))
+    first = oracle.kept_attention(Q, K, V, idx, flags=CAUSAL)[0]
+    np.testing.assert_allclose(first, np.repeat(V[idx[0]], H // Hkv, axis=0), rtol=1e-6)
+    # tokens that are not kept have no influence: changing them changes nothing
+    Q2, K2, V2 = Q.copy(), K.copy(), V.copy()
+    drop = np.setdiff1d(np.arange(S), idx)
+    Q2[drop] += 3.0; K2[drop] -= 2.0; V2[drop] *= 5.0
+    np.testing.assert_array_equal(oracle.kept_attention(Q2, K2, V2, idx), oracle.kept_attention(Q, K, V, idx))
+    # one key far stronger than the rest takes all the weight of the queries that may see it
+    Kd = K.copy(); Kd[idx[5]] = 0.0
+    Qd = np.abs(Q)
+    Kd[idx[5]] = 50.0
+    got = oracle.kept_attention(Qd, Kd, V, idx, flags=CAUSAL)
+    np.testing.assert_allclose(got[5:, 0], np.broadcast_to(V[idx[5], 0], (M - 5, d)), rtol=1e-5, atol=1e-6)
+    # the scale argument; an explicit 1/sqrt(d) equals the default
+    np.testing.assert_allclose(oracle.kept_attention(Q, K, V, idx, scale=1.0 / math.sqrt(d)), oracle.kept_attention(Q, K, V, idx), rtol=1e-6)
+    assert not np.allclose(oracle.kept_attention(Q, K, V, idx, scale=1.0), oracle.kept_attention(Q, K, V, idx))
+
+
 # ------------------------------------------------------------------------------ scatter-add
 
 @pytest.mark.parametrize("gdt,xdt", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32"), ("f32", "bf16")])
