@@ -233,6 +233,35 @@ int lemo_gather_gemm_add(const void* X, int64_t S, int64_t ldx, const int32_t* k
                          const int32_t* out_idx, int32_t C, int32_t N, lemo_dtype_t dt, void* stream);
 
 /*
+ * Attention over the kept tokens, read in place (Sec. 4.4: the attention block loads the selected tokens
+ * straight from the original inputs instead of from a re-permuted copy):
+ *
+ *     O[m, h, :] = sum_n softmax_n( scale * <Q[kept_idx[m],h,:], K[kept_idx[n],g,:]> ) * V[kept_idx[n],g,:]
+ *
+ * with g = floor(h * H_kv / H) and n over all M kept tokens, or with LEMO_CAUSAL over n <= m (kept_idx
+ * must then be ascending, as lemo_select_topk / lemo_select_threshold write it, so that list order is
+ * position order).  LEMO_EXCLUDE_SELF is not accepted here.
+ *
+ *   Q [S,H,d], K and V [S,H_kv,d], element strides as for lemo_score_segments (d contiguous, 16-byte rule);
+ *   kept_idx [M] int32 token positions in [0,S) (not checked on the device), or NULL for the first M tokens;
+ *   O [M,H,d] compact result with element strides o_tok_stride, o_head_stride (multiples of 8, d contiguous):
+ *     row m belongs to token kept_idx[m]; lemo_gather_gemm_add with out_idx = kept_idx puts the block's
+ *     projection back into the residual stream;
+ *   workspace: lemo_kept_attention_workspace_bytes(M,H_kv,d) bytes, 256-byte aligned (holds the kept rows
+ *     of V transposed, 2 bytes per kept element).
+ *
+ * Supported: LEMO_BF16, d in {64,128}; Q and K each spanning less than 4 GiB.  The probabilities are
+ * rounded to bf16 for the second product and the normaliser is summed in binary32 from the unrounded
+ * values; one rounding of the result at the store.  M == 0 is a no-op.  Deterministic.
+ */
+int lemo_kept_attention_workspace_bytes(int64_t M, int32_t H_kv, int32_t d, size_t* bytes);
+int lemo_kept_attention(const void* Q, const void* K, const void* V, int64_t S, int32_t H, int32_t H_kv, int32_t d,
+                        lemo_dtype_t dt, int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride,
+                        int64_t k_head_stride, int64_t v_tok_stride, int64_t v_head_stride, const int32_t* kept_idx,
+                        int64_t M, float scale, uint32_t flags, void* O, int64_t o_tok_stride, int64_t o_head_stride,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * In-place add at the kept positions (Sec. 4.4: zero padding and the residual add collapse into one
  * read-modify-write of the kept rows); also the backward of the selective load:
  *

@@ -514,10 +514,48 @@ int oracle_gather_gemm_add(const void* X, int64_t S, int64_t ldx, const int32_t*
  * is not after idx[m].  Everything in double, ONE rounding to the element type.  Q [S,H,d], K and V
  * [S,H_kv,d] with element strides (d contiguous); O [M,H,d] with strides o_tok, o_head.  idx == NULL
  * means the first M tokens. */
+/* one kept query m, all heads -> out_row[H*d] (o_head_stride apart); w [M] and acc [d] are scratch */
+static void attention_one_query(const void* Q, const void* K, const void* V, int32_t H, int32_t H_kv, int32_t d, int dtype,
+                                int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                                int64_t v_tok_stride, int64_t v_head_stride, const int32_t* idx, int64_t M, double scale, int causal,
+                                int64_t m, void* O, int64_t o_base, int64_t o_head_stride, double* w, double* acc) {
+    int64_t pm = idx ? idx[m] : m;
+    for (int h = 0; h < H; ++h) {
+        int g = (int)(((int64_t)h * H_kv) / H);
+        double mx = -INFINITY;
+        for (int64_t n = 0; n < M; ++n) {
+            int64_t pn = idx ? idx[n] : n;
+            if (causal && pn > pm) { w[n] = -INFINITY; continue; }
+            double dot = 0.0;
+            for (int c = 0; c < d; ++c)
+                dot += load_elem(Q, pm * q_tok_stride + h * q_head_stride + c, dtype) *
+                       load_elem(K, pn * k_tok_stride + g * k_head_stride + c, dtype);
+            w[n] = scale * dot;
+            if (w[n] > mx) mx = w[n];
+        }
+        double den = 0.0;
+        for (int64_t n = 0; n < M; ++n) { w[n] = (w[n] == -INFINITY) ? 0.0 : exp(w[n] - mx); den += w[n]; }
+        for (int c = 0; c < d; ++c) acc[c] = 0.0;
+        for (int64_t n = 0; n < M; ++n) {
+            if (w[n] == 0.0) continue;
+            int64_t pn = idx ? idx[n] : n;
+            double p = w[n] / den;
+            for (int c = 0; c < d; ++c) acc[c] += p * load_elem(V, pn * v_tok_stride + g * v_head_stride + c, dtype);
+        }
+        for (int c = 0; c < d; ++c) {
+            int64_t o = o_base + h * o_head_stride + c;
+            if (dtype == ORACLE_BF16) ((uint16_t*)O)[o] = double_to_bf16_bits(acc[c]);
+            else ((float*)O)[o] = (float)acc[c];
+        }
+    }
+}
+
+/* rows == NULL: every kept query m < M, written to O row m.  rows != NULL: only the listed kept queries, written to O
+ * rows 0 .. n_rows-1 (spot checks at sizes where all M queries would take hours). */
 int oracle_kept_attention(const void* Q, const void* K, const void* V, int64_t S, int32_t H, int32_t H_kv, int32_t d, int dtype,
                           int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
                           int64_t v_tok_stride, int64_t v_head_stride, const int32_t* idx, int64_t M, double scale,
-                          uint32_t flags, void* O, int64_t o_tok_stride, int64_t o_head_stride) {
+                          uint32_t flags, const int64_t* rows, int64_t n_rows, void* O, int64_t o_tok_stride, int64_t o_head_stride) {
     if (!Q || !K || !V || !O || S <= 0 || M < 0 || H <= 0 || H_kv <= 0 || d <= 0 || H % H_kv) return ORACLE_ERR_ARG;
     if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_ERR_ARG;
     if (!idx && M > S) return ORACLE_ERR_ARG;
@@ -525,45 +563,23 @@ int oracle_kept_attention(const void* Q, const void* K, const void* V, int64_t S
         int64_t r = idx ? idx[m] : m;
         if (r < 0 || r >= S) return ORACLE_ERR_ARG;
     }
+    if (!rows) n_rows = M;
+    for (int64_t t = 0; rows && t < n_rows; ++t)
+        if (rows[t] < 0 || rows[t] >= M) return ORACLE_ERR_ARG;
     if (!(scale > 0.0)) scale = 1.0 / sqrt((double)d);
     const int causal = (flags & ORACLE_CAUSAL) != 0;
     int fail = 0;
 #pragma omp parallel for schedule(dynamic, 1)
-    for (int64_t m = M - 1; m >= 0; --m) {
+    for (int64_t t = n_rows - 1; t >= 0; --t) {
         double* w = (double*)malloc(sizeof(double) * (size_t)(M > 0 ? M : 1));
-        double* out = (double*)malloc(sizeof(double) * (size_t)d);
-        if (!w || !out) { fail = 1; free(w); free(out); continue; }
-        int64_t pm = idx ? idx[m] : m;
-        for (int h = 0; h < H; ++h) {
-            int g = (int)(((int64_t)h * H_kv) / H);
-            double mx = -INFINITY;
-            for (int64_t n = 0; n < M; ++n) {
-                int64_t pn = idx ? idx[n] : n;
-                if (causal && pn > pm) { w[n] = -INFINITY; continue; }
-                double dot = 0.0;
-                for (int c = 0; c < d; ++c)
-                    dot += load_elem(Q, pm * q_tok_stride + h * q_head_stride + c, dtype) *
-                           load_elem(K, pn * k_tok_stride + g * k_head_stride + c, dtype);
-                w[n] = scale * dot;
-                if (w[n] > mx) mx = w[n];
-            }
-            double den = 0.0;
-            for (int64_t n = 0; n < M; ++n) { w[n] = (w[n] == -INFINITY) ? 0.0 : exp(w[n] - mx); den += w[n]; }
-            for (int c = 0; c < d; ++c) out[c] = 0.0;
-            for (int64_t n = 0; n < M; ++n) {
-                if (w[n] == 0.0) continue;
-                int64_t pn = idx ? idx[n] : n;
-                double p = w[n] / den;
-                for (int c = 0; c < d; ++c) out[c] += p * load_elem(V, pn * v_tok_stride + g * v_head_stride + c, dtype);
-            }
-            for (int c = 0; c < d; ++c) {
-                int64_t o = m * o_tok_stride + h * o_head_stride + c;
-                if (dtype == ORACLE_BF16) ((uint16_t*)O)[o] = double_to_bf16_bits(out[c]);
-                else ((float*)O)[o] = (float)out[c];
-            }
-        }
+        double* acc = (double*)malloc(sizeof(double) * (size_t)d);
+        if (w && acc)
+            attention_one_query(Q, K, V, H, H_kv, d, dtype, q_tok_stride, q_head_stride, k_tok_stride, k_head_stride, v_tok_stride,
+                                v_head_stride, idx, M, scale, causal, rows ? rows[t] : t, O, t * o_tok_stride, o_head_stride, w, acc);
+        else
+            fail = 1;
         free(w);
-        free(out);
+        free(acc);
     }
     return fail ? ORACLE_ERR_NOMEM : ORACLE_OK;
 }

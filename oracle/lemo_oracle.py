@@ -62,7 +62,7 @@ def _load():
             lib.oracle_gather_gemm_add.restype = ctypes.c_int
             lib.oracle_gather_gemm_add.argtypes = [vp, i64, i64, vp, i64, vp, i64, vp, vp, i64, i64, vp, i32, i32, ctypes.c_int]
             lib.oracle_kept_attention.restype = ctypes.c_int
-            lib.oracle_kept_attention.argtypes = [vp, vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, i64, i64, vp, i64, dbl, u32, vp, i64, i64]
+            lib.oracle_kept_attention.argtypes = [vp, vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, i64, i64, vp, i64, dbl, u32, vp, i64, vp, i64, i64]
             lib.oracle_scatter_add.restype = ctypes.c_int
             lib.oracle_scatter_add.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, ctypes.c_int, ctypes.c_int, ctypes.c_int]
             lib.oracle_num_threads.restype = ctypes.c_int
@@ -282,8 +282,9 @@ def gather_gemm_add(X: np.ndarray, in_idx, W: np.ndarray, R: np.ndarray, out_idx
     return R
 
 
-def kept_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, idx, flags: int = CAUSAL, scale: float = 0.0) -> np.ndarray:
-    """Attention over the kept tokens (rows idx of Q, K, V; None = all) -> compact O [M,H,d] of the input dtype."""
+def kept_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, idx, flags: int = CAUSAL, scale: float = 0.0, rows=None) -> np.ndarray:
+    """Attention over the kept tokens (rows idx of Q, K, V; None = all) -> compact O [M,H,d] of the input dtype.
+    With ``rows`` (kept-query numbers) only those queries are computed -> [len(rows),H,d]."""
     S, H, Hkv, d, qts, qhs, kts, khs = _qk_layout(Q, K)
     dt = _dtype_code(Q)
     if _dtype_code(K) != dt or _dtype_code(V) != dt or V.shape != K.shape or V.strides[2] != V.itemsize:
@@ -293,10 +294,13 @@ def kept_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, idx, flags: int 
         M = idx.shape[0]
     else:
         M = S
-    O = np.empty((M, H, d), dtype=Q.dtype)
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+    n_rows = M if rows is None else len(rows)
+    O = np.empty((n_rows, H, d), dtype=Q.dtype)
     _check(_load().oracle_kept_attention(_ptr(Q), _ptr(K), _ptr(V), S, H, Hkv, d, dt, qts, qhs, kts, khs,
                                          V.strides[0] // V.itemsize, V.strides[1] // V.itemsize, _ptr(idx), M, float(scale), flags,
-                                         _ptr(O), H * d, d), "oracle_kept_attention")
+                                         _ptr(rows), n_rows, _ptr(O), H * d, d), "oracle_kept_attention")
     return O
 
 

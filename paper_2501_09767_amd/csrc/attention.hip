@@ -1,0 +1,308 @@
+// Attention over the kept tokens, read in place (Sec. 4.4: the block loads the selected tokens straight from the
+// original inputs; no re-permuted copy of Q or K is made).
+//
+//   O[m,h,:] = sum_n softmax_n(scale * <Q[idx[m],h], K[idx[n],g]>) V[idx[n],g,:]        g = floor(h * H_kv / H)
+//
+// A workgroup owns 256 kept queries of one head (4 waves x 64), their rows gathered through idx into MFMA fragments that
+// stay in registers, and walks the kept keys in stages of 128 through two LDS stages.  Both products are computed
+// transposed so that a lane owns one QUERY column throughout:
+//   S^T = K Q^T       acc[key row][query col]: the 16 logits a lane holds belong to one query -> the online softmax is
+//                     an in-register chain; the two half-waves (which hold the other 16 keys of the same query) agree
+//                     on the running maximum with one cross-lane exchange per tile
+//   O^T += V^T P^T    the B operand (P^T: 8 keys per lane for its query column) is exactly what the lane already holds:
+//                     registers 8c..8c+7 of the logit tile are keys 16c + 4*half + {0..3} and 16c + 8 + 4*half + {0..3},
+//                     and since a dot product does not care in which order its terms are paired, the A operand (V^T)
+//                     simply supplies the same keys in the same slots.
+// V^T needs the keys contiguous per value column, which the [token, head, d] layout does not offer; a small kernel first
+// writes the kept rows of V transposed ([H_kv, d, M] in the workspace; 2 bytes per kept element, once per call).
+// P is rounded to bf16 for the second product (as in every flash-attention kernel); the normaliser is summed from the
+// unrounded values.
+#include <mutex>
+
+#include "lemo_common.hpp"
+
+namespace lemo {
+
+constexpr int AT_THREADS = 256;
+constexpr int AT_BQ = 256;  // queries per workgroup
+constexpr int AT_KT = 128;  // keys per LDS stage
+
+template <int D> struct AGeo {
+    static constexpr int ROWB = D * 2;            // bytes per head row (bf16)
+    static constexpr int NCH = ROWB / 32;         // MFMA chunks per K / Q row
+    static constexpr int CPR = ROWB / 16;         // 16-byte pieces per K row
+    static constexpr int KSTRIDE = ROWB + 16;     // LDS pitch of a K row
+    static constexpr int VSTRIDE = AT_KT * 2 + 16;  // LDS pitch of a V^T row (128 keys)
+    static constexpr int NDV = D / 32;            // 32-row tiles of the value dimension
+    static constexpr int NLK = AT_KT * CPR / AT_THREADS;  // K loads per thread and stage
+    static constexpr int K_RPL = AT_THREADS / CPR;        // K rows covered by one load of the workgroup
+    static constexpr int NLV = D * 16 / AT_THREADS;       // V^T loads per thread and stage (16 pieces per row)
+    static constexpr int STAGE = AT_KT * KSTRIDE + D * VSTRIDE;
+    static constexpr int LDS = 2 * STAGE;
+};
+
+struct AttnParams {
+    const uint16_t* Q;
+    const uint16_t* K;
+    const uint16_t* Vt;  // [H_kv, D, Mpad]
+    const int* idx;      // [M] or null
+    uint16_t* O;
+    int M, Mpad, H, H_kv;
+    long long q_ts, q_hs, k_ts, k_hs, o_ts, o_hs;  // element strides
+    unsigned q_bytes, k_bytes;                     // spans of Q and K (32-bit buffer offsets)
+    float c2;
+    unsigned flags;
+    int n_qblocks, heads_per_xcd;
+};
+
+// kept rows of V, transposed: Vt[g][c][m] = V[idx[m], g, c] for m < M, zero for M <= m < Mpad
+__global__ __launch_bounds__(256) void gather_vt_kernel(const uint16_t* __restrict__ V, long long v_ts, long long v_hs, const int* __restrict__ idx,
+                                                        int M, int Mpad, int D, uint16_t* __restrict__ Vt) {
+    __shared__ uint16_t tile[64][128 + 2];
+    const int m0 = blockIdx.x * 64, g = blockIdx.y, tid = threadIdx.x;
+    // load 64 kept rows x D values: thread -> (row = tid / 16 + 16 * i, 8 values at (tid % 16) * 8)
+    for (int i = 0; i < 4; ++i) {
+        const int row = tid / 16 + 16 * i, c0 = (tid % 16) * 8, m = m0 + row;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (m < M && c0 < D) {
+            const long long tok = idx ? idx[m] : m;
+            v = *reinterpret_cast<const u32x4*>(V + tok * v_ts + (long long)g * v_hs + c0);
+        }
+        if (c0 < D) {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) tile[row][c0 + e] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+        }
+    }
+    __syncthreads();
+    // store: value column c, 64 consecutive kept tokens = 128 bytes; thread -> (c = tid / 8 + 32 * i, 8 tokens at (tid % 8) * 8)
+    for (int i = 0; i < 4; ++i) {
+        const int c = tid / 8 + 32 * i, r0 = (tid % 8) * 8;
+        if (c < D) {
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = (uint32_t)tile[r0 + 2 * e][c] | ((uint32_t)tile[r0 + 2 * e + 1][c] << 16);
+            *reinterpret_cast<u32x4*>(Vt + ((long long)g * D + c) * Mpad + m0 + r0) = u32x4{w[0], w[1], w[2], w[3]};
+        }
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParams p) {
+    using G = AGeo<D>;
+    using T = bf16_t;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    // block -> (head, query block): die b % 8 gets a contiguous range of heads; late query blocks (most keys) first
+    const int b = blockIdx.x, x = b % NUM_XCD, w_ = b / NUM_XCD;
+    const int slot = w_ / p.n_qblocks;
+    int qb = w_ - slot * p.n_qblocks;
+    const int h = x * p.heads_per_xcd + slot;
+    if (h >= p.H) return;
+    const bool causal = (p.flags & LEMO_CAUSAL) != 0;
+    if (causal) qb = p.n_qblocks - 1 - qb;
+    const int g = (int)(((long long)h * p.H_kv) / p.H);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    const int M = p.M;
+    const float c2 = p.c2;
+    const int m0 = qb * AT_BQ, mw0 = m0 + wave * 64;
+
+    // resident operand: this wave's 64 queries (rows gathered through idx), as MFMA B fragments
+    u32x4 qf[2][G::NCH];
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+        const int m = mw0 + qs * 32 + l32;
+        const long long tok = m < M ? (p.idx ? (long long)p.idx[m] : (long long)m) : -1;
+#pragma unroll
+        for (int c = 0; c < G::NCH; ++c) {
+            qf[qs][c] = u32x4{0u, 0u, 0u, 0u};
+            if (tok >= 0) qf[qs][c] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.Q + tok * p.q_ts + (long long)h * p.q_hs) + c * 32 + half * 16);
+        }
+    }
+
+    // O^T accumulators: o[qs][dv][r] = element (value row dv*32 + acc_row(r), query column l32 of subtile qs)
+    f32x16 o[2][G::NDV];
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+        for (int dv = 0; dv < G::NDV; ++dv) o[qs][dv] = f32x16{0};
+    float mrun[2] = {-INFINITY, -INFINITY};  // running maximum (base-2 units), identical in both half-waves
+    float lrun[2] = {0.f, 0.f};              // this half-wave's share of the normaliser
+
+    const int k_last = causal ? min(m0 + AT_BQ, M) - 1 : M - 1;
+    const int nstage = k_last / AT_KT + 1;
+
+    // staging.  K rows are gathered through idx (32-bit offsets into a range-checked descriptor of the whole K tensor);
+    // V^T rows are contiguous in the workspace.
+    const int k_row = tid / G::CPR, k_cc = tid % G::CPR;
+    const int k_row_bytes = (int)p.k_ts * 2;
+    const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(p.K + (long long)g * p.k_hs)), 0, (int)(p.k_bytes - (unsigned)(g * p.k_hs * 2)), 0x00020000);
+    const int v_row = tid / 16, v_cc = tid % 16;
+    const uint16_t* vt_head = p.Vt + (long long)g * D * p.Mpad;
+    u32x4 prek[G::NLK], prev_[G::NLV];
+    auto fetch = [&](int t) {
+        const int n0 = t * AT_KT;
+#pragma unroll
+        for (int i = 0; i < G::NLK; ++i) {
+            const int n = min(n0 + k_row + i * G::K_RPL, M - 1);  // rows past the end repeat the last kept row (masked later)
+            const unsigned tok = p.idx ? (unsigned)p.idx[n] : (unsigned)n;
+            prek[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(tok * (unsigned)k_row_bytes + (unsigned)k_cc * 16u), 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < G::NLV; ++i)  // Mpad is a multiple of the stage length: always in range
+            prev_[i] = *reinterpret_cast<const u32x4*>(vt_head + (long long)(v_row + i * 16) * p.Mpad + n0 + v_cc * 8);
+    };
+    auto stash = [&](int buf) {
+        char* s = smem + buf * G::STAGE;
+#pragma unroll
+        for (int i = 0; i < G::NLK; ++i) *reinterpret_cast<u32x4*>(s + (k_row + i * G::K_RPL) * G::KSTRIDE + k_cc * 16) = prek[i];
+#pragma unroll
+        for (int i = 0; i < G::NLV; ++i) *reinterpret_cast<u32x4*>(s + AT_KT * G::KSTRIDE + (v_row + i * 16) * G::VSTRIDE + v_cc * 16) = prev_[i];
+    };
+
+    fetch(0);
+    stash(0);
+    for (int t = 0; t < nstage; ++t) {
+        __syncthreads();  // stage t is complete; every wave is done reading stage t-1
+        const bool more = t + 1 < nstage;
+        if (more) fetch(t + 1);
+        const int k0 = t * AT_KT;
+        const char* sk = smem + (t & 1) * G::STAGE;
+        const char* sv = sk + AT_KT * G::KSTRIDE;
+        if (!(causal && k0 > mw0 + 63)) {  // otherwise every key of the stage lies after every query of the wave
+#pragma unroll 1
+            for (int ks = 0; ks < AT_KT / 32; ++ks) {
+                const int kmin = k0 + ks * 32;
+                if (kmin >= M || (causal && kmin > mw0 + 63)) break;
+                u32x4 kf[G::NCH];
+#pragma unroll
+                for (int c = 0; c < G::NCH; ++c) kf[c] = *reinterpret_cast<const u32x4*>(&sk[(ks * 32 + l32) * G::KSTRIDE + c * 32 + half * 16]);
+                // V^T fragments of this key subtile: value row dv*32 + l32, keys 16c + 4*half + {0..3} and 16c + 8 + 4*half + {0..3}
+                u32x4 vf[G::NDV][2];
+#pragma unroll
+                for (int dv = 0; dv < G::NDV; ++dv)
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) {
+                        const char* a = &sv[(dv * 32 + l32) * G::VSTRIDE + (ks * 32 + 16 * c + 4 * half) * 2];
+                        const uint2 lo = *reinterpret_cast<const uint2*>(a), hi = *reinterpret_cast<const uint2*>(a + 16);
+                        vf[dv][c] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                    }
+#pragma unroll
+                for (int qs = 0; qs < 2; ++qs) {
+                    const int qmin = mw0 + qs * 32;
+                    if (causal && kmin > qmin + 31) continue;  // every key lies after every query (wave-uniform)
+                    f32x16 acc = {0};
+#pragma unroll
+                    for (int c = 0; c < G::NCH; ++c) mma_chunk<T>(acc, kf[c], qf[qs][c]);  // acc[key row][query col]
+                    const bool all_allowed = (kmin + 31 < M) && (!causal || kmin + 31 <= qmin);
+                    if (!all_allowed) {
+                        const int lim = causal ? min(qmin + l32, M - 1) : M - 1;  // last key this lane's query may use
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[r] = (kmin + acc_row(r, lane) <= lim) ? acc[r] : -INFINITY;
+                    }
+                    // online softmax of the lane's query over its 16 keys + the partner half-wave's 16
+                    float t0 = fmaxf(fmaxf(acc[0], acc[1]), acc[2]), t1 = fmaxf(fmaxf(acc[3], acc[4]), acc[5]);
+                    float t2 = fmaxf(fmaxf(acc[6], acc[7]), acc[8]), t3 = fmaxf(fmaxf(acc[9], acc[10]), acc[11]);
+                    float t4 = fmaxf(fmaxf(acc[12], acc[13]), acc[14]);
+                    float tmax = fmaxf(fmaxf(fmaxf(t0, t1), t2), fmaxf(fmaxf(t3, t4), acc[15])) * c2;
+                    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+                    const float mn = fmaxf(mrun[qs], tmax);
+                    const float ms = mn == -INFINITY ? 0.f : mn;  // nothing allowed so far (padding rows only): keep arguments finite
+                    const float corr = __builtin_amdgcn_exp2f(mrun[qs] - ms);
+                    float pr[16], s0 = 0.f, s1 = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        pr[r] = __builtin_amdgcn_exp2f(fmaf(acc[r], c2, -ms));
+                        if (r & 1) s1 += pr[r]; else s0 += pr[r];
+                    }
+                    lrun[qs] = fmaf(lrun[qs], corr, s0 + s1);
+                    if (__any(mn > mrun[qs])) {  // the reference moved for some query of the wave: rescale what has been summed
+#pragma unroll
+                        for (int dv = 0; dv < G::NDV; ++dv)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) o[qs][dv][r] *= corr;
+                    }
+                    mrun[qs] = mn;
+                    // P^T as B operand: registers 8c .. 8c+7 are this lane's 8 key slots of chunk c
+                    u32x4 pb[2];
+#pragma unroll
+                    for (int c = 0; c < 2; ++c)
+                        pb[c] = u32x4{pack_bf16x2_hw(pr[8 * c + 0], pr[8 * c + 1]), pack_bf16x2_hw(pr[8 * c + 2], pr[8 * c + 3]),
+                                      pack_bf16x2_hw(pr[8 * c + 4], pr[8 * c + 5]), pack_bf16x2_hw(pr[8 * c + 6], pr[8 * c + 7])};
+#pragma unroll
+                    for (int dv = 0; dv < G::NDV; ++dv)
+#pragma unroll
+                        for (int c = 0; c < 2; ++c) mma_chunk<T>(o[qs][dv], vf[dv][c], pb[c]);  // o[value row][query col]
+                }
+            }
+        }
+        if (more) stash((t + 1) & 1);
+    }
+
+    // normalise and store: lane (query l32, half) holds value rows 8*(r/4) + 4*half + r%4 of every 32-row tile
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+        const float ltot = lrun[qs] + __shfl_xor(lrun[qs], 32);
+        const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
+        const int m = mw0 + qs * 32 + l32;
+        if (m >= M) continue;
+        uint16_t* orow = p.O + (long long)m * p.o_ts + (long long)h * p.o_hs;
+#pragma unroll
+        for (int dv = 0; dv < G::NDV; ++dv)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int c0 = dv * 32 + gq * 8 + half * 4;
+                uint2 v;
+                v.x = pack_bf16x2_hw(o[qs][dv][gq * 4 + 0] * inv, o[qs][dv][gq * 4 + 1] * inv);
+                v.y = pack_bf16x2_hw(o[qs][dv][gq * 4 + 2] * inv, o[qs][dv][gq * 4 + 3] * inv);
+                *reinterpret_cast<uint2*>(orow + c0) = v;  // host guarantees 8-byte alignment of every output row
+            }
+    }
+}
+
+template <int D>
+static int launch_attn_t(AttnParams p, hipStream_t st) {
+    using G = AGeo<D>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&kept_attention_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS);
+    });
+    if (attr_err != hipSuccess) return (int)attr_err;
+    p.n_qblocks = (p.M + AT_BQ - 1) / AT_BQ;
+    p.heads_per_xcd = (p.H + NUM_XCD - 1) / NUM_XCD;
+    hipLaunchKernelGGL((kept_attention_kernel<D>), dim3((unsigned)(NUM_XCD * p.heads_per_xcd * p.n_qblocks)), dim3(AT_THREADS), G::LDS, st, p);
+    return (int)hipGetLastError();
+}
+
+// V [S,H_kv,d] element strides v_ts, v_hs; workspace holds V^T of the kept rows: H_kv * d * Mpad bf16
+int launch_kept_attention(const void* Q, const void* K, const void* V, long long S, int H, int H_kv, int d, long long q_ts, long long q_hs,
+                          long long k_ts, long long k_hs, long long v_ts, long long v_hs, const int* idx, long long M, float c2,
+                          unsigned flags, void* O, long long o_ts, long long o_hs, void* workspace, hipStream_t st) {
+    if (M == 0) return 0;
+    const int Mpad = (int)((M + AT_KT - 1) / AT_KT) * AT_KT;
+    uint16_t* Vt = static_cast<uint16_t*>(workspace);
+    hipLaunchKernelGGL(gather_vt_kernel, dim3((unsigned)(Mpad / 64), (unsigned)H_kv), dim3(256), 0, st, static_cast<const uint16_t*>(V), v_ts, v_hs,
+                       idx, (int)M, Mpad, d, Vt);
+    int rc = (int)hipGetLastError();
+    if (rc) return rc;
+    AttnParams p{};
+    p.Q = static_cast<const uint16_t*>(Q);
+    p.K = static_cast<const uint16_t*>(K);
+    p.Vt = Vt;
+    p.idx = idx;
+    p.O = static_cast<uint16_t*>(O);
+    p.M = (int)M;
+    p.Mpad = Mpad;
+    p.H = H;
+    p.H_kv = H_kv;
+    p.q_ts = q_ts; p.q_hs = q_hs; p.k_ts = k_ts; p.k_hs = k_hs; p.o_ts = o_ts; p.o_hs = o_hs;
+    p.q_bytes = (unsigned)(((S - 1) * q_ts + (long long)(H - 1) * q_hs + d) * 2);
+    p.k_bytes = (unsigned)(((S - 1) * k_ts + (long long)(H_kv - 1) * k_hs + d) * 2);
+    p.c2 = c2;
+    p.flags = flags;
+    return d == 128 ? launch_attn_t<128>(p, st) : launch_attn_t<64>(p, st);
+}
+
+}  // namespace lemo

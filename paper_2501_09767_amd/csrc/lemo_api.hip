@@ -234,6 +234,42 @@ int lemo_select_threshold(const float* token_blocks, int64_t S, int32_t b, float
                                           static_cast<hipStream_t>(stream)));
 }
 
+int lemo_kept_attention_workspace_bytes(int64_t M, int32_t H_kv, int32_t d, size_t* bytes) {
+    if (!bytes) return LEMO_ERR_NULL;
+    if (M < 0 || M >= (int64_t)1 << 31 || H_kv <= 0 || d <= 0) return LEMO_ERR_SHAPE;
+    const size_t Mpad = (size_t)((M + 127) / 128) * 128;
+    *bytes = round_up((size_t)H_kv * (size_t)d * Mpad * 2, 256);
+    if (*bytes == 0) *bytes = 256;
+    return LEMO_OK;
+}
+
+int lemo_kept_attention(const void* Q, const void* K, const void* V, int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt,
+                        int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                        int64_t v_tok_stride, int64_t v_head_stride, const int32_t* kept_idx, int64_t M, float scale, uint32_t flags,
+                        void* O, int64_t o_tok_stride, int64_t o_head_stride, void* workspace, size_t workspace_bytes, void* stream) {
+    ScoreParams sp;
+    const int rc = check_qk(Q, K, S, H, H_kv, d, dt, q_tok_stride, q_head_stride, k_tok_stride, k_head_stride, scale, flags & LEMO_CAUSAL, sp);
+    if (rc != LEMO_OK) return rc;
+    if (flags & ~(uint32_t)LEMO_CAUSAL) return LEMO_ERR_SHAPE;  // the self pair always takes part in attention
+    if (dt != LEMO_BF16) return LEMO_ERR_UNSUPPORTED;
+    if (M == 0) return LEMO_OK;
+    if (!V || !O || !workspace) return LEMO_ERR_NULL;
+    if (M < 0 || M >= (int64_t)1 << 31 || (!kept_idx && M > S)) return LEMO_ERR_SHAPE;
+    if (v_tok_stride < 0 || v_head_stride < 0 || o_tok_stride < d || o_head_stride < 0) return LEMO_ERR_SHAPE;
+    if (!aligned16(V) || !aligned16(O) || v_tok_stride % 8 || v_head_stride % 8 || o_tok_stride % 8 || o_head_stride % 8) return LEMO_ERR_ALIGN;
+    if (kept_idx && (reinterpret_cast<uintptr_t>(kept_idx) & 3u)) return LEMO_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return LEMO_ERR_ALIGN;
+    size_t need = 0;
+    lemo_kept_attention_workspace_bytes(M, H_kv, d, &need);
+    if (workspace_bytes < need) return LEMO_ERR_WORKSPACE;
+    // Q and K are addressed with 32-bit byte offsets
+    if (((S - 1) * q_tok_stride + (int64_t)(H - 1) * q_head_stride + d) * 2 >= ((int64_t)1 << 32)) return LEMO_ERR_UNSUPPORTED;
+    if (((S - 1) * k_tok_stride + (int64_t)(H_kv - 1) * k_head_stride + d) * 2 >= ((int64_t)1 << 32)) return LEMO_ERR_UNSUPPORTED;
+    return hip_rc(launch_kept_attention(Q, K, V, S, H, H_kv, d, q_tok_stride, q_head_stride, k_tok_stride, k_head_stride, v_tok_stride,
+                                        v_head_stride, kept_idx, M, sp.c2, flags, O, o_tok_stride, o_head_stride, workspace,
+                                        static_cast<hipStream_t>(stream)));
+}
+
 int lemo_gather_gemm(const void* X, int64_t S, int64_t ldx, const int32_t* kept_idx, int64_t M, const void* W, int64_t ldw,
                      const void* bias, void* Y, int64_t ldy, int32_t C, int32_t N, lemo_dtype_t dt, void* stream) {
     if (!valid_dtype(dt)) return LEMO_ERR_DTYPE;

@@ -23,7 +23,8 @@ LIB_PATH = os.path.join(_HERE, "liblemo_hip.so")
 EXPORTS = ("lemo_strerror", "lemo_keep_k", "lemo_kept_count", "lemo_score_workspace_bytes",
            "lemo_score_segments", "lemo_score_rowstats", "lemo_score_colsums", "lemo_score_head_mean",
            "lemo_select_topk", "lemo_gather_gemm", "lemo_gather_gemm_add", "lemo_scatter_grad",
-           "lemo_score_blocks_workspace_bytes", "lemo_score_blocks", "lemo_threshold_init", "lemo_select_threshold")
+           "lemo_score_blocks_workspace_bytes", "lemo_score_blocks", "lemo_threshold_init", "lemo_select_threshold",
+           "lemo_kept_attention_workspace_bytes", "lemo_kept_attention")
 
 
 class LemoError(RuntimeError):
@@ -64,6 +65,11 @@ def _load() -> ctypes.CDLL:
     lib.lemo_threshold_init.argtypes = [vp, i64, vp, vp]
     lib.lemo_select_threshold.restype = ctypes.c_int
     lib.lemo_select_threshold.argtypes = [vp, i64, i32, f32, vp, vp, vp, vp]
+    lib.lemo_kept_attention_workspace_bytes.restype = ctypes.c_int
+    lib.lemo_kept_attention_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.lemo_kept_attention.restype = ctypes.c_int
+    lib.lemo_kept_attention.argtypes = [vp, vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, i64, i64, vp, i64, f32, u32,
+                                        vp, i64, i64, vp, ctypes.c_size_t, vp]
     lib.lemo_select_topk.restype = ctypes.c_int
     lib.lemo_select_topk.argtypes = [vp, i64, i32, i32, vp, vp]
     lib.lemo_gather_gemm.restype = ctypes.c_int
@@ -353,6 +359,39 @@ def lemo_gather_gemm_add(X: torch.Tensor, kept_idx: Optional[torch.Tensor], W: t
     _check(_lib.lemo_gather_gemm_add(_ptr(X), S, X.stride(0), _ptr(kept_idx), M, _ptr(W), W.stride(0), _ptr(bias), _ptr(R),
                                      R.stride(0), R.shape[0], _ptr(out_idx), C, N, _dt(X), _stream()), "lemo_gather_gemm_add")
     return R
+
+
+def lemo_kept_attention_workspace_bytes(M: int, H_kv: int, d: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.lemo_kept_attention_workspace_bytes(M, H_kv, d, ctypes.byref(n)), "lemo_kept_attention_workspace_bytes")
+    return int(n.value)
+
+
+def lemo_kept_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, kept_idx: Optional[torch.Tensor], flags: int = CAUSAL,
+                        scale: float = 0.0, O: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                        M: Optional[int] = None) -> torch.Tensor:
+    """Attention over the kept rows of Q [S,H,d], K, V [S,H_kv,d] -> compact O [M,H,d]."""
+    a = _qk_args(Q, K)
+    _dev(V, kept_idx, O, workspace)
+    S, H, Hkv, d = a[2], a[3], a[4], a[5]
+    if V.dim() != 3 or tuple(V.shape) != tuple(K.shape) or V.stride(2) != 1 or V.dtype != K.dtype:
+        raise ValueError("V must match K: [S,H_kv,d], head_dim contiguous")
+    if kept_idx is not None:
+        if kept_idx.dtype != torch.int32 or kept_idx.dim() != 1 or not kept_idx.is_contiguous():
+            raise ValueError("kept_idx must be contiguous int32 [M]")
+        M = kept_idx.numel() if M is None else M
+    elif M is None:
+        M = S
+    if O is None:
+        O = torch.empty((M, H, d), dtype=Q.dtype, device=Q.device)
+    elif O.dtype != Q.dtype or O.dim() != 3 or O.shape[0] < M or O.shape[1] != H or O.shape[2] != d or O.stride(2) != 1:
+        raise ValueError("O must be [M,H,d] of the input dtype, head_dim contiguous")
+    if workspace is None:
+        workspace = torch.empty(lemo_kept_attention_workspace_bytes(M, Hkv, d), dtype=torch.uint8, device=Q.device)
+    _check(_lib.lemo_kept_attention(a[0], a[1], _ptr(V), *a[2:11], V.stride(0), V.stride(1), _ptr(kept_idx), M, float(scale), int(flags), _ptr(O),
+                                    O.stride(0) if M > 0 else H * d, O.stride(1) if M > 0 else d, _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream()), "lemo_kept_attention")
+    return O
 
 
 def lemo_scatter_grad(G: torch.Tensor, kept_idx: torch.Tensor, dX: torch.Tensor, mode: int = SCATTER_ACCUMULATE) -> torch.Tensor:

@@ -654,6 +654,93 @@ def test_gather_gemm_add_output_projection_shape_sampled(lemo):
     assert (g == o).mean() > 0.98
 
 
+# ------------------------------------------------------------------------------------ attention over the kept tokens
+
+def assert_attention_close(got_bits, want_bits, V_kept_bits):
+    """GPU: probabilities rounded to bf16 before the second product (2^-9 each, weights summing to one, so at most
+    2^-9 * max|V| in the output) and one output rounding (2^-9 relative); the test allows twice that."""
+    g = widen(got_bits).astype(np.float64)
+    o = widen(want_bits).astype(np.float64)
+    vmax = np.abs(widen(V_kept_bits)).max()
+    assert np.isfinite(g).all()
+    bad = np.abs(g - o) > 2.0 ** -7 * np.abs(o) + 2.0 ** -8 * vmax
+    assert not bad.any(), f"{bad.sum()} of {bad.size} outputs beyond tolerance, worst {np.abs(g - o).max():.3e}"
+    assert np.sqrt(np.mean((g - o) ** 2)) < 2.0 ** -9 * vmax  # and on average far inside it
+
+
+ATTN_CASES = [(300, 4, 2, 128, 130), (1000, 8, 2, 128, 517), (700, 2, 2, 64, 300), (64, 1, 1, 128, 1), (2000, 4, 4, 128, 1000),
+              (513, 4, 1, 64, 513)]
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("S,H,Hkv,d,M", ATTN_CASES)
+def test_kept_attention_small_shapes(lemo, S, H, Hkv, d, M, causal):
+    say(f"[attention] S={S} H={H}/{Hkv} d={d} M={M} causal={causal}")
+    Q, K = wl.tiny_qk(S, H, Hkv, d, "bf16", seed=S + M, heavy=5)
+    V = torch.from_numpy(np.random.default_rng(S).standard_normal((S, Hkv, d)).astype(np.float32)).to(torch.bfloat16)
+    idx = np.sort(np.random.default_rng(M).permutation(S)[:M]).astype(np.int32)
+    flags = lemo.CAUSAL if causal else 0
+    O = lemo.lemo_kept_attention(Q.cuda(), K.cuda(), V.cuda(), torch.from_numpy(idx).cuda(), flags=flags)
+    torch.cuda.synchronize()
+    want = oracle.kept_attention(wl.as_numpy(Q), wl.as_numpy(K), wl.as_numpy(V), idx, flags=flags)
+    assert_attention_close(wl.to_bf16_bits(O), want, wl.as_numpy(V)[idx])
+
+
+def test_kept_attention_options(lemo):
+    say("[attention] options")
+    S, H, Hkv, d, M = 600, 4, 2, 128, 333
+    Q, K = wl.tiny_qk(S, H, Hkv, d, "bf16", seed=9)
+    V = torch.from_numpy(np.random.default_rng(9).standard_normal((S, Hkv, d)).astype(np.float32)).to(torch.bfloat16)
+    idx = np.sort(np.random.default_rng(10).permutation(S)[:M]).astype(np.int32)
+    Qd, Kd, Vd, idxd = Q.cuda(), K.cuda(), V.cuda(), torch.from_numpy(idx).cuda()
+    O = lemo.lemo_kept_attention(Qd, Kd, Vd, idxd)
+    # gathered in place == the same kernel on materialised compact copies (the gather is exact), and repeatable
+    Oc = lemo.lemo_kept_attention(Qd[idxd.long()].contiguous(), Kd[idxd.long()].contiguous(), Vd[idxd.long()].contiguous(), None)
+    O2 = lemo.lemo_kept_attention(Qd, Kd, Vd, idxd)
+    torch.cuda.synchronize()
+    assert torch.equal(O, Oc) and torch.equal(O, O2)
+    # strided views of a fused QKV buffer, strided output, explicit scale
+    qkv = torch.zeros((S, H + 2 * Hkv, d), dtype=torch.bfloat16, device="cuda")
+    qkv[:, :H] = Qd; qkv[:, H:H + Hkv] = Kd; qkv[:, H + Hkv:] = Vd
+    Obig = torch.zeros((M, H + 1, d), dtype=torch.bfloat16, device="cuda")
+    lemo.lemo_kept_attention(qkv[:, :H], qkv[:, H:H + Hkv], qkv[:, H + Hkv:], idxd, scale=1.0 / math.sqrt(d), O=Obig[:, :H])
+    torch.cuda.synchronize()
+    assert torch.equal(Obig[:, :H], O) and not Obig[:, H].any()
+    # dropped tokens have no influence
+    Q2, K2, V2 = Qd.clone(), Kd.clone(), Vd.clone()
+    drop = torch.from_numpy(np.setdiff1d(np.arange(S), idx)).cuda()
+    Q2[drop] += 3.0; K2[drop] -= 2.0; V2[drop] *= 5.0
+    assert torch.equal(lemo.lemo_kept_attention(Q2, K2, V2, idxd), O)
+    # refused: fp32 inputs, the self-exclusion flag; M == 0 is a no-op
+    with pytest.raises(lemo.LemoError) as e:
+        lemo.lemo_kept_attention(Qd.float(), Kd.float(), Vd.float(), idxd)
+    assert e.value.code == -6
+    with pytest.raises(lemo.LemoError):
+        lemo.lemo_kept_attention(Qd, Kd, Vd, idxd, flags=lemo.CAUSAL | lemo.EXCLUDE_SELF)
+    assert lemo.lemo_kept_attention(Qd, Kd, Vd, torch.empty(0, dtype=torch.int32, device="cuda")).shape == (0, H, d)
+
+
+def test_kept_attention_full_size_sampled(lemo):
+    """The 32K-token layer with its 9856 kept tokens and all 32 heads, as the bench runs it: sampled kept queries (all
+    heads, all value columns) against the oracle; every output finite."""
+    cfg = wl.CONFIGS["C5"]
+    lay = wl.make_layer(cfg, want_gemm=False, device="cuda")
+    say("[attention] C5: inputs")
+    rng = np.random.default_rng(cfg.seed + 300)
+    V = torch.from_numpy(rng.standard_normal((cfg.S, cfg.H_kv, cfg.d), dtype=np.float32)).to(torch.bfloat16)
+    idx = oracle.select_topk(rng.random(cfg.S).astype(np.float32), cfg.L, cfg.k)
+    say("[attention] C5: GPU")
+    O = lemo.lemo_kept_attention(lay["Q"], lay["K"], V.cuda(), torch.from_numpy(idx).cuda())
+    torch.cuda.synchronize()
+    got = wl.to_bf16_bits(O)
+    assert np.isfinite(widen(got)).all()
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 255, 256, cfg.M - 257, cfg.M - 1], rng.integers(0, cfg.M, 8)]))
+    say(f"[attention] C5: oracle on {len(rows)} kept queries")
+    Vn = wl.as_numpy(V)
+    want = oracle.kept_attention(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), Vn, idx, rows=rows)
+    assert_attention_close(got[rows], want, Vn[idx])
+
+
 # ------------------------------------------------------------------------------------ scatter-add
 
 @pytest.mark.parametrize("gdt,xdt", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32"), ("f32", "bf16")])

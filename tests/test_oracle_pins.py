@@ -588,6 +588,9 @@ def test_kept_attention_special_cases():
         np.testing.assert_allclose(got[:, h], want, rtol=1e-6, atol=1e-7)
     got = oracle.kept_attention(Z, K, V, idx, flags=0)
     np.testing.assert_allclose(got[3, 1], V[idx, 0].astype(np.float64).mean(axis=0), rtol=1e-6, atol=1e-7)
+    # a list of queries computes just those rows of the full result
+    full = oracle.kept_attention(Q, K, V, idx)
+    np.testing.assert_array_equal(oracle.kept_attention(Q, K, V, idx, rows=[0, 7, M - 1]), full[[0, 7, M - 1]])
     # no index list == the first M tokens; all tokens kept == ordinary attention; first kept token attends to itself only
     np.testing.assert_array_equal(oracle.kept_attention(Q, K, V, None), oracle.kept_attention(Q, K, V, np.arange(S, dtype=np.int32)))
     first = oracle.kept_attention(Q, K, V, idx, flags=CAUSAL)[0]
