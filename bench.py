@@ -180,6 +180,29 @@ def measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, Y, reps=10):
             "folded_ms": round(t_fold, 5), "unfolded_ms": round(t_unf, 5), "bytes_saved": 2.0 * cfg.M * cfg.C * esz}
 
 
+def measure_kept_attention(cfg, lemo, ev, stream, Q, K, kept, reps=5):
+    """Outside the timed step: causal attention over the M kept tokens of the layer, Q/K rows read in place through
+    kept_idx (Sec. 4.4).  4*d flops per allowed (query, key) pair and head (both products)."""
+    import torch
+    M, H, d = cfg.M, cfg.H, cfg.d
+    g = torch.Generator(device="cuda").manual_seed(11)
+    V = torch.randn(tuple(K.shape), device="cuda", dtype=torch.float32, generator=g).to(K.dtype)
+    O = torch.empty((M, H, d), dtype=Q.dtype, device="cuda")
+    ws = torch.empty(lemo.lemo_kept_attention_workspace_bytes(M, cfg.H_kv, d), dtype=torch.uint8, device="cuda")
+    fn = lambda: lemo.lemo_kept_attention(Q, K, V, kept, O=O, workspace=ws)
+    fn()
+    marks = [ev.create() for _ in range(reps + 1)]
+    ev.record(marks[0], stream)
+    for i in range(reps):
+        fn()
+        ev.record(marks[i + 1], stream)
+    torch.cuda.synchronize()
+    ms = sum(ev.elapsed_ms(marks[i], marks[i + 1]) for i in range(reps)) / reps
+    flops = 4.0 * d * H * M * (M + 1) / 2
+    return {"what": f"causal attention over the M={M} kept tokens, {H} heads, rows read in place", "ms": round(ms, 5),
+            "tflops": round(flops / ms * 1e-9, 2)}
+
+
 def measure_block_scoring(cfg, lemo, ev, stream, Q, K, lse2, flags, b=64, reps=5):
     """Outside the timed step: the paper's own criterion (Sec. 4.2 Eq. 2): block-wise informativeness with b x b score
     blocks from the row statistics sweep 1 already produced, then the initial threshold of Alg. 1 and the threshold
@@ -347,6 +370,8 @@ def main():
     }
     out["gather_fold"] = measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, Y)
     out["fused_in_place_add"] = measure_fused_output_projection(cfg, lemo, ev, stream, kept)
+    if cfg.dtype == "bf16":
+        out["kept_attention"] = measure_kept_attention(cfg, lemo, ev, stream, Q, K, kept)
     out["block_wise"] = measure_block_scoring(cfg, lemo, ev, stream, Q, K, lse2, flags)
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)

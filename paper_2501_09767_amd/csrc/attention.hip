@@ -143,12 +143,19 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
     u32x4 prek[G::NLK], prev_[G::NLV];
     auto fetch = [&](int t) {
         const int n0 = t * AT_KT;
+        // all row indices first, in one batch (no load of a row waits behind the index of another);
+        // rows past the end repeat the last kept row (masked later)
+        unsigned tok[G::NLK];
+        if (p.idx) {
 #pragma unroll
-        for (int i = 0; i < G::NLK; ++i) {
-            const int n = min(n0 + k_row + i * G::K_RPL, M - 1);  // rows past the end repeat the last kept row (masked later)
-            const unsigned tok = p.idx ? (unsigned)p.idx[n] : (unsigned)n;
-            prek[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(tok * (unsigned)k_row_bytes + (unsigned)k_cc * 16u), 0, 0);
+            for (int i = 0; i < G::NLK; ++i) tok[i] = (unsigned)p.idx[min(n0 + k_row + i * G::K_RPL, M - 1)];
+        } else {
+#pragma unroll
+            for (int i = 0; i < G::NLK; ++i) tok[i] = (unsigned)min(n0 + k_row + i * G::K_RPL, M - 1);
         }
+#pragma unroll
+        for (int i = 0; i < G::NLK; ++i)
+            prek[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(tok[i] * (unsigned)k_row_bytes + (unsigned)k_cc * 16u), 0, 0);
 #pragma unroll
         for (int i = 0; i < G::NLV; ++i)  // Mpad is a multiple of the stage length: always in range
             prev_[i] = *reinterpret_cast<const u32x4*>(vt_head + (long long)(v_row + i * 16) * p.Mpad + n0 + v_cc * 8);
