@@ -3,8 +3,8 @@
 //
 //   O[m,h,:] = sum_n softmax_n(scale * <Q[idx[m],h], K[idx[n],g]>) V[idx[n],g,:]        g = floor(h * H_kv / H)
 //
-// A workgroup owns 256 kept queries of one head (4 waves x 64), their rows gathered through idx into MFMA fragments that
-// stay in registers, and walks the kept keys in stages of 128 through two LDS stages.  Both products are computed
+// A workgroup owns 128 kept queries of one head (4 waves x 32), their rows gathered through idx into MFMA fragments that
+// stay in registers, and walks the kept keys in stages of 64 through two LDS stages.  Both products are computed
 // transposed so that a lane owns one QUERY column throughout:
 //   S^T = K Q^T       acc[key row][query col]: the 16 logits a lane holds belong to one query -> the online softmax is
 //                     an in-register chain; the two half-waves (which hold the other 16 keys of the same query) agree
@@ -24,8 +24,13 @@
 namespace lemo {
 
 constexpr int AT_THREADS = 256;
-constexpr int AT_BQ = 256;  // queries per workgroup
-constexpr int AT_KT = 128;  // keys per LDS stage
+// Two workgroups per CU (two waves per SIMD: while one wave does its softmax arithmetic the other has the matrix core),
+// so a wave keeps ONE 32-query subtile: 64 accumulator registers for O^T instead of 128, and a workgroup's two LDS
+// stages of 64 keys fit twice into the CU's 160 KB.
+constexpr int AT_NQ = 1;             // 32-query subtiles per wave
+constexpr int AT_BQ = 128 * AT_NQ;   // queries per workgroup
+constexpr int AT_KT = 64;            // keys per LDS stage
+constexpr int AT_MPAD = 128;         // the transposed V is padded to a multiple of this many kept tokens
 
 template <int D> struct AGeo {
     static constexpr int ROWB = D * 2;            // bytes per head row (bf16)
@@ -36,7 +41,9 @@ template <int D> struct AGeo {
     static constexpr int NDV = D / 32;            // 32-row tiles of the value dimension
     static constexpr int NLK = AT_KT * CPR / AT_THREADS;  // K loads per thread and stage
     static constexpr int K_RPL = AT_THREADS / CPR;        // K rows covered by one load of the workgroup
-    static constexpr int NLV = D * 16 / AT_THREADS;       // V^T loads per thread and stage (16 pieces per row)
+    static constexpr int VCPR = AT_KT * 2 / 16;           // 16-byte pieces per V^T row of a stage
+    static constexpr int NLV = D * VCPR / AT_THREADS;     // V^T loads per thread and stage
+    static constexpr int V_RPL = AT_THREADS / VCPR;       // V^T rows covered by one load of the workgroup
     static constexpr int STAGE = AT_KT * KSTRIDE + D * VSTRIDE;
     static constexpr int LDS = 2 * STAGE;
 };
@@ -88,7 +95,7 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(const uint16_t* __restri
 }
 
 template <int D>
-__global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParams p) {
+__global__ __launch_bounds__(AT_THREADS, 2) void kept_attention_kernel(AttnParams p) {
     using G = AGeo<D>;
     using T = bf16_t;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -105,12 +112,12 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
     const int M = p.M;
     const float c2 = p.c2;
-    const int m0 = qb * AT_BQ, mw0 = m0 + wave * 64;
+    const int m0 = qb * AT_BQ, mw0 = m0 + wave * 32 * AT_NQ;
 
     // resident operand: this wave's 64 queries (rows gathered through idx), as MFMA B fragments
-    u32x4 qf[2][G::NCH];
+    u32x4 qf[AT_NQ][G::NCH];
 #pragma unroll
-    for (int qs = 0; qs < 2; ++qs) {
+    for (int qs = 0; qs < AT_NQ; ++qs) {
         const int m = mw0 + qs * 32 + l32;
         const long long tok = m < M ? (p.idx ? (long long)p.idx[m] : (long long)m) : -1;
 #pragma unroll
@@ -121,13 +128,14 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
     }
 
     // O^T accumulators: o[qs][dv][r] = element (value row dv*32 + acc_row(r), query column l32 of subtile qs)
-    f32x16 o[2][G::NDV];
+    f32x16 o[AT_NQ][G::NDV];
 #pragma unroll
-    for (int qs = 0; qs < 2; ++qs)
+    for (int qs = 0; qs < AT_NQ; ++qs)
 #pragma unroll
         for (int dv = 0; dv < G::NDV; ++dv) o[qs][dv] = f32x16{0};
-    float mrun[2] = {-INFINITY, -INFINITY};  // running maximum (base-2 units), identical in both half-waves
-    float lrun[2] = {0.f, 0.f};              // this half-wave's share of the normaliser
+    float mrun[AT_NQ], lrun[AT_NQ];  // running maximum (base-2 units, identical in both half-waves); this half-wave's share of the normaliser
+#pragma unroll
+    for (int qs = 0; qs < AT_NQ; ++qs) { mrun[qs] = -INFINITY; lrun[qs] = 0.f; }
 
     const int k_last = causal ? min(m0 + AT_BQ, M) - 1 : M - 1;
     const int nstage = k_last / AT_KT + 1;
@@ -138,7 +146,7 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
     const int k_row_bytes = (int)p.k_ts * 2;
     const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<char*>(reinterpret_cast<const char*>(p.K + (long long)g * p.k_hs)), 0, (int)(p.k_bytes - (unsigned)(g * p.k_hs * 2)), 0x00020000);
-    const int v_row = tid / 16, v_cc = tid % 16;
+    const int v_row = tid / G::VCPR, v_cc = tid % G::VCPR;
     const uint16_t* vt_head = p.Vt + (long long)g * D * p.Mpad;
     u32x4 prek[G::NLK], prev_[G::NLV];
     auto fetch = [&](int t) {
@@ -158,14 +166,14 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
             prek[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(tok[i] * (unsigned)k_row_bytes + (unsigned)k_cc * 16u), 0, 0);
 #pragma unroll
         for (int i = 0; i < G::NLV; ++i)  // Mpad is a multiple of the stage length: always in range
-            prev_[i] = *reinterpret_cast<const u32x4*>(vt_head + (long long)(v_row + i * 16) * p.Mpad + n0 + v_cc * 8);
+            prev_[i] = *reinterpret_cast<const u32x4*>(vt_head + (long long)(v_row + i * G::V_RPL) * p.Mpad + n0 + v_cc * 8);
     };
     auto stash = [&](int buf) {
         char* s = smem + buf * G::STAGE;
 #pragma unroll
         for (int i = 0; i < G::NLK; ++i) *reinterpret_cast<u32x4*>(s + (k_row + i * G::K_RPL) * G::KSTRIDE + k_cc * 16) = prek[i];
 #pragma unroll
-        for (int i = 0; i < G::NLV; ++i) *reinterpret_cast<u32x4*>(s + AT_KT * G::KSTRIDE + (v_row + i * 16) * G::VSTRIDE + v_cc * 16) = prev_[i];
+        for (int i = 0; i < G::NLV; ++i) *reinterpret_cast<u32x4*>(s + AT_KT * G::KSTRIDE + (v_row + i * G::V_RPL) * G::VSTRIDE + v_cc * 16) = prev_[i];
     };
 
     fetch(0);
@@ -177,11 +185,11 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
         const int k0 = t * AT_KT;
         const char* sk = smem + (t & 1) * G::STAGE;
         const char* sv = sk + AT_KT * G::KSTRIDE;
-        if (!(causal && k0 > mw0 + 63)) {  // otherwise every key of the stage lies after every query of the wave
+        if (!(causal && k0 > mw0 + 32 * AT_NQ - 1)) {  // otherwise every key of the stage lies after every query of the wave
 #pragma unroll 1
             for (int ks = 0; ks < AT_KT / 32; ++ks) {
                 const int kmin = k0 + ks * 32;
-                if (kmin >= M || (causal && kmin > mw0 + 63)) break;
+                if (kmin >= M || (causal && kmin > mw0 + 32 * AT_NQ - 1)) break;
                 u32x4 kf[G::NCH];
 #pragma unroll
                 for (int c = 0; c < G::NCH; ++c) kf[c] = *reinterpret_cast<const u32x4*>(&sk[(ks * 32 + l32) * G::KSTRIDE + c * 32 + half * 16]);
@@ -196,7 +204,7 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
                         vf[dv][c] = u32x4{lo.x, lo.y, hi.x, hi.y};
                     }
 #pragma unroll
-                for (int qs = 0; qs < 2; ++qs) {
+                for (int qs = 0; qs < AT_NQ; ++qs) {
                     const int qmin = mw0 + qs * 32;
                     if (causal && kmin > qmin + 31) continue;  // every key lies after every query (wave-uniform)
                     f32x16 acc = {0};
@@ -213,7 +221,10 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
                     float t2 = fmaxf(fmaxf(acc[6], acc[7]), acc[8]), t3 = fmaxf(fmaxf(acc[9], acc[10]), acc[11]);
                     float t4 = fmaxf(fmaxf(acc[12], acc[13]), acc[14]);
                     float tmax = fmaxf(fmaxf(fmaxf(t0, t1), t2), fmaxf(fmaxf(t3, t4), acc[15])) * c2;
-                    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+                    {  // the other half-wave holds the other 16 keys of the same query: both take the larger maximum
+                        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+                        tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                    }
                     const float mn = fmaxf(mrun[qs], tmax);
                     const float ms = mn == -INFINITY ? 0.f : mn;  // nothing allowed so far (padding rows only): keep arguments finite
                     const float corr = __builtin_amdgcn_exp2f(mrun[qs] - ms);
@@ -249,7 +260,7 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
 
     // normalise and store: lane (query l32, half) holds value rows 8*(r/4) + 4*half + r%4 of every 32-row tile
 #pragma unroll
-    for (int qs = 0; qs < 2; ++qs) {
+    for (int qs = 0; qs < AT_NQ; ++qs) {
         const float ltot = lrun[qs] + __shfl_xor(lrun[qs], 32);
         const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
         const int m = mw0 + qs * 32 + l32;
@@ -288,7 +299,7 @@ int launch_kept_attention(const void* Q, const void* K, const void* V, long long
                           long long k_ts, long long k_hs, long long v_ts, long long v_hs, const int* idx, long long M, float c2,
                           unsigned flags, void* O, long long o_ts, long long o_hs, void* workspace, hipStream_t st) {
     if (M == 0) return 0;
-    const int Mpad = (int)((M + AT_KT - 1) / AT_KT) * AT_KT;
+    const int Mpad = (int)((M + AT_MPAD - 1) / AT_MPAD) * AT_MPAD;
     uint16_t* Vt = static_cast<uint16_t*>(workspace);
     hipLaunchKernelGGL(gather_vt_kernel, dim3((unsigned)(Mpad / 64), (unsigned)H_kv), dim3(256), 0, st, static_cast<const uint16_t*>(V), v_ts, v_hs,
                        idx, (int)M, Mpad, d, Vt);
