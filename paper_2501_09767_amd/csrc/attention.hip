@@ -133,7 +133,7 @@ __global__ __launch_bounds__(AT_THREADS, 2) void kept_attention_kernel(AttnParam
     for (int qs = 0; qs < AT_NQ; ++qs)
 #pragma unroll
         for (int dv = 0; dv < G::NDV; ++dv) o[qs][dv] = f32x16{0};
-    float mrun[AT_NQ], lrun[AT_NQ];  // running maximum (base-2 units, identical in both half-waves); this half-wave's share of the normaliser
+    float mrun[AT_NQ], lrun[AT_NQ];  // reference of the exponentials (base-2 units, identical in both half-waves); this half-wave's share of the normaliser
 #pragma unroll
     for (int qs = 0; qs < AT_NQ; ++qs) { mrun[qs] = -INFINITY; lrun[qs] = 0.f; }
 
@@ -149,11 +149,11 @@ __global__ __launch_bounds__(AT_THREADS, 2) void kept_attention_kernel(AttnParam
     const int v_row = tid / G::VCPR, v_cc = tid % G::VCPR;
     const uint16_t* vt_head = p.Vt + (long long)g * D * p.Mpad;
     u32x4 prek[G::NLK], prev_[G::NLV];
-    auto fetch = [&](int t) {
+    // Row indices run one stage ahead of the rows (tok holds the K rows of the stage about to be fetched), so a row load
+    // never waits behind its own index; rows past the end repeat the last kept row (masked later).
+    unsigned tok[G::NLK];
+    auto fetch_idx = [&](int t) {
         const int n0 = t * AT_KT;
-        // all row indices first, in one batch (no load of a row waits behind the index of another);
-        // rows past the end repeat the last kept row (masked later)
-        unsigned tok[G::NLK];
         if (p.idx) {
 #pragma unroll
             for (int i = 0; i < G::NLK; ++i) tok[i] = (unsigned)p.idx[min(n0 + k_row + i * G::K_RPL, M - 1)];
@@ -161,12 +161,16 @@ __global__ __launch_bounds__(AT_THREADS, 2) void kept_attention_kernel(AttnParam
 #pragma unroll
             for (int i = 0; i < G::NLK; ++i) tok[i] = (unsigned)min(n0 + k_row + i * G::K_RPL, M - 1);
         }
+    };
+    auto fetch = [&](int t) {  // needs tok = fetch_idx(t); leaves tok = fetch_idx(t + 1)
+        const int n0 = t * AT_KT;
 #pragma unroll
         for (int i = 0; i < G::NLK; ++i)
             prek[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(tok[i] * (unsigned)k_row_bytes + (unsigned)k_cc * 16u), 0, 0);
 #pragma unroll
-        for (int i = 0; i < G::NLV; ++i)  // Mpad is a multiple of the stage length: always in range
+        for (int i = 0; i < G::NLV; ++i)  // the padded length is a multiple of the stage length: always in range
             prev_[i] = *reinterpret_cast<const u32x4*>(vt_head + (long long)(v_row + i * G::V_RPL) * p.Mpad + n0 + v_cc * 8);
+        fetch_idx(t + 1);  // clamped to the last kept row, so any t is fine
     };
     auto stash = [&](int buf) {
         char* s = smem + buf * G::STAGE;
@@ -176,6 +180,7 @@ __global__ __launch_bounds__(AT_THREADS, 2) void kept_attention_kernel(AttnParam
         for (int i = 0; i < G::NLV; ++i) *reinterpret_cast<u32x4*>(s + AT_KT * G::KSTRIDE + (v_row + i * G::V_RPL) * G::VSTRIDE + v_cc * 16) = prev_[i];
     };
 
+    fetch_idx(0);
     fetch(0);
     stash(0);
     for (int t = 0; t < nstage; ++t) {
@@ -225,7 +230,10 @@ __global__ __launch_bounds__(AT_THREADS, 2) void kept_attention_kernel(AttnParam
                         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
                         tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
                     }
-                    const float mn = fmaxf(mrun[qs], tmax);
+                    // Lazy reference: the running reference only moves when the tile's maximum exceeds it by more than 2^8
+                    // (probabilities up to 256 are harmless in binary32 and bf16 keeps its relative precision), so
+                    // the rescale below becomes rare instead of happening in almost every tile for some query.
+                    const float mn = tmax > mrun[qs] + 8.f ? tmax : mrun[qs];
                     const float ms = mn == -INFINITY ? 0.f : mn;  // nothing allowed so far (padding rows only): keep arguments finite
                     const float corr = __builtin_amdgcn_exp2f(mrun[qs] - ms);
                     float pr[16], s0 = 0.f, s1 = 0.f;
