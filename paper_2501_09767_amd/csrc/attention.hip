@@ -3,8 +3,8 @@
 //
 //   O[m,h,:] = sum_n softmax_n(scale * <Q[idx[m],h], K[idx[n],g]>) V[idx[n],g,:]        g = floor(h * H_kv / H)
 //
-// A workgroup owns 128 kept queries of one head (4 waves x 32), their rows gathered through idx into MFMA fragments that
-// stay in registers, and walks the kept keys in stages of 64 through two LDS stages.  Both products are computed
+// A workgroup owns 256 kept queries of one head (8 waves x 32), their rows gathered through idx into MFMA fragments that
+// stay in registers, and walks the kept keys in stages of 128 through two LDS stages.  Both products are computed
 // transposed so that a lane owns one QUERY column throughout:
 //   S^T = K Q^T       acc[key row][query col]: the 16 logits a lane holds belong to one query -> the online softmax is
 //                     an in-register chain; the two half-waves (which hold the other 16 keys of the same query) agree
@@ -23,13 +23,13 @@
 
 namespace lemo {
 
-constexpr int AT_THREADS = 256;
-// Two workgroups per CU (two waves per SIMD: while one wave does its softmax arithmetic the other has the matrix core),
-// so a wave keeps ONE 32-query subtile: 64 accumulator registers for O^T instead of 128, and a workgroup's two LDS
-// stages of 64 keys fit twice into the CU's 160 KB.
-constexpr int AT_NQ = 1;             // 32-query subtiles per wave
-constexpr int AT_BQ = 128 * AT_NQ;   // queries per workgroup
-constexpr int AT_KT = 64;            // keys per LDS stage
+// Eight waves per workgroup (two per SIMD: while one wave does its softmax arithmetic the other has the matrix core),
+// each keeping ONE 32-query subtile: 64 accumulator registers for O^T, everything within 256 registers.  One workgroup
+// per CU with two LDS stages of 128 keys: a barrier every four tiles, and a stage of K and V^T is shared by 256 queries.
+constexpr int AT_THREADS = 512;
+constexpr int AT_NQ = 1;                            // 32-query subtiles per wave
+constexpr int AT_BQ = (AT_THREADS / 64) * 32 * AT_NQ;  // queries per workgroup
+constexpr int AT_KT = 128;                          // keys per LDS stage
 constexpr int AT_MPAD = 128;         // the transposed V is padded to a multiple of this many kept tokens
 
 template <int D> struct AGeo {
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(const uint16_t* __restri
 }
 
 template <int D>
-__global__ __launch_bounds__(AT_THREADS, 2) void kept_attention_kernel(AttnParams p) {
+__global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParams p) {
     using G = AGeo<D>;
     using T = bf16_t;
     extern __shared__ __attribute__((aligned(16))) char smem[];
