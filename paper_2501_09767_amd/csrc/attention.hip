@@ -62,7 +62,12 @@ struct AttnParams {
     int n_qblocks, heads_per_xcd;
 };
 
-// kept rows of V, transposed: Vt[g][c][m] = V[idx[m], g, c] for m < M, zero for M <= m < Mpad
+// Inside every group of 16 kept tokens the transposed V is stored with its two middle quads exchanged (tokens 0-3, 8-11,
+// 4-7, 12-15): the 8 key slots a lane feeds to the second MFMA are keys 4*half + {0..3} and 8 + 4*half + {0..3} of a
+// 16-key chunk, and in this order they are 16 contiguous bytes.  The permutation is its own inverse.
+__device__ __forceinline__ int vt_src(int pos) { return (pos & ~12) | ((pos & 4) << 1) | ((pos & 8) >> 1); }
+
+// kept rows of V, transposed: Vt[g][c][pos] = V[idx[vt_src(pos)], g, c] for kept tokens below M, zero up to Mpad
 __global__ __launch_bounds__(256) void gather_vt_kernel(const uint16_t* __restrict__ V, long long v_ts, long long v_hs, const int* __restrict__ idx,
                                                         int M, int Mpad, int D, uint16_t* __restrict__ Vt) {
     __shared__ uint16_t tile[64][128 + 2];
@@ -88,7 +93,7 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(const uint16_t* __restri
         if (c < D) {
             uint32_t w[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = (uint32_t)tile[r0 + 2 * e][c] | ((uint32_t)tile[r0 + 2 * e + 1][c] << 16);
+            for (int e = 0; e < 4; ++e) w[e] = (uint32_t)tile[vt_src(r0 + 2 * e)][c] | ((uint32_t)tile[vt_src(r0 + 2 * e + 1)][c] << 16);
             *reinterpret_cast<u32x4*>(Vt + ((long long)g * D + c) * Mpad + m0 + r0) = u32x4{w[0], w[1], w[2], w[3]};
         }
     }
@@ -199,14 +204,13 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
 #pragma unroll
                 for (int c = 0; c < G::NCH; ++c) kf[c] = *reinterpret_cast<const u32x4*>(&sk[(ks * 32 + l32) * G::KSTRIDE + c * 32 + half * 16]);
                 // V^T fragments of this key subtile: value row dv*32 + l32, keys 16c + 4*half + {0..3} and 16c + 8 + 4*half + {0..3}
+                // (contiguous in the quad-exchanged layout)
                 u32x4 vf[G::NDV][2];
 #pragma unroll
                 for (int dv = 0; dv < G::NDV; ++dv)
 #pragma unroll
                     for (int c = 0; c < 2; ++c) {
-                        const char* a = &sv[(dv * 32 + l32) * G::VSTRIDE + (ks * 32 + 16 * c + 4 * half) * 2];
-                        const uint2 lo = *reinterpret_cast<const uint2*>(a), hi = *reinterpret_cast<const uint2*>(a + 16);
-                        vf[dv][c] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                        vf[dv][c] = *reinterpret_cast<const u32x4*>(&sv[(dv * 32 + l32) * G::VSTRIDE + (ks * 32 + 16 * c + 8 * half) * 2]);
                     }
 #pragma unroll
                 for (int qs = 0; qs < AT_NQ; ++qs) {
