@@ -866,3 +866,31 @@ def test_whole_path_small_layer(lemo):
     want = np.zeros((cfg.S, cfg.C), dtype=np.uint16)
     oracle.scatter_add(wl.as_numpy(lay["G"]), kept_np, want)
     np.testing.assert_array_equal(wl.as_numpy(dX), want)
+
+
+def test_attention_block_flow(lemo):
+    """The attention block of Sec. 4.4 end to end on a small layer: score -> select -> attention over the kept tokens
+    (rows read in place) -> output projection added in place into the residual rows; each stage against the oracle fed
+    with the GPU's upstream result, and the dropped tokens' residual rows untouched."""
+    cfg = wl.scaled(wl.CONFIGS["C2"], S=1024, H=4, H_kv=2, C=512, N=512, L=256, ratio=0.5)
+    say("[flow] attention block")
+    lay = wl.make_layer(cfg)
+    rng = np.random.default_rng(77)
+    V = torch.from_numpy(rng.standard_normal((cfg.S, cfg.H_kv, cfg.d), dtype=np.float32)).to(torch.bfloat16)
+    Wo = torch.from_numpy(rng.standard_normal((cfg.C, cfg.H * cfg.d), dtype=np.float32) * np.float32(0.02)).to(torch.bfloat16)
+    R = torch.from_numpy(rng.standard_normal((cfg.S, cfg.C), dtype=np.float32)).to(torch.bfloat16)
+    Q, K = lay["Q"].cuda(), lay["K"].cuda()
+    scores = lemo.lemo_score_segments(Q, K, cfg.L)
+    kept = lemo.lemo_select_topk(scores, cfg.L, cfg.k)
+    O = lemo.lemo_kept_attention(Q, K, V.cuda(), kept)                       # [M, H, d], compact
+    Rd = R.cuda()
+    lemo.lemo_gather_gemm_add(O.view(cfg.M, cfg.H * cfg.d), None, Wo.cuda(), Rd, kept)
+    torch.cuda.synchronize()
+    kept_np = kept.cpu().numpy()
+    assert_selection_equivalent(kept_np, oracle.score(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"])), cfg.L, cfg.k)
+    want_O = oracle.kept_attention(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), wl.as_numpy(V), kept_np)
+    assert_attention_close(wl.to_bf16_bits(O), want_O, wl.as_numpy(V)[kept_np])
+    O2 = wl.to_bf16_bits(O).reshape(cfg.M, cfg.H * cfg.d)
+    before = wl.as_numpy(R)
+    want_R = oracle.gather_gemm_add(O2, None, wl.as_numpy(Wo), before.copy(), kept_np)
+    assert_gemm_add_close(wl.to_bf16_bits(Rd), want_R, before, O2, wl.as_numpy(Wo), kept_np)
