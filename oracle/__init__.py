@@ -10,6 +10,6 @@ module only compiles it with gcc and marshals numpy arrays into it.
 from .lemo_oracle import (  # noqa: F401
     BF16, F32, CAUSAL, EXCLUDE_SELF, SCATTER_ACCUMULATE, SCATTER_ZERO_PAD,
     build, num_threads, keep_k, kept_count, score, score_bruteforce, score_blocks, score_block_rows, select_threshold, threshold_init,
-    PROBABILITIES, POSITIVE_LOGITS, select_topk, gather_gemm, gather_gemm_add, kept_attention, scatter_add,
+    PROBABILITIES, POSITIVE_LOGITS, select_topk, gather_gemm, gather_gemm_add, gather_gemm_dw, kept_attention, scatter_add,
     double_to_bf16_bits, bf16_bits_to_float32, float32_to_bf16_bits,
 )

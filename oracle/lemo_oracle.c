@@ -21,6 +21,7 @@
  *                           Y[m,:] = X[idx[m],:] . W^T (+ bias).
  *   oracle_gather_gemm_add  Sec. 4.4, both halves fused: selective load on the way in, in-place add
  *                           into the residual rows on the way out.
+ *   oracle_gather_gemm_dw   weight gradient of the selective-load GEMM (the gather on the contraction axis).
  *   oracle_kept_attention   Sec. 4.4: the attention block computed over the kept tokens, read in place.
  *   oracle_scatter_add      Sec. 4.4 in-place add (padding and residual add in one step):
  *                           dX[idx[m],:] += G[m,:].
@@ -502,6 +503,32 @@ int oracle_gather_gemm_add(const void* X, int64_t S, int64_t ldx, const int32_t*
             else ((float*)R)[o * ldr + n] = (float)acc;
         }
     }
+    return ORACLE_OK;
+}
+
+/* Weight gradient of the selective-load GEMM Y = X[idx] W^T:  dW[n,c] = round( sum_m dY[m,n] * X[idx[m],c] ),
+ * the contraction running over the kept tokens (the gather sits on the contraction axis), sum in double, ONE rounding.
+ * dY [M,N] row stride ldy, X [S,C] row stride ldx, dW [N,C] row stride lddw; idx == NULL means rows 0..M-1. */
+int oracle_gather_gemm_dw(const void* dY, int64_t ldy, const void* X, int64_t S, int64_t ldx, const int32_t* idx, int64_t M,
+                          void* dW, int64_t lddw, int32_t C, int32_t N, int dtype) {
+    if (!dY || !X || !dW || S <= 0 || M < 0 || C <= 0 || N <= 0 || ldy < N || ldx < C || lddw < C) return ORACLE_ERR_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_ERR_ARG;
+    if (!idx && M > S) return ORACLE_ERR_ARG;
+    for (int64_t m = 0; m < M; ++m) {
+        int64_t r = idx ? idx[m] : m;
+        if (r < 0 || r >= S) return ORACLE_ERR_ARG;
+    }
+#pragma omp parallel for schedule(static)
+    for (int32_t n = 0; n < N; ++n)
+        for (int32_t c = 0; c < C; ++c) {
+            double acc = 0.0;
+            for (int64_t m = 0; m < M; ++m) {
+                int64_t r = idx ? idx[m] : m;
+                acc += load_elem(dY, m * ldy + n, dtype) * load_elem(X, r * ldx + c, dtype);
+            }
+            if (dtype == ORACLE_BF16) ((uint16_t*)dW)[(int64_t)n * lddw + c] = double_to_bf16_bits(acc);
+            else ((float*)dW)[(int64_t)n * lddw + c] = (float)acc;
+        }
     return ORACLE_OK;
 }
 

@@ -61,6 +61,8 @@ def _load():
             lib.oracle_gather_gemm.argtypes = [vp, i64, i64, vp, i64, vp, i64, vp, vp, i64, i32, i32, ctypes.c_int]
             lib.oracle_gather_gemm_add.restype = ctypes.c_int
             lib.oracle_gather_gemm_add.argtypes = [vp, i64, i64, vp, i64, vp, i64, vp, vp, i64, i64, vp, i32, i32, ctypes.c_int]
+            lib.oracle_gather_gemm_dw.restype = ctypes.c_int
+            lib.oracle_gather_gemm_dw.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp, i64, i32, i32, ctypes.c_int]
             lib.oracle_kept_attention.restype = ctypes.c_int
             lib.oracle_kept_attention.argtypes = [vp, vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, i64, i64, vp, i64, dbl, u32, vp, i64, vp, i64, i64]
             lib.oracle_scatter_add.restype = ctypes.c_int
@@ -280,6 +282,24 @@ def gather_gemm_add(X: np.ndarray, in_idx, W: np.ndarray, R: np.ndarray, out_idx
     _check(_load().oracle_gather_gemm_add(_ptr(X), S, C, _ptr(in_idx), M, _ptr(W), C, _ptr(bias), _ptr(R), N, R.shape[0],
                                           _ptr(out_idx), C, N, dt), "oracle_gather_gemm_add")
     return R
+
+
+def gather_gemm_dw(dY: np.ndarray, X: np.ndarray, idx) -> np.ndarray:
+    """dW[n,c] = sum_m dY[m,n] * X[idx[m],c] (fp64, one rounding) -> [N,C] of the input dtype."""
+    dY = np.ascontiguousarray(dY)
+    X = np.ascontiguousarray(X)
+    dt = _dtype_code(X)
+    if _dtype_code(dY) != dt:
+        raise TypeError("dY and X must share a dtype")
+    M, N = dY.shape
+    S, C = X.shape
+    if idx is not None:
+        idx = np.ascontiguousarray(idx, dtype=np.int32)
+        if idx.shape[0] != M:
+            raise ValueError("idx must have one entry per row of dY")
+    dW = np.empty((N, C), dtype=X.dtype)
+    _check(_load().oracle_gather_gemm_dw(_ptr(dY), N, _ptr(X), S, C, _ptr(idx), M, _ptr(dW), C, C, N, dt), "oracle_gather_gemm_dw")
+    return dW
 
 
 def kept_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, idx, flags: int = CAUSAL, scale: float = 0.0, rows=None) -> np.ndarray:

@@ -524,6 +524,32 @@ def test_gemm_add_single_rounding_and_special_cases():
         oracle.gather_gemm_add(X, idx, W, R0.copy(), bad)
 
 
+# ------------------------------------------------------------------------------ weight gradient of the selective-load GEMM
+
+def test_gemm_dw_against_numpy_and_adjoint():
+    """dW = dY^T X[idx]: exact against numpy float64 on a dyadic grid (bf16 and fp32); and the adjoint identity that
+    ties it to the forward oracle: <dY, X[idx] W^T> == <dY^T X[idx], W> for any W."""
+    rng = np.random.default_rng(51)
+    S, C, N, M = 50, 24, 20, 31
+    X = (rng.integers(-8, 9, (S, C)) / 4.0).astype(np.float32)
+    dY = (rng.integers(-8, 9, (M, N)) / 8.0).astype(np.float32)
+    idx = rng.permutation(S)[:M].astype(np.int32)
+    want = dY.astype(np.float64).T @ X[idx].astype(np.float64)
+    np.testing.assert_array_equal(oracle.gather_gemm_dw(bf16_bits(dY), bf16_bits(X), idx), bf16_bits(want))
+    np.testing.assert_array_equal(oracle.gather_gemm_dw(dY, X, idx), want.astype(np.float32))
+    np.testing.assert_array_equal(oracle.gather_gemm_dw(dY, X[:M], None), oracle.gather_gemm_dw(dY, X, np.arange(M, dtype=np.int32)))
+    # a transposed result or a gather on the wrong operand changes the answer
+    assert oracle.gather_gemm_dw(dY, X, idx).shape == (N, C)
+    assert not np.array_equal(oracle.gather_gemm_dw(dY, X, idx), oracle.gather_gemm_dw(dY, X, np.sort(idx)))
+    # adjoint identity with random (non-dyadic) data, fp32 oracle outputs, float64 inner products
+    Xr = rng.standard_normal((S, C)).astype(np.float32)
+    Wr = rng.standard_normal((N, C)).astype(np.float32)
+    dYr = rng.standard_normal((M, N)).astype(np.float32)
+    lhs = np.sum(dYr.astype(np.float64) * oracle.gather_gemm(Xr, idx, Wr))
+    rhs = np.sum(oracle.gather_gemm_dw(dYr, Xr, idx).astype(np.float64) * Wr)
+    assert lhs == pytest.approx(rhs, rel=1e-5)
+
+
 # ------------------------------------------------------------------------------ attention over the kept tokens
 
 def dense_attention(Q, K, V, idx, causal, scale=None):
