@@ -233,6 +233,26 @@ int lemo_gather_gemm_add(const void* X, int64_t S, int64_t ldx, const int32_t* k
                          const int32_t* out_idx, int32_t C, int32_t N, lemo_dtype_t dt, void* stream);
 
 /*
+ * Weight gradient of the selective-load GEMM Y = X[kept_idx] W^T (the backward of Sec. 4.4's selective load with
+ * respect to the weights; the gather sits on the contraction axis):
+ *
+ *     dW[n, c] = sum over m < M of dY[m, n] * X[kept_idx[m], c]            n < N, c < C
+ *
+ *   dY [M, N] row stride ldy;  X [S, C] row stride ldx;  dW [N, C] row stride lddw (overwritten);  all of dtype dt;
+ *   kept_idx [M] rows of X in [0,S) (not checked on the device), or NULL for rows 0..M-1.  M == 0 writes zeros.
+ *   workspace: lemo_gather_gemm_dw_workspace_bytes(M,C,N,dt) bytes, 256-byte aligned, device memory.  It receives
+ *   dY and the kept rows of X transposed (the kept rows are read in place; the token axis is padded to a multiple of 64).
+ *
+ * binary32 accumulation, one rounding at the store.  Supported: C % 8 == 0 and N % 8 == 0 (bf16) / % 4 (fp32);
+ * dY and X follow the 16-byte rule; M below 4M (bf16) / 2M (fp32) tokens and N * M * element size below 4 GiB.
+ * (The input gradient of the same GEMM, dX[kept_idx] += dY W, is lemo_gather_gemm_add with W^T stored as [C, N].)
+ */
+int lemo_gather_gemm_dw_workspace_bytes(int64_t M, int32_t C, int32_t N, lemo_dtype_t dt, size_t* bytes);
+int lemo_gather_gemm_dw(const void* dY, int64_t ldy, const void* X, int64_t S, int64_t ldx, const int32_t* kept_idx, int64_t M,
+                        void* dW, int64_t lddw, int32_t C, int32_t N, lemo_dtype_t dt, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/*
  * Attention over the kept tokens, read in place (Sec. 4.4: the attention block loads the selected tokens
  * straight from the original inputs instead of from a re-permuted copy):
  *

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "liblemo_hip.so")
-SOURCES = ["lemo_api.hip", "score.hip", "score_blocks.hip", "attention.hip", "select.hip", "gather_gemm.hip", "scatter.hip"]
+SOURCES = ["lemo_api.hip", "score.hip", "score_blocks.hip", "attention.hip", "select.hip", "gather_gemm.hip", "transpose.hip", "scatter.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 code generation is switched off on purpose ("Build flags")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",

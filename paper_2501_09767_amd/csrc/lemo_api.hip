@@ -318,6 +318,40 @@ int lemo_gather_gemm_add(const void* X, int64_t S, int64_t ldx, const int32_t* k
                ? LEMO_OK : LEMO_ERR_HIP;
 }
 
+int lemo_gather_gemm_dw_workspace_bytes(int64_t M, int32_t C, int32_t N, lemo_dtype_t dt, size_t* bytes) {
+    if (!bytes) return LEMO_ERR_NULL;
+    if (!valid_dtype(dt)) return LEMO_ERR_DTYPE;
+    if (M < 0 || M >= (int64_t)1 << 31 || C <= 0 || N <= 0) return LEMO_ERR_SHAPE;
+    const size_t Mpad = (size_t)((M + 63) / 64) * 64, esz = dt == LEMO_BF16 ? 2 : 4;
+    *bytes = round_up((size_t)N * Mpad * esz, 256) + round_up((size_t)C * Mpad * esz, 256);
+    if (*bytes == 0) *bytes = 256;
+    return LEMO_OK;
+}
+
+int lemo_gather_gemm_dw(const void* dY, int64_t ldy, const void* X, int64_t S, int64_t ldx, const int32_t* kept_idx, int64_t M, void* dW,
+                        int64_t lddw, int32_t C, int32_t N, lemo_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!valid_dtype(dt)) return LEMO_ERR_DTYPE;
+    if (!dW || !workspace || (M > 0 && (!dY || !X))) return LEMO_ERR_NULL;
+    if (S <= 0 || M < 0 || C <= 0 || N <= 0 || ldy < N || ldx < C || lddw < C) return LEMO_ERR_SHAPE;
+    if ((!kept_idx && M > S) || M >= (int64_t)1 << 31 || S >= (int64_t)1 << 31) return LEMO_ERR_SHAPE;
+    const int e16 = elems_per_16B(dt);
+    if (C % e16 || N % e16) return LEMO_ERR_UNSUPPORTED;
+    if ((M > 0 && (!aligned16(dY) || !aligned16(X))) || ldy % e16 || ldx % e16) return LEMO_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(dW) % (dt == LEMO_BF16 ? 2 : 4) || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return LEMO_ERR_ALIGN;
+    if (kept_idx && (reinterpret_cast<uintptr_t>(kept_idx) & 3u)) return LEMO_ERR_ALIGN;
+    size_t need = 0;
+    lemo_gather_gemm_dw_workspace_bytes(M, C, N, dt, &need);
+    if (workspace_bytes < need) return LEMO_ERR_WORKSPACE;
+    const int64_t esz = dt == LEMO_BF16 ? 2 : 4, Mpad = (M + 63) / 64 * 64;
+    if (Mpad * esz >= (1 << 23) || (int64_t)N * Mpad * esz >= ((int64_t)1 << 32)) return LEMO_ERR_UNSUPPORTED;  // limits of the GEMM on the transposed operands
+    const int64_t tiles = (((int64_t)N + 255) / 256) * (((int64_t)C + 255) / 256);
+    if (tiles >= (int64_t)1 << 28) return LEMO_ERR_UNSUPPORTED;
+    if (M == 0) {  // an empty sum: dW = 0
+        return hip_rc((int)hipMemset2DAsync(dW, (size_t)lddw * esz, 0, (size_t)C * esz, (size_t)N, static_cast<hipStream_t>(stream)));
+    }
+    return hip_rc(launch_gather_gemm_dw(dY, ldy, X, S, ldx, kept_idx, M, dW, lddw, C, N, dt, workspace, static_cast<hipStream_t>(stream)));
+}
+
 int lemo_scatter_grad(const void* G, int64_t ldg, const int32_t* kept_idx, int64_t M, void* dX, int64_t lddx, int64_t S,
                       int32_t C, lemo_dtype_t g_dt, lemo_dtype_t dx_dt, int32_t mode, void* stream) {
     if (!dX || (M > 0 && (!G || !kept_idx))) return LEMO_ERR_NULL;

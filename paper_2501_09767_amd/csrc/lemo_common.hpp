@@ -102,6 +102,8 @@ int launch_select(const float* scores, int S, int L, int k, int* kept, hipStream
 int launch_block_mean(const float* token_blocks, int nb, float* out, hipStream_t st);
 int launch_select_threshold(const float* token_blocks, int S, int b, float t_host, const float* t_dev, int* kept, int* kept_count,
                             hipStream_t st);
+int launch_gather_gemm_dw(const void* dY, long long ldy, const void* X, long long S, long long ldx, const int* idx, long long M, void* dW,
+                          long long lddw, int C, int N, lemo_dtype_t dt, void* workspace, hipStream_t st);
 int launch_kept_attention(const void* Q, const void* K, const void* V, long long S, int H, int H_kv, int d, long long q_ts, long long q_hs,
                           long long k_ts, long long k_hs, long long v_ts, long long v_hs, const int* idx, long long M, float c2,
                           unsigned flags, void* O, long long o_ts, long long o_hs, void* workspace, hipStream_t st);

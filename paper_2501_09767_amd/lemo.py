@@ -24,7 +24,8 @@ EXPORTS = ("lemo_strerror", "lemo_keep_k", "lemo_kept_count", "lemo_score_worksp
            "lemo_score_segments", "lemo_score_rowstats", "lemo_score_colsums", "lemo_score_head_mean",
            "lemo_select_topk", "lemo_gather_gemm", "lemo_gather_gemm_add", "lemo_scatter_grad",
            "lemo_score_blocks_workspace_bytes", "lemo_score_blocks", "lemo_threshold_init", "lemo_select_threshold",
-           "lemo_kept_attention_workspace_bytes", "lemo_kept_attention")
+           "lemo_kept_attention_workspace_bytes", "lemo_kept_attention",
+           "lemo_gather_gemm_dw_workspace_bytes", "lemo_gather_gemm_dw")
 
 
 class LemoError(RuntimeError):
@@ -70,6 +71,10 @@ def _load() -> ctypes.CDLL:
     lib.lemo_kept_attention.restype = ctypes.c_int
     lib.lemo_kept_attention.argtypes = [vp, vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, i64, i64, vp, i64, f32, u32,
                                         vp, i64, i64, vp, ctypes.c_size_t, vp]
+    lib.lemo_gather_gemm_dw_workspace_bytes.restype = ctypes.c_int
+    lib.lemo_gather_gemm_dw_workspace_bytes.argtypes = [i64, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    lib.lemo_gather_gemm_dw.restype = ctypes.c_int
+    lib.lemo_gather_gemm_dw.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp, i64, i32, i32, ctypes.c_int, vp, ctypes.c_size_t, vp]
     lib.lemo_select_topk.restype = ctypes.c_int
     lib.lemo_select_topk.argtypes = [vp, i64, i32, i32, vp, vp]
     lib.lemo_gather_gemm.restype = ctypes.c_int
@@ -392,6 +397,34 @@ def lemo_kept_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, kept_
                                     O.stride(0) if M > 0 else H * d, O.stride(1) if M > 0 else d, _ptr(workspace),
                                     workspace.numel() * workspace.element_size(), _stream()), "lemo_kept_attention")
     return O
+
+
+def lemo_gather_gemm_dw_workspace_bytes(M: int, C: int, N: int, dtype: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.lemo_gather_gemm_dw_workspace_bytes(M, C, N, dtype, ctypes.byref(n)), "lemo_gather_gemm_dw_workspace_bytes")
+    return int(n.value)
+
+
+def lemo_gather_gemm_dw(dY: torch.Tensor, X: torch.Tensor, kept_idx: Optional[torch.Tensor], dW: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """dW[n,c] = sum_m dY[m,n] * X[kept_idx[m],c].  dY [M,N], X [S,C] -> dW [N,C]."""
+    _dev(dY, X, kept_idx, dW, workspace)
+    if dY.dim() != 2 or X.dim() != 2 or _dt(dY) != _dt(X) or X.stride(1) != 1 or (dY.shape[0] > 0 and dY.stride(1) != 1):
+        raise ValueError("dY must be [M,N] and X [S,C], same dtype, rows contiguous")
+    M, N = dY.shape
+    S, C = X.shape
+    if kept_idx is not None and (kept_idx.dtype != torch.int32 or kept_idx.dim() != 1 or kept_idx.numel() != M or not kept_idx.is_contiguous()):
+        raise ValueError("kept_idx must be contiguous int32 [M]")
+    if dW is None:
+        dW = torch.empty((N, C), dtype=X.dtype, device=X.device)
+    elif dW.dtype != X.dtype or tuple(dW.shape) != (N, C) or dW.stride(1) != 1:
+        raise ValueError("dW must be [N,C] of the input dtype, rows contiguous")
+    if workspace is None:
+        workspace = torch.empty(lemo_gather_gemm_dw_workspace_bytes(M, C, N, _dt(X)), dtype=torch.uint8, device=X.device)
+    _check(_lib.lemo_gather_gemm_dw(_ptr(dY), dY.stride(0) if M > 0 else N, _ptr(X), S, X.stride(0), _ptr(kept_idx), M, _ptr(dW),
+                                    dW.stride(0), C, N, _dt(X), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                    _stream()), "lemo_gather_gemm_dw")
+    return dW
 
 
 def lemo_scatter_grad(G: torch.Tensor, kept_idx: torch.Tensor, dX: torch.Tensor, mode: int = SCATTER_ACCUMULATE) -> torch.Tensor:

@@ -654,6 +654,74 @@ def test_gather_gemm_add_output_projection_shape_sampled(lemo):
     assert (g == o).mean() > 0.98
 
 
+# ------------------------------------------------------------------------------------ weight gradient of the selective-load GEMM
+
+@pytest.mark.parametrize("S,C,N,M", [(300, 64, 40, 130), (1000, 256, 304, 517), (513, 1000, 264, 513), (64, 8, 8, 1), (700, 512, 4096, 300)])
+def test_gather_gemm_dw_bf16(lemo, S, C, N, M):
+    say(f"[gemm dW] bf16 S={S} C={C} N={N} M={M}")
+    rng = np.random.default_rng(S + C + N + 2)
+    X = torch.from_numpy(rng.standard_normal((S, C)).astype(np.float32)).to(torch.bfloat16)
+    dY = torch.from_numpy((rng.standard_normal((M, N)) * 0.1).astype(np.float32)).to(torch.bfloat16)
+    idx = rng.permutation(S)[:M].astype(np.int32)
+    dW = lemo.lemo_gather_gemm_dw(dY.cuda(), X.cuda(), torch.from_numpy(idx).cuda())
+    # the gather folded into the transpose == the same call on a materialised compact copy
+    dWc = lemo.lemo_gather_gemm_dw(dY.cuda(), X.cuda()[torch.from_numpy(idx).cuda().long()].contiguous(), None)
+    torch.cuda.synchronize()
+    got = wl.to_bf16_bits(dW)
+    np.testing.assert_array_equal(got, wl.to_bf16_bits(dWc))
+    want = oracle.gather_gemm_dw(wl.as_numpy(dY), wl.as_numpy(X), idx)
+    assert_gemm_close(got, want, np.ascontiguousarray(wl.as_numpy(dY).T), np.ascontiguousarray(wl.as_numpy(X)[idx].T))
+
+
+def test_gather_gemm_dw_exact_and_edge_cases(lemo):
+    say("[gemm dW] exact cases")
+    rng = np.random.default_rng(24)
+    S, C, N, M = 200, 72, 48, 101
+    Xf = (rng.integers(-8, 9, (S, C)) / 4.0).astype(np.float32)
+    dYf = (rng.integers(-8, 9, (M, N)) / 8.0).astype(np.float32)
+    idx = rng.permutation(S)[:M].astype(np.int32)
+    want = dYf.astype(np.float64).T @ Xf[idx].astype(np.float64)
+    for dtype in (torch.bfloat16, torch.float32):
+        X, dY = torch.from_numpy(Xf).to(dtype), torch.from_numpy(dYf).to(dtype)
+        # padded output rows, and a second call into the same buffer (dW is overwritten, not accumulated)
+        big = torch.full((N, C + 8), 3.0, dtype=dtype, device="cuda")
+        for _ in range(2):
+            lemo.lemo_gather_gemm_dw(dY.cuda(), X.cuda(), torch.from_numpy(idx).cuda(), dW=big[:, :C])
+        torch.cuda.synchronize()
+        assert (big[:, C:] == 3.0).all()
+        got = big[:, :C].contiguous()
+        if dtype == torch.bfloat16:
+            np.testing.assert_array_equal(wl.to_bf16_bits(got), bf16(want))
+        else:
+            np.testing.assert_array_equal(got.cpu().numpy(), want.astype(np.float32))
+    # no kept tokens: an empty sum
+    z = lemo.lemo_gather_gemm_dw(torch.empty((0, N), dtype=torch.bfloat16, device="cuda"), torch.from_numpy(Xf).to(torch.bfloat16).cuda(),
+                                 torch.empty(0, dtype=torch.int32, device="cuda"))
+    assert z.shape == (N, C) and not z.any()
+    with pytest.raises(lemo.LemoError) as e:  # N must be a multiple of 8 for bf16
+        lemo.lemo_gather_gemm_dw(torch.zeros((M, 44), dtype=torch.bfloat16, device="cuda"), torch.from_numpy(Xf).to(torch.bfloat16).cuda(),
+                                 torch.from_numpy(idx).cuda())
+    assert e.value.code == -6
+
+
+def test_gather_gemm_dw_bench_shape_sampled(lemo):
+    """The 32K layer's consumer GEMM backward: M = 9856 kept rows, C = 4096, N = 11008; sampled weight rows (all columns)."""
+    cfg = wl.CONFIGS["C5"]
+    say("[gemm dW] C5 shape: inputs")
+    rng = np.random.default_rng(cfg.seed + 400)
+    X = torch.from_numpy(rng.standard_normal((cfg.S, cfg.C), dtype=np.float32)).to(torch.bfloat16)
+    dY = torch.from_numpy(rng.standard_normal((cfg.M, cfg.N), dtype=np.float32) * np.float32(0.05)).to(torch.bfloat16)
+    idx = oracle.select_topk(rng.random(cfg.S).astype(np.float32), cfg.L, cfg.k)
+    say("[gemm dW] C5 shape: GPU")
+    dW = lemo.lemo_gather_gemm_dw(dY.cuda(), X.cuda(), torch.from_numpy(idx).cuda())
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 255, 256, cfg.N - 1], rng.integers(0, cfg.N, 4)]))
+    say(f"[gemm dW] C5 shape: oracle on {len(rows)} weight rows")
+    dYs = np.ascontiguousarray(wl.as_numpy(dY)[:, rows])
+    want = oracle.gather_gemm_dw(dYs, wl.as_numpy(X), idx)
+    assert_gemm_close(wl.to_bf16_bits(dW)[rows], want, np.ascontiguousarray(dYs.T), np.ascontiguousarray(wl.as_numpy(X)[idx].T))
+
+
 # ------------------------------------------------------------------------------------ attention over the kept tokens
 
 def assert_attention_close(got_bits, want_bits, V_kept_bits):
