@@ -138,7 +138,7 @@ int lemo_score_head_mean(const float* colsum_per_head, const float* diag_per_hea
  * segment, to kept_idx[0 .. lemo_kept_count(S,L,k)).  Scores must not be NaN (then the selection is
  * unspecified but still in range).  Bit-exact and deterministic.
  *
- * Supported: 1 <= k <= L <= 8192, S < 2^31.
+ * Supported: 1 <= k <= L <= 32768, S < 2^31.
  */
 int lemo_select_topk(const float* scores, int64_t S, int32_t L, int32_t k, int32_t* kept_idx, void* stream);
 

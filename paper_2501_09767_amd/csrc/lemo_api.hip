@@ -164,7 +164,7 @@ int lemo_score_segments(const void* Q, const void* K, int64_t S, int32_t H, int3
 int lemo_select_topk(const float* scores, int64_t S, int32_t L, int32_t k, int32_t* kept_idx, void* stream) {
     if (!scores || !kept_idx) return LEMO_ERR_NULL;
     if (S <= 0 || S >= (int64_t)1 << 31 || L <= 0 || k <= 0 || k > L) return LEMO_ERR_SHAPE;
-    if (L > 8192) return LEMO_ERR_UNSUPPORTED;
+    if (L > 32768) return LEMO_ERR_UNSUPPORTED;
     return launch_select(scores, (int)S, L, k, kept_idx, static_cast<hipStream_t>(stream)) == 0 ? LEMO_OK : LEMO_ERR_HIP;
 }
 

@@ -6,6 +6,8 @@
 // is exactly "ties go to the lower index".  A block-wide prefix sum in index order gives every kept
 // element its output slot, so the indices come out ascending without a sort.  Integer work only:
 // bit-exact and deterministic.
+#include <mutex>
+
 #include "lemo_common.hpp"
 
 namespace lemo {
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
         ngt += key > pivot;
         neq += key == pivot;
     }
-    scan[tid] = ngt | (neq << 16);  // len <= 8192 so both counts fit 16 bits, as do their prefix sums
+    scan[tid] = ngt | (neq << 16);  // len <= 32768 so both counts fit 16 bits, as do their prefix sums
     __syncthreads();
 #pragma unroll
     for (int off = 1; off < SEL_THREADS; off <<= 1) {
@@ -176,7 +178,13 @@ int launch_select_threshold(const float* token_blocks, int S, int b, float t_hos
 
 int launch_select(const float* scores, int S, int L, int k, int* kept, hipStream_t st) {
     const int Leff = L < S ? L : S;
-    const int nseg = (S + L - 1) / L;  // L <= 8192 here (keys of one segment live in LDS), no overflow
+    const int nseg = (S + L - 1) / L;  // L <= 32768 here (keys of one segment live in LDS), no overflow
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {  // a 32768-token segment needs 128 KB of dynamic LDS
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_topk_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
+    });
+    if (attr_err != hipSuccess) return (int)attr_err;
     hipLaunchKernelGGL(select_topk_kernel, dim3(nseg), dim3(SEL_THREADS), (size_t)Leff * sizeof(uint32_t), st, scores, S, L, k, kept);
     return (int)hipGetLastError();
 }

@@ -98,7 +98,7 @@ def test_select_gemm_scatter_argument_errors(lib):
     assert lib.lemo_select_topk(None, 100, 10, 5, B, None) == -1
     assert lib.lemo_select_topk(A, 100, 10, 11, B, None) == -2
     assert lib.lemo_select_topk(A, 0, 10, 5, B, None) == -2
-    assert lib.lemo_select_topk(A, 100000, 16384, 5, B, None) == -6
+    assert lib.lemo_select_topk(A, 100000, 40000, 5, B, None) == -6
     g = lambda **kw: lib.lemo_gather_gemm(*[dict(dict(X=A, S=100, ldx=64, idx=B, M=10, W=C_, ldw=64, bias=None, Y=D, ldy=32, C=64, N=32, dt=1, st=None), **kw)[k]
                                             for k in ("X", "S", "ldx", "idx", "M", "W", "ldw", "bias", "Y", "ldy", "C", "N", "dt", "st")])
     assert g(X=None) == -1 and g(Y=None) == -1

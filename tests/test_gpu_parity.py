@@ -229,7 +229,8 @@ def test_score_full_length_head_subset(lemo, name, heads):
 # ------------------------------------------------------------------------------------ selection
 
 @pytest.mark.parametrize("S,L,k", [(1024, 128, 64), (1000, 128, 64), (7, 4, 3), (1, 8, 8), (8192, 512, 205), (32768, 1024, 308),
-                                   (16384, 1024, 512), (300, 100, 1), (300, 100, 100), (20000, 8192, 3000), (513, 512, 205), (100, 1, 1)])
+                                   (16384, 1024, 512), (300, 100, 1), (300, 100, 100), (20000, 8192, 3000), (513, 512, 205), (100, 1, 1),
+                                   (32768, 32768, 9831), (70000, 20000, 7000)])
 def test_select_bit_exact(lemo, S, L, k):
     say(f"[select] S={S} L={L} k={k}")
     rng = np.random.default_rng(S + L + k)
@@ -899,7 +900,7 @@ def test_error_codes_leave_outputs_untouched(lemo):
         lemo.lemo_gather_gemm(X[:, :60], bad_idx, W[:, :60], Y=Y)  # C = 60 is not a multiple of 8
     assert e.value.code == -6
     with pytest.raises(lemo.LemoError) as e:
-        lemo.lemo_select_topk(torch.zeros(100, device="cuda"), 10000, 5000)  # segment longer than the kernel supports
+        lemo.lemo_select_topk(torch.zeros(100, device="cuda"), 40000, 5000)  # segment longer than the kernel supports
     assert e.value.code == -6
     Q = torch.randn(100, 2, 96, device="cuda").to(torch.bfloat16)
     with pytest.raises(lemo.LemoError) as e:
