@@ -278,7 +278,7 @@ def main():
                          "contains a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures ONE GPU (the path has no cross-GPU step; see DESIGN.md 'Sharding'); "
+        print("bench.py: this build measures ONE GPU (the path has no cross-GPU step: heads, segments and sequences shard without communication beyond one small all-reduce); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 

@@ -1,6 +1,6 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
 
-Bars (see DESIGN.md): scores |gpu - oracle| <= 2e-3 * |oracle| + 1e-6; kept-index sets bit-exact when
+Bars: scores |gpu - oracle| <= 2e-3 * |oracle| + 1e-6; kept-index sets bit-exact when
 fed the oracle's own scores, and equal up to swaps inside the 2e-3 band around the cut when fed the
 GPU's scores; gather bit-exact and the GEMM within one bf16 step plus the binary32 accumulation bound; scatter bit-exact.
 """
