@@ -114,3 +114,64 @@ def test_select_gemm_scatter_argument_errors(lib):
     assert s(C=60) == -6
     assert s(lddx=68) == -5
     assert lib.lemo_strerror(-4) == b"workspace too small" and lib.lemo_strerror(0) == b"ok"
+
+
+def _caller(fn, order, ok):
+    return lambda **kw: fn(*[dict(ok, **kw)[k] for k in order])
+
+
+def test_block_score_threshold_attention_and_gradient_argument_errors(lib):
+    """The later entry points refuse bad arguments on the host, before any launch (fake addresses are never touched)."""
+    E = 0x50000
+    lib.lemo_score_blocks.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, f32, i32, u32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.lemo_score_blocks_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(ctypes.c_size_t)]
+    n = ctypes.c_size_t()
+    assert lib.lemo_score_blocks_workspace_bytes(32768, 32, ctypes.byref(n)) == 0
+    assert n.value == 32 * 32768 * 4 + 1024 * 1024 * 4  # row statistics + one float per 32 x 32 tile
+    sb = _caller(lib.lemo_score_blocks, ("Q", "K", "S", "H", "Hkv", "d", "dt", "qts", "qhs", "kts", "khs", "scale", "b", "flags", "mode", "lse", "sb", "tb",
+                                         "ws", "wsb", "st"),
+                 dict(Q=A, K=B, S=1024, H=4, Hkv=4, d=64, dt=1, qts=256, qhs=64, kts=256, khs=64, scale=0.0, b=64, flags=3, mode=0, lse=None, sb=None,
+                      tb=C_, ws=D, wsb=1 << 20, st=None))
+    assert sb(tb=None) == -1 and sb(ws=None) == -1 and sb(Q=None) == -1
+    assert sb(mode=2) == -2 and sb(b=0) == -2 and sb(flags=4) == -2
+    assert sb(b=48) == -6 and sb(d=96) == -6
+    assert sb(wsb=1000) == -4 and sb(ws=D + 64) == -5
+
+    lib.lemo_select_threshold.argtypes = [vp, i64, i32, f32, vp, vp, vp, vp]
+    lib.lemo_threshold_init.argtypes = [vp, i64, vp, vp]
+    assert lib.lemo_select_threshold(None, 1024, 64, 0.5, None, B, C_, None) == -1
+    assert lib.lemo_select_threshold(A, 1024, 64, 0.5, None, B, None, None) == -1
+    assert lib.lemo_select_threshold(A, 0, 64, 0.5, None, B, C_, None) == -2
+    assert lib.lemo_select_threshold(A, 1024, 64, float("nan"), None, B, C_, None) == -2
+    assert lib.lemo_select_threshold(A, 1 << 20, 32, 0.5, None, B, C_, None) == -6  # more than 16384 token blocks
+    assert lib.lemo_threshold_init(A, 0, B, None) == -2 and lib.lemo_threshold_init(None, 4, B, None) == -1
+
+    lib.lemo_kept_attention.argtypes = [vp, vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, i64, i64, vp, i64, f32, u32, vp, i64, i64, vp,
+                                        ctypes.c_size_t, vp]
+    at = _caller(lib.lemo_kept_attention, ("Q", "K", "V", "S", "H", "Hkv", "d", "dt", "qts", "qhs", "kts", "khs", "vts", "vhs", "idx", "M", "scale", "flags",
+                                           "O", "ots", "ohs", "ws", "wsb", "st"),
+                 dict(Q=A, K=B, V=C_, S=1024, H=4, Hkv=2, d=128, dt=1, qts=512, qhs=128, kts=256, khs=128, vts=256, vhs=128, idx=D, M=100, scale=0.0,
+                      flags=1, O=E, ots=512, ohs=128, ws=0x60000, wsb=1 << 20, st=None))
+    assert at(V=None) == -1 and at(O=None) == -1 and at(ws=None) == -1
+    assert at(dt=0) == -6 and at(d=96) == -6
+    assert at(flags=3) == -2 and at(idx=None, M=2000) == -2 and at(ots=64) == -2
+    assert at(vts=260) == -5 and at(O=E + 8) == -5
+    assert at(wsb=100) == -4
+    assert at(M=0, O=None, V=None) == 0  # nothing to do
+
+    lib.lemo_gather_gemm_add.argtypes = [vp, i64, i64, vp, i64, vp, i64, vp, vp, i64, i64, vp, i32, i32, ctypes.c_int, vp]
+    ga = _caller(lib.lemo_gather_gemm_add, ("X", "S", "ldx", "idx", "M", "W", "ldw", "bias", "R", "ldr", "So", "oidx", "C", "N", "dt", "st"),
+                 dict(X=A, S=100, ldx=64, idx=B, M=10, W=C_, ldw=64, bias=None, R=D, ldr=32, So=50, oidx=E, C=64, N=32, dt=1, st=None))
+    assert ga(R=None) == -1 and ga(X=None) == -1
+    assert ga(M=60) == -2 and ga(ldr=16) == -2 and ga(So=0) == -2
+    assert ga(C=60) == -6 and ga(oidx=E + 2) == -5 and ga(dt=3) == -3
+    assert ga(M=0) == 0
+
+    lib.lemo_gather_gemm_dw.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp, i64, i32, i32, ctypes.c_int, vp, ctypes.c_size_t, vp]
+    lib.lemo_gather_gemm_dw_workspace_bytes.argtypes = [i64, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    assert lib.lemo_gather_gemm_dw_workspace_bytes(100, 64, 32, 1, ctypes.byref(n)) == 0 and n.value == (32 + 64) * 128 * 2
+    dw = _caller(lib.lemo_gather_gemm_dw, ("dY", "ldy", "X", "S", "ldx", "idx", "M", "dW", "lddw", "C", "N", "dt", "ws", "wsb", "st"),
+                 dict(dY=A, ldy=32, X=B, S=100, ldx=64, idx=C_, M=10, dW=D, lddw=64, C=64, N=32, dt=1, ws=E, wsb=1 << 20, st=None))
+    assert dw(dW=None) == -1 and dw(dY=None) == -1 and dw(ws=None) == -1
+    assert dw(ldy=16) == -2 and dw(idx=None, M=200) == -2
+    assert dw(N=36, ldy=40) == -6 and dw(ldx=68) == -5 and dw(wsb=64) == -4 and dw(dt=2) == -3
