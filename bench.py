@@ -24,6 +24,14 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 
+# HBM-side bytes per launch (reads + writes behind L2) of each hot-path kernel on the 32K-token configuration, from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a 1 GiB device copy
+# (2.000 and 1.000 KiB per counter unit); the runs and the raw figures are in profiles/C5_hotpath_kernels.md.
+MEASURED_TRAFFIC_BYTES = {
+    "C5:rowstats": 2421200000, "C5:colsum": 2541300000, "C5:head_mean": 8542899, "C5:select": 237219,
+    "C5:gather_gemm": 1732000000, "C5:scatter": 242879684,
+}
+
 
 class HipEvents:
     """hipEvent_t handles created straight from the HIP runtime, recorded on a given stream."""
@@ -366,10 +374,7 @@ def main():
         report[name] = r
 
     dominant = max(phases, key=lambda n: phase_ms[n])
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(f"{cfg.name}:{dominant}")
+    traffic = MEASURED_TRAFFIC_BYTES.get(f"{cfg.name}:{dominant}")  # null for configurations that were not profiled
     if "flops" in work[dominant]:
         roof = {"bound": "mfma", "kernel": dominant, "achieved": report[dominant]["tflops"], "peak": peak_tflops,
                 "unit": "TFLOP/s", "frac": round(report[dominant]["tflops"] / peak_tflops, 4), "traffic": traffic}
