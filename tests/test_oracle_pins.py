@@ -683,3 +683,50 @@ def test_scatter_rejects_duplicate_or_out_of_range_indices():
         oracle.scatter_add(G, np.array([1, 1], np.int32), D)
     with pytest.raises(ValueError):
         oracle.scatter_add(G, np.array([1, 5], np.int32), D)
+
+
+# ------------------------------------------------------------------------------ randomised cross-checks (hypothesis)
+
+from hypothesis import given, settings, strategies as st  # noqa: E402
+
+
+@settings(max_examples=60, deadline=None)
+@given(st.integers(1, 300), st.integers(1, 64), st.data())
+def test_select_topk_randomised_against_lexsort(S, L, data):
+    """Any length, segment size, keep count and score multiset (many ties on purpose): the oracle's kept set equals the
+    first k entries of a (score descending, index ascending) lexicographic sort, per segment, listed ascending."""
+    k = data.draw(st.integers(1, L))
+    vals = data.draw(st.lists(st.sampled_from([-1.5, -0.0, 0.0, 0.25, 0.25, 1.0, 3.0, 1e-30]), min_size=S, max_size=S))
+    scores = np.array(vals, dtype=np.float32)
+    got = oracle.select_topk(scores, L, k)
+    want = []
+    for s0 in range(0, S, L):
+        seg = scores[s0:s0 + L]
+        keep = k if len(seg) == L else max(1, min(len(seg), -(-k * len(seg) // L)))
+        order = np.lexsort((np.arange(len(seg)), -(seg + np.float32(0.0))))  # +0.0 folds -0.0 into +0.0
+        want.extend(sorted(s0 + order[:keep]))
+    np.testing.assert_array_equal(got, np.array(want, dtype=np.int32))
+
+
+@settings(max_examples=40, deadline=None)
+@given(st.integers(1, 40), st.integers(1, 12), st.data())
+def test_scatter_then_gather_round_trip_randomised(S, C, data):
+    """ZERO_PAD scatter followed by a row gather returns the source rows bit for bit, every other row is +0."""
+    M = data.draw(st.integers(0, S))
+    rng = np.random.default_rng(data.draw(st.integers(0, 2 ** 31)))
+    idx = np.sort(rng.permutation(S)[:M]).astype(np.int32)
+    G = bf16_bits(rng.standard_normal((M, C)))
+    D = bf16_bits(rng.standard_normal((S, C)))
+    oracle.scatter_add(G, idx, D, mode=oracle.SCATTER_ZERO_PAD)
+    np.testing.assert_array_equal(D[idx], G)
+    assert not D[np.setdiff1d(np.arange(S), idx)].any()
+
+
+@settings(max_examples=40, deadline=None)
+@given(st.integers(1, 200), st.integers(1, 40), st.floats(-1.0, 2.0))
+def test_threshold_selection_randomised(S, b, T):
+    rng = np.random.default_rng(S * 41 + b)
+    nb = -(-S // b)
+    tb = rng.random(nb).astype(np.float32)
+    want = np.nonzero(np.repeat(tb.astype(np.float64) >= T, b)[:S])[0]
+    np.testing.assert_array_equal(oracle.select_threshold(tb, S, b, T), want)
