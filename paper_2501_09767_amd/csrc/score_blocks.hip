@@ -27,12 +27,14 @@ template <typename T, int D> struct BGeo {
     static constexpr int CPR = ROWB / 16;            // 16-byte pieces per row
     static constexpr int STRIDE = ROWB + 16;         // LDS row pitch (16 consecutive rows -> 16 distinct bank groups)
     static constexpr int TT = ROWB > 256 ? 64 : 128; // rectangle edge (queries and keys)
-    // Waves: 2 along the queries x NWK along the keys.  The LDS only reaches its bandwidth with two waves per SIMD
+    // Waves: NWQ along the queries x NWK along the keys.  The LDS only reaches its bandwidth with two waves per SIMD
     // (measured: 114 B/clk/CU with four waves reading, 220 with eight), and this kernel moves 5 LDS bytes per 1000
-    // flops, so the 128-row rectangle is worked by eight waves of 64 x 32.
-    static constexpr int NWK = TT == 128 ? 4 : 2;
-    static constexpr int THREADS = 2 * NWK * 64;
-    static constexpr int NSQ = TT / 2 / 32;          // 32-row query subtiles per wave
+    // flops, so the 128-row rectangle is worked by eight waves of 32 queries x 64 keys (one query subtile per wave: half
+    // as many row-statistic reads as with 64 x 32).
+    static constexpr int NWQ = TT == 128 ? 4 : 2;
+    static constexpr int NWK = 2;
+    static constexpr int THREADS = NWQ * NWK * 64;
+    static constexpr int NSQ = TT / NWQ / 32;        // 32-row query subtiles per wave
     static constexpr int NSK = TT / NWK / 32;        // 32-row key subtiles per wave
     static constexpr int ROWS_PER_LOAD = THREADS / CPR;
     static constexpr int NLOAD = TT / ROWS_PER_LOAD; // 16-byte loads per thread, head and operand
