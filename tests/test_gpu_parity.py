@@ -963,3 +963,54 @@ def test_attention_block_flow(lemo):
     before = wl.as_numpy(R)
     want_R = oracle.gather_gemm_add(O2, None, wl.as_numpy(Wo), before.copy(), kept_np)
     assert_gemm_add_close(wl.to_bf16_bits(Rd), want_R, before, O2, wl.as_numpy(Wo), kept_np)
+
+
+# ------------------------------------------------------------------------------------ randomised sweep over every entry point
+
+def test_randomised_shapes_every_entry_point(lemo):
+    """Seeded random shapes, flags, segment / block sizes and index sets for all entry points against the oracle, each to
+    the bar of its own section above (odd sizes, ragged tails, GQA ratios, empty and full kept sets come up by chance)."""
+    rng = np.random.default_rng(2025)
+    bf = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16)
+    for it in range(24):
+        S = int(rng.integers(1, 1200)); H = int(rng.choice([1, 2, 4, 8])); Hkv = int(rng.choice([h for h in (1, 2, 4, 8) if H % h == 0]))
+        d = int(rng.choice([64, 128])); dtype = str(rng.choice(["bf16", "f32"])); flags = int(rng.integers(0, 4)); L = int(rng.integers(1, 600))
+        k = int(rng.integers(1, L + 1)); b = int(rng.choice([32, 64, 96, 128])); mode = int(rng.integers(0, 2))
+        C = int(rng.choice([8, 64, 136, 256, 520])); N = int(rng.choice([8, 40, 264, 512])); M = int(rng.integers(0, S + 1))
+        say(f"[random] it={it} S={S} H={H}/{Hkv} d={d} {dtype} flags={flags} L={L} k={k} b={b} mode={mode} C={C} N={N} M={M}")
+        Q, K = wl.tiny_qk(S, H, Hkv, d, dtype, seed=int(rng.integers(1 << 30)), heavy=3)
+        Qn, Kn = wl.as_numpy(Q), wl.as_numpy(K)
+        scores, col, dg = run_score(lemo, Q, K, L, flags)
+        o_s, o_col, o_dg = oracle.score(Qn, Kn, flags=flags, per_head=True)
+        assert_scores_close(scores, o_s, "scores"); assert_scores_close(col, o_col, "column sums"); assert_scores_close(dg, o_dg, "diagonal")
+        sc = rng.choice([-1.0, 0.0, 0.5, 0.5, 2.0, 1e-20], size=S).astype(np.float32) if it % 2 else rng.standard_normal(S).astype(np.float32)
+        np.testing.assert_array_equal(lemo.lemo_select_topk(torch.from_numpy(sc).cuda(), L, k).cpu().numpy(), oracle.select_topk(sc, L, k))
+        sb, tb = lemo.lemo_score_blocks(Q.cuda(), K.cuda(), b, flags=flags, mode=mode)
+        w_sb, w_tb = oracle.score_blocks(Qn, Kn, b, flags=flags, mode=mode)
+        atol = 1e-6 if mode == 0 else 1e-5
+        assert_blocks_close(sb.cpu().numpy(), w_sb, "score blocks", atol); assert_blocks_close(tb.cpu().numpy(), w_tb, "token blocks", atol)
+        T0 = float(np.sort(w_tb)[len(w_tb) // 2])
+        kept_t, cnt = lemo.lemo_select_threshold(tb, S, b, T0)
+        np.testing.assert_array_equal(kept_t.cpu().numpy()[:int(cnt.item())], oracle.select_threshold(tb.cpu().numpy(), S, b, T0))
+        if M == 0:
+            continue
+        X, W, idx = bf(rng.standard_normal((S, C))), bf(rng.standard_normal((N, C)) * 0.05), rng.permutation(S)[:M].astype(np.int32)
+        Xn, Wn, idxd = wl.as_numpy(X), wl.as_numpy(W), torch.from_numpy(idx).cuda()
+        assert_gemm_close(wl.to_bf16_bits(lemo.lemo_gather_gemm(X.cuda(), idxd, W.cuda())), oracle.gather_gemm(Xn, idx, Wn), Xn[idx], Wn)
+        So = int(rng.integers(M, M + 50)); R = bf(rng.standard_normal((So, N))); oidx = rng.permutation(So)[:M].astype(np.int32)
+        Rd = R.cuda()
+        lemo.lemo_gather_gemm_add(X.cuda(), idxd, W.cuda(), Rd, torch.from_numpy(oidx).cuda())
+        before = wl.as_numpy(R)
+        assert_gemm_add_close(wl.to_bf16_bits(Rd), oracle.gather_gemm_add(Xn, idx, Wn, before.copy(), oidx), before, Xn[idx], Wn, oidx)
+        dY = bf(rng.standard_normal((M, N)) * 0.1)
+        assert_gemm_close(wl.to_bf16_bits(lemo.lemo_gather_gemm_dw(dY.cuda(), X.cuda(), idxd)), oracle.gather_gemm_dw(wl.as_numpy(dY), Xn, idx),
+                          np.ascontiguousarray(wl.as_numpy(dY).T), np.ascontiguousarray(Xn[idx].T))
+        G, dX = bf(rng.standard_normal((M, C))), bf(rng.standard_normal((S, C)))
+        dXd = dX.cuda()
+        lemo.lemo_scatter_grad(G.cuda(), idxd, dXd)
+        np.testing.assert_array_equal(wl.as_numpy(dXd), oracle.scatter_add(wl.as_numpy(G), idx, wl.as_numpy(dX).copy()))
+        if dtype == "bf16":
+            V, sidx, causal = bf(rng.standard_normal((S, Hkv, d))), np.sort(idx), flags & 1
+            O = lemo.lemo_kept_attention(Q.cuda(), K.cuda(), V.cuda(), torch.from_numpy(sidx).cuda(), flags=causal)
+            assert_attention_close(wl.to_bf16_bits(O), oracle.kept_attention(Qn, Kn, wl.as_numpy(V), sidx, flags=causal), wl.as_numpy(V)[sidx])
+    torch.cuda.synchronize()
