@@ -9,6 +9,11 @@
  *   lemo_gather_gemm      consumer GEMM that loads the kept rows straight from the input   (Sec. 4.4)
  *   lemo_scatter_grad     in-place add of per-kept-row results / gradients back into [S,C] (Sec. 4.4)
  *
+ * Beside them: the paper's block-wise criterion and threshold rule (lemo_score_blocks, lemo_threshold_init,
+ * lemo_select_threshold; Sec. 4.2 Eq. 2, Alg. 1 step 1), the attention block over the kept tokens with its
+ * projection added back in place (lemo_kept_attention, lemo_gather_gemm_add; Sec. 4.4), and the gradients
+ * of the selective-load GEMM (lemo_gather_gemm_add with the transposed weight, lemo_gather_gemm_dw).
+ *
  * Conventions shared by every call
  *   - Pointers are DEVICE pointers unless the comment says "host".  The caller owns every buffer;
  *     the library never allocates, frees or keeps a pointer after the call returns.
@@ -20,7 +25,9 @@
  *     rounds to nearest-even once when a bf16 result is stored (mixed precision, Sec. 6.1).
  *   - Strides and leading dimensions are in ELEMENTS.  Base pointers and row starts must be 16-byte
  *     aligned (so strides are multiples of 8 for bf16, 4 for fp32); otherwise LEMO_ERR_ALIGN.
- *   - No global mutable state: calls are re-entrant and may be issued from several host threads.
+ *   - No global mutable state beyond one-time kernel attribute set-up: calls are re-entrant and may be
+ *     issued from several host threads.  Calls that are given a workspace use it until their work on
+ *     the stream has finished; two calls in flight at once need two workspaces.
  */
 #ifndef LEMO_H
 #define LEMO_H
