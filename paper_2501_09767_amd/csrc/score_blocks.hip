@@ -12,6 +12,10 @@
 // Unlike the two sweeps of the token-wise score there is no operand that stays resident across the inner loop (every
 // head brings its own Q and K rows), so the kernel leans on the caches: the 256 workgroups in flight form a 16 x 16
 // super-patch of rectangles (32 operand tiles for 256 rectangles), and each die works on a 4 x 8 sub-patch of it.
+// Per head a workgroup moves 64 KB from L2 into LDS and 192 KB from LDS into registers for 4.2 MFLOP, so the head loop
+// is one software pipeline three heads deep: head h in registers (MFMA fragments, refilled in place as soon as an
+// MFMA has used them), head h + 1 complete in one LDS stage, head h + 2 arriving in the other through LDS-direct
+// loads, one barrier per head.
 #include <mutex>
 #include <type_traits>
 
@@ -25,7 +29,6 @@ template <typename T, int D> struct BGeo {
     static constexpr int ROWB = D * (int)sizeof(T);  // bytes per head row
     static constexpr int NCH = ROWB / 32;            // MFMA chunks per row
     static constexpr int CPR = ROWB / 16;            // 16-byte pieces per row
-    static constexpr int STRIDE = ROWB + 16;         // LDS row pitch (16 consecutive rows -> 16 distinct bank groups)
     static constexpr int TT = ROWB > 256 ? 64 : 128; // rectangle edge (queries and keys)
     // Waves: NWQ along the queries x NWK along the keys.  The LDS only reaches its bandwidth with two waves per SIMD
     // (measured: 114 B/clk/CU with four waves reading, 220 with eight), and this kernel moves 5 LDS bytes per 1000
@@ -36,14 +39,44 @@ template <typename T, int D> struct BGeo {
     static constexpr int THREADS = NWQ * NWK * 64;
     static constexpr int NSQ = TT / NWQ / 32;        // 32-row query subtiles per wave
     static constexpr int NSK = TT / NWK / 32;        // 32-row key subtiles per wave
-    static constexpr int ROWS_PER_LOAD = THREADS / CPR;
-    static constexpr int NLOAD = TT / ROWS_PER_LOAD; // 16-byte loads per thread, head and operand
-    static constexpr int STAGE_BYTES = 2 * TT * STRIDE + TT * (int)sizeof(float);  // Q rows, K rows, -lse2 of the Q rows
-    static constexpr int LDS = 2 * STAGE_BYTES;
-    static_assert(TT % ROWS_PER_LOAD == 0, "tile must split evenly over the workgroup");
+    // Staging is done by LDS-direct buffer loads (the data never passes through registers): a wave instruction fills
+    // 1 KB of consecutive LDS bytes, lane by lane, so rows cannot be padded.  Instead unit u (16 bytes) of a tile holds
+    // row u / CPR, piece (u % CPR) ^ swz(row): 16 consecutive rows still put any one piece into 16 distinct bank groups.
+    static constexpr int NLOAD = TT * CPR / THREADS; // 16-byte loads per thread, head and operand
+    static constexpr int TILE_BYTES = TT * ROWB;
+    static constexpr int STAGE_BYTES = 2 * TILE_BYTES;                            // Q rows, K rows
+    static constexpr int LSE_BASE = 2 * STAGE_BYTES, LSE_BYTES = TT * (int)sizeof(float);  // ring of four heads' row statistics
+    static constexpr int LDS = LSE_BASE + 4 * LSE_BYTES;
+    static_assert(TT * CPR % THREADS == 0 && THREADS % CPR == 0, "tile must split evenly over the workgroup");
+    __device__ static constexpr int swz(int row) { return CPR >= 16 ? (row & 15) : ((row >> 1) & (CPR - 1)); }
 };
 
 __device__ __forceinline__ void sb_fence() { __builtin_amdgcn_sched_barrier(0); }
+
+// LDS-direct loads: every lane fetches 16 (or 4) bytes at its own offset into the buffer; the wave's 64 pieces land in
+// consecutive LDS bytes starting at the wave-uniform LDS offset.  Written as assembly so that the compiler does not
+// make LDS reads of the OTHER stage wait for them; the kernel awaits completion itself (vmcnt) before the barrier that
+// publishes a stage.
+__device__ __forceinline__ void lds_direct_b128(u32x4 rsrc, unsigned lds_off, int voff) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_off), "v"(voff), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ void lds_direct_b32(u32x4 rsrc, unsigned lds_off, int voff) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(lds_off), "v"(voff), "s"(rsrc) : "memory");
+}
+// raw buffer descriptor over [base, base + bytes): offsets at or past `bytes` read as zero
+__device__ __forceinline__ u32x4 raw_rsrc(const void* base, long long bytes) {
+    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+    u32x4 r;
+    r[0] = (unsigned)a;
+    r[1] = (unsigned)(a >> 32) & 0xffffu;
+    r[2] = (unsigned)min(bytes, 0x7fffffffLL);
+    r[3] = 0x00020000u;
+    return r;
+}
+
+// s_waitcnt immediate that waits on the vector-memory counter only (gfx9 layout: vmcnt in bits 3:0 and 15:14)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+constexpr int LGKMCNT0 = 0xC07F;  // waits on the LDS/scalar-memory counter only
 
 // MODE 0: probabilities exp2(s * c2 - lse2_i);  MODE 1: positive part of the raw dot product (scaled at the end)
 template <typename T, int D, int MODE>
@@ -78,38 +111,57 @@ __global__ __launch_bounds__((BGeo<T, D>::THREADS), 1) void tilemax_kernel(Block
     const T* Qb = static_cast<const T*>(p.Q);
     const T* Kb = static_cast<const T*>(p.K);
 
-    // staging: thread owns the 16-byte piece (tid % CPR) of rows tid / CPR + i * ROWS_PER_LOAD of both operands
-    const int st_row = tid / G::CPR, st_cc = tid % G::CPR;
+    // staging: unit u = i * THREADS + tid of a tile goes to LDS bytes [16u, 16u + 16); the lane fetches the piece that
+    // belongs there.  Range-checked loads: the descriptor starts at the rectangle's first row of the head and ends with
+    // the last row of the tensor, so rows past the end arrive as zeros.
     const int q_row_bytes = (int)p.q_ts * (int)sizeof(T), k_row_bytes = (int)p.k_ts * (int)sizeof(T);  // host: < 2^24
-    const int q_voff = st_row * q_row_bytes + st_cc * 16, k_voff = st_row * k_row_bytes + st_cc * 16;
-    const int st_off = st_row * G::STRIDE + st_cc * 16;
-    u32x4 preq[G::NLOAD], prek[G::NLOAD];
-    float pre_l = 0.f;
-    // Range-checked loads: the descriptor starts at the rectangle's first row of the head and ends with the last row
-    // of the tensor, so rows past the end read as zero.
-    auto fetch = [&](int h) {
-        const int g = (int)(((long long)h * p.H_kv) / p.H);
+    int q_voff[G::NLOAD], k_voff[G::NLOAD];
+#pragma unroll
+    for (int i = 0; i < G::NLOAD; ++i) {
+        const int u = i * G::THREADS + tid, row = u / G::CPR, piece = (u % G::CPR) ^ G::swz(row);
+        q_voff[i] = row * q_row_bytes + piece * 16;
+        k_voff[i] = row * k_row_bytes + piece * 16;
+    }
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const unsigned group = (unsigned)(p.H / p.H_kv);  // query heads per key head (the host checks divisibility)
+    const unsigned lds0 = (unsigned)reinterpret_cast<unsigned long long>(smem);  // LDS byte offset of the staging area
+    // Row statistics: every wave brings in 64 of the TT values (several waves the same ones: no branch in the stream).
+    // Rows past the end reuse the last row's (they are masked at the end).
+    const int l_voff = min(q0 + tid % G::TT, S - 1) * (int)sizeof(float);
+    // A head's loads are described once (`aim`) and then issued one by one (`issue_one`), so that a computing wave can
+    // spread them between its MFMAs: the CU's vector-memory pipe takes 16 cycles per 1 KB instruction, and a wave that
+    // issues its share back to back stalls on the queue.
+    constexpr int PER_HEAD = 2 * G::NLOAD;  // tile loads per wave and head (the row statistics are one more)
+    u32x4 aim_q, aim_k, aim_l;
+    unsigned aim_s = 0, aim_ls = 0;
+    // Head hh goes to stage buf and to entry hh & 3 of the statistics ring.  Past the last head the descriptors have
+    // length zero: the loads stay in the stream (no branch) but fetch nothing, and what they write nobody reads.
+    auto aim = [&](int hh, int buf) {
+        const bool live = hh < p.H;
+        const int h = min(hh, p.H - 1);
+        const int g = (int)((unsigned)h / group);
         const char* qh = reinterpret_cast<const char*>(Qb + (long long)h * p.q_hs) + (long long)q0 * q_row_bytes;
         const char* kh = reinterpret_cast<const char*>(Kb + (long long)g * p.k_hs) + (long long)k0 * k_row_bytes;
         const long long qspan = (long long)(S - q0 - 1) * q_row_bytes + G::ROWB, kspan = (long long)(S - k0 - 1) * k_row_bytes + G::ROWB;
-        const __amdgpu_buffer_rsrc_t qr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(qh), 0, (int)min(qspan, 0x7fffffffLL), 0x00020000);
-        const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kh), 0, (int)min(kspan, 0x7fffffffLL), 0x00020000);
-#pragma unroll
-        for (int i = 0; i < G::NLOAD; ++i) {
-            preq[i] = __builtin_amdgcn_raw_buffer_load_b128(qr, q_voff, i * G::ROWS_PER_LOAD * q_row_bytes, 0);
-            prek[i] = __builtin_amdgcn_raw_buffer_load_b128(kr, k_voff, i * G::ROWS_PER_LOAD * k_row_bytes, 0);
-        }
-        if (MODE == 0 && tid < G::TT) pre_l = p.lse2[(size_t)h * S + min(q0 + tid, S - 1)];
+        aim_q = raw_rsrc(qh, live ? qspan : 0);
+        aim_k = raw_rsrc(kh, live ? kspan : 0);
+        if (MODE == 0) aim_l = raw_rsrc(p.lse2 + (size_t)h * S, live ? (long long)S * 4 : 0);
+        aim_s = lds0 + buf * G::STAGE_BYTES;
+        aim_ls = lds0 + G::LSE_BASE + (hh & 3) * G::LSE_BYTES;
     };
-    auto stash = [&](int buf) {
-        char* s = smem + buf * G::STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < G::NLOAD; ++i) {
-            *reinterpret_cast<u32x4*>(s + st_off + i * G::ROWS_PER_LOAD * G::STRIDE) = preq[i];
-            *reinterpret_cast<u32x4*>(s + G::TT * G::STRIDE + st_off + i * G::ROWS_PER_LOAD * G::STRIDE) = prek[i];
+    auto issue_one = [&](int n) {  // n = 0 .. PER_HEAD (compile-time after unrolling)
+        if (n < PER_HEAD) {
+            const int i = n >> 1;
+            if (n & 1) lds_direct_b128(aim_k, aim_s + G::TILE_BYTES + wave_u * 1024 + i * G::THREADS * 16, k_voff[i]);
+            else lds_direct_b128(aim_q, aim_s + wave_u * 1024 + i * G::THREADS * 16, q_voff[i]);
+        } else if (MODE == 0 && n == PER_HEAD) {
+            lds_direct_b32(aim_l, aim_ls + wave_u % (G::TT / 64) * 256, l_voff);
         }
-        // stored negated (p = exp2(s*c2 + nl)); rows past the end get -inf, i.e. probability 0
-        if (MODE == 0 && tid < G::TT) reinterpret_cast<float*>(s + 2 * G::TT * G::STRIDE)[tid] = q0 + tid < S ? -pre_l : -INFINITY;
+    };
+    auto issue = [&](int h, int buf) {
+        aim(h, buf);
+#pragma unroll
+        for (int n = 0; n <= PER_HEAD; ++n) issue_one(n);
     };
 
     // head sums of this wave's NSQ x NSK tiles: sbar[qs][ks][r] = element (row acc_row(r), column l32) of tile (qs, ks)
@@ -122,77 +174,103 @@ __global__ __launch_bounds__((BGeo<T, D>::THREADS), 1) void tilemax_kernel(Block
     // add the tile `raw` (unscaled dot products) into its accumulator; slice c of NSL covers elements [c*16/NSL, ...)
     auto accumulate = [&](f32x16& dst, const f32x16& raw, const float (&nl)[16], int c, int nsl) {
         const int lo = c * 16 / nsl, hi = (c + 1) * 16 / nsl;
+        // The slice's arithmetic hangs on a scalar that an (empty) volatile statement defines here, so that instruction
+        // selection cannot gather the slices of a tile in front of the first of them.
+        float k = MODE == 0 ? c2 : 0.f;
+        asm volatile("" : "+s"(k));
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             if (r < lo || r >= hi) continue;
-            if (MODE == 0) dst[r] += __builtin_amdgcn_exp2f(fmaf(raw[r], c2, nl[r]));
-            else dst[r] += fmaxf(raw[r], 0.f);
+            if (MODE == 0) dst[r] += __builtin_amdgcn_exp2f(fmaf(raw[r], k, -nl[r]));
+            else dst[r] += fmaxf(raw[r], k);
         }
     };
 
-    // carry: the last tile of the previous head, added while this head's fragments arrive from LDS
-    f32x16 carry = {0};
-    float carry_nl[16];
-    bool have_carry = false;
+    // fragments of the head being worked on (registers); refilled in place, piece by piece, with the next head's
+    u32x4 qf[NSQ][G::NCH], kf[NSK][G::NCH];
+    float nl[NSQ][16];  // row statistics of the head whose tiles are being accumulated
 #pragma unroll
-    for (int r = 0; r < 16; ++r) carry_nl[r] = -INFINITY;
+    for (int r = 0; r < 16 * NSQ; ++r) nl[r / 16][r % 16] = INFINITY;  // the first "tile before" is empty: exp2(0 - inf) = 0
+    const int q_row0 = wq * NSQ * 32 + l32, k_row0 = wk * NSK * 32 + l32;  // + 32 s: swz() of the row does not depend on s
+    const int q_frag = q_row0 * G::ROWB, k_frag = G::TILE_BYTES + k_row0 * G::ROWB, f_swz = G::swz(l32);
+    auto read_q = [&](int buf, int s_, int c) {
+        qf[s_][c] = *reinterpret_cast<const u32x4*>(&smem[buf * G::STAGE_BYTES + q_frag + s_ * 32 * G::ROWB + (((2 * c + half) ^ f_swz) << 4)]);
+    };
+    auto read_k = [&](int buf, int s_, int c) {
+        kf[s_][c] = *reinterpret_cast<const u32x4*>(&smem[buf * G::STAGE_BYTES + k_frag + s_ * 32 * G::ROWB + (((2 * c + half) ^ f_swz) << 4)]);
+    };
+    auto read_nl = [&](int h) {
+        if (MODE != 0) return;
+        const float* sl = reinterpret_cast<const float*>(smem + G::LSE_BASE + (h & 3) * G::LSE_BYTES);
+#pragma unroll
+        for (int s_ = 0; s_ < NSQ; ++s_)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {  // rows 8*gq + 4*half + 0..3 of query subtile s_
+                const f32x4 v = *reinterpret_cast<const f32x4*>(&sl[(wq * NSQ + s_) * 32 + gq * 8 + half * 4]);
+                nl[s_][gq * 4 + 0] = v[0]; nl[s_][gq * 4 + 1] = v[1]; nl[s_][gq * 4 + 2] = v[2]; nl[s_][gq * 4 + 3] = v[3];
+            }
+    };
 
-    fetch(0);
-    stash(0);
+    // Prologue: head 0 into stage 0 and from there into registers, head 1 into stage 1.
+    issue(0, 0);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < G::NCH; ++c) {
+#pragma unroll
+        for (int s_ = 0; s_ < NSQ; ++s_) read_q(0, s_, c);
+#pragma unroll
+        for (int s_ = 0; s_ < NSK; ++s_) read_k(0, s_, c);
+    }
+    if (p.H > 1) issue(1, 1);
+    aim(2, 0);
+
+    // Head h: one barrier, then a single instruction stream in which every MFMA is followed by the LDS reads that refill
+    // the fragments it was the last to use (with head h + 1, from stage (h+1) & 1), by this wave's next LDS-direct load
+    // of head h + 2 (into stage h & 1, which nobody reads any more; row statistics into entry (h+2) & 3 of their ring) and
+    // by a slice of the exponentials of the tile before -- for the first tile that is the last tile of head h - 1
+    // (`carry`).  Nothing is issued in bursts and nothing is left for a tail: a wave gets one 16-byte LDS read through in
+    // about 40 cycles, the CU's vector-memory pipe takes 16 cycles per 1 KB load instruction, and while a wave does
+    // vector-only work at the end of a step the matrix unit of its SIMD idles.
+    constexpr int NT = NSQ * NSK, NM = NT * G::NCH, NL = PER_HEAD + 1, LPM = (NL + NM - 1) / NM;  // tiles, MFMAs, loads, loads per MFMA
+    constexpr int AIM_SLOT = (NL + LPM - 1) / LPM;  // the first MFMA after the step's last load: describe the next step's loads
+    static_assert(NSQ == 1 && AIM_SLOT < NM, "the stream below assumes one query subtile per wave and room after the loads");
+    f32x16 carry = {0};
     for (int h = 0; h < p.H; ++h) {
-        __syncthreads();  // stage h is complete; every wave is done reading stage h-1
-        const bool more = h + 1 < p.H;
-        if (more) fetch(h + 1);
-        const char* sq = smem + (h & 1) * G::STAGE_BYTES;
-        const char* sk = sq + G::TT * G::STRIDE;
-        const float* sl = reinterpret_cast<const float*>(sq + 2 * G::TT * G::STRIDE);
-        u32x4 qf[NSQ][G::NCH], kf[NSK][G::NCH];
-        float nl[NSQ][16] = {};
+        // The stages are refilled by loads the compiler does not see: this wave's reads of stage h & 1 must have
+        // returned, and its part of head h + 1 must have landed, before anyone passes the barrier.
+        __builtin_amdgcn_s_waitcnt(LGKMCNT0);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __syncthreads();
+        const int nxt = (h + 1) & 1;
+        f32x16 prev = carry;
 #pragma unroll
-        for (int c = 0; c < G::NCH; ++c) {
-#pragma unroll
-            for (int s = 0; s < NSQ; ++s) qf[s][c] = *reinterpret_cast<const u32x4*>(&sq[((wq * NSQ + s) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
-#pragma unroll
-            for (int s = 0; s < NSK; ++s) kf[s][c] = *reinterpret_cast<const u32x4*>(&sk[((wk * NSK + s) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
-        }
-        if (MODE == 0) {
-#pragma unroll
-            for (int s = 0; s < NSQ; ++s)
-#pragma unroll
-                for (int gq = 0; gq < 4; ++gq) {  // rows 8*gq + 4*half + 0..3 of query subtile s
-                    const f32x4 v = *reinterpret_cast<const f32x4*>(&sl[(wq * NSQ + s) * 32 + gq * 8 + half * 4]);
-                    nl[s][gq * 4 + 0] = v[0]; nl[s][gq * 4 + 1] = v[1]; nl[s][gq * 4 + 2] = v[2]; nl[s][gq * 4 + 3] = v[3];
-                }
-        }
-        if (have_carry) {  // vector work that covers the LDS latency of the reads above
-#pragma unroll
-            for (int c = 0; c < 4; ++c) accumulate(sbar[NSQ - 1][NSK - 1], carry, carry_nl, c, 4);
-        }
-        // tiles of this head in the order (0,0), (0,1), ..: the accumulation of one tile is issued slice by slice
-        // between the MFMAs of the next
-        f32x16 prev = {0};
-#pragma unroll
-        for (int t = 0; t < NSQ * NSK; ++t) {
-            const int qs = t / NSK, ks = t % NSK;
-            const int pq = (t + NSQ * NSK - 1) % (NSQ * NSK) / NSK, pk = (t + NSQ * NSK - 1) % (NSQ * NSK) % NSK;  // the tile before
+        for (int tl = 0; tl < NT; ++tl) {
+            const int qs = tl / NSK, ks = tl % NSK;
+            const int pq = (tl + NT - 1) % NT / NSK, pk = (tl + NT - 1) % NT % NSK;  // the tile before
             f32x16 acc = {0};
             sb_fence();
 #pragma unroll
             for (int c = 0; c < G::NCH; ++c) {
-                if (t > 0) accumulate(sbar[pq][pk], prev, nl[pq], c, G::NCH);
                 mma_chunk<T>(acc, qf[qs][c], kf[ks][c]);  // acc[query row][key col]
+                if (ks == NSK - 1) read_q(nxt, qs, c);
+                if (qs == NSQ - 1) read_k(nxt, ks, c);
+                const int m = tl * G::NCH + c;  // loads go out with the first MFMAs: they must have landed by the end of the step
+#pragma unroll
+                for (int n = m * LPM; n < (m + 1) * LPM; ++n) issue_one(n);  // (issue_one ignores n past the last load)
+                if (m == AIM_SLOT) aim(h + 3, nxt);
+                accumulate(sbar[pq][pk], prev, nl[pq], c, G::NCH);
+                // the statistics of head h - 1 have served (its last tile has just been added): bring in head h's
+                if (tl == 0 && c == G::NCH - 1) read_nl(h);
                 sb_fence();
             }
             prev = acc;
         }
         carry = prev;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) carry_nl[r] = nl[NSQ - 1][r];
-        have_carry = true;
-        if (more) stash((h + 1) & 1);
     }
+    __builtin_amdgcn_s_waitcnt(LGKMCNT0);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) accumulate(sbar[NSQ - 1][NSK - 1], carry, carry_nl, c, 4);
+    for (int c = 0; c < 4; ++c) accumulate(sbar[NSQ - 1][NSK - 1], carry, nl[NSQ - 1], c, 4);
 
     // maximum of every 32 x 32 tile over the pairs that are admitted
     const bool excl = (p.flags & LEMO_EXCLUDE_SELF) != 0;
