@@ -39,6 +39,35 @@ template <> __device__ __forceinline__ void mma_chunk<float>(f32x16& acc, const 
 //   row = 8*(r/4) + 4*(l/32) + (r%4)   (A-operand row),   col = l % 32   (B-operand row).
 __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
+// ---- LDS-direct loads ----------------------------------------------------------------------------
+// Every lane fetches 16 (or 4) bytes at its own byte offset `voff` (+ the wave-uniform `soff`) into the buffer; the
+// wave's 64 pieces land in consecutive LDS bytes starting at the wave-uniform LDS byte offset `lds_off`.  No registers
+// and no LDS write instructions are involved.  Written as assembly so that the compiler does not make every later LDS
+// read wait for them; a kernel that uses them awaits completion itself (vmcnt, they complete in issue order) before
+// the barrier that publishes the data, and makes sure (lgkmcnt) that its own reads of the target have returned before
+// the barrier that releases it.
+__device__ __forceinline__ void lds_direct_b128(u32x4 rsrc, unsigned lds_off, int voff, int soff = 0) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(lds_off), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+__device__ __forceinline__ void lds_direct_b32(u32x4 rsrc, unsigned lds_off, int voff, int soff = 0) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds" ::"s"(lds_off), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+// raw buffer descriptor over [base, base + bytes): offsets at or past `bytes` read as zero
+__device__ __forceinline__ u32x4 raw_rsrc(const void* base, long long bytes) {
+    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+    u32x4 r;
+    r[0] = (unsigned)a;
+    r[1] = (unsigned)(a >> 32) & 0xffffu;
+    r[2] = (unsigned)(bytes < 0xffffffffLL ? (bytes > 0 ? bytes : 0) : 0xffffffffLL);
+    r[3] = 0x00020000u;
+    return r;
+}
+// s_waitcnt immediates that wait on one counter only (gfx9 layout: vmcnt in bits 3:0 and 15:14, lgkmcnt in 11:8)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+constexpr int LGKMCNT0 = 0xC07F;
+// LDS byte offset of a pointer into the workgroup's LDS
+__device__ __forceinline__ unsigned lds_offset_of(const void* p) { return (unsigned)reinterpret_cast<unsigned long long>(p); }
+
 // ---- bf16 <-> binary32 ----------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t packed) { return __uint_as_float(packed << 16); }

@@ -49,7 +49,12 @@ template <typename T, int D, int NRT_> struct Geo {
     static constexpr int ROWB = D * (int)sizeof(T);  // bytes per head row
     static constexpr int NCH = ROWB / 32;            // MFMA chunks per row
     static constexpr int CPR = ROWB / 16;            // 16-byte pieces per row
-    static constexpr int STRIDE = ROWB + 16;         // LDS row pitch: +16 B so that 16 consecutive rows hit 16 distinct bank groups
+    // LDS rows are not padded (LDS-direct loads fill consecutive bytes): piece p of row r sits at position p ^ swz(r),
+    // which spreads any one piece of 16 consecutive rows over 16 distinct bank groups
+    static constexpr int STRIDE = ROWB;
+    __device__ static constexpr int swz(int row) { return CPR >= 16 ? (row & 15) : ((row >> 1) & (CPR - 1)); }
+    // byte offset inside a stage of the fragment piece (chunk c, half) of row `row`
+    __device__ static constexpr int frag(int row, int c, int half) { return row * ROWB + (((2 * c + half) ^ swz(row)) << 4); }
     static constexpr int TILE = ROWB > 256 ? 64 : 128; // streamed rows per LDS stage (two stages; long enough to hide a global load)
     static constexpr int NSUB = TILE / 32;           // 32-row MFMA subtiles per stage
     static constexpr int NLOAD = TILE * CPR / SC_THREADS;  // 16-byte global loads per thread per stage
@@ -81,29 +86,48 @@ __device__ __forceinline__ u32x4 load_piece(const T* base, long long tok_stride,
     return v;
 }
 
-// Stage loads: thread owns the 16-byte piece (tid % CPR) of rows tid / CPR + i * ROWS_PER_LOAD of the tile
-// that starts at row0.  They go through a buffer descriptor rebuilt per stage (wave-uniform base = first
-// row of the stage, size = bytes up to the end of the last valid row): the address is one per-thread
-// 32-bit offset plus a scalar offset per load, so it costs no vector instructions, and pieces of rows
-// beyond the end of the tensor are returned as zero by the hardware range check instead of being read.
+// Stage loads: LDS-direct (no staging registers, no LDS write instructions).  Unit u = i * SC_THREADS + tid of a stage is
+// its LDS bytes [16u, 16u + 16) = row u / CPR, position u % CPR; the lane fetches the piece that belongs there.  The
+// loads go through a buffer descriptor rebuilt per stage (wave-uniform base = first row of the stage, size = bytes up to
+// the end of the last valid row), so pieces of rows beyond the end of the tensor arrive as zeros.
 template <typename G>
-__device__ __forceinline__ void stage_fetch(u32x4 (&pre)[G::NLOAD], const char* head, int row_bytes, int row0, int nrows, int voff) {
-    const long long span = (long long)(nrows - row0 - 1) * row_bytes + G::ROWB;  // bytes from row0 to the end of row nrows-1
-    const int nrec = span <= 0 ? 0 : (span > 0x7fffffffLL ? 0x7fffffff : (int)span);
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(head) + (long long)row0 * row_bytes, 0, nrec, 0x00020000);
+__device__ __forceinline__ void stage_offsets(int (&voff)[G::NLOAD], int row_bytes, int tid) {
 #pragma unroll
-    for (int i = 0; i < G::NLOAD; ++i) pre[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, i * G::ROWS_PER_LOAD * row_bytes, 0);
+    for (int i = 0; i < G::NLOAD; ++i) {
+        const int u = i * SC_THREADS + tid, row = u / G::CPR, piece = (u % G::CPR) ^ G::swz(row);
+        voff[i] = row * row_bytes + piece * 16;
+    }
 }
+// descriptor of the stage that starts at row0 (length zero when !live: its loads then fetch nothing)
 template <typename G>
-__device__ __forceinline__ void stage_stash(const u32x4 (&pre)[G::NLOAD], char* lds_piece) {
+__device__ __forceinline__ u32x4 stage_desc(const char* head, int row_bytes, int row0, int nrows, bool live) {
+    const long long span = (long long)(nrows - row0 - 1) * row_bytes + G::ROWB;  // bytes from row0 to the end of row nrows-1
+    return raw_rsrc(head + (long long)row0 * row_bytes, !live ? 0 : span > 0x7fffffffLL ? 0x7fffffffLL : span);
+}
+// lds_stage: LDS byte offset of the stage plus 1024 * (wave index), wave-uniform
+template <typename G>
+__device__ __forceinline__ void stage_load(const int (&voff)[G::NLOAD], u32x4 rsrc, unsigned lds_stage) {
 #pragma unroll
-    for (int i = 0; i < G::NLOAD; ++i) *reinterpret_cast<u32x4*>(lds_piece + i * G::ROWS_PER_LOAD * G::STRIDE) = pre[i];
+    for (int i = 0; i < G::NLOAD; ++i) lds_direct_b128(rsrc, lds_stage + i * (SC_THREADS * 16), voff[i]);
+}
+// the share of pipeline slot `ti` of `nslots`: issued one slot at a time, the loads do not queue up behind each other
+// in the CU's vector-memory pipe (16 cycles per 1 KB instruction) while the wave stands still
+template <typename G>
+__device__ __forceinline__ void stage_load_slot(const int (&voff)[G::NLOAD], u32x4 rsrc, unsigned lds_stage, int ti, int nslots) {
+#pragma unroll
+    for (int i = 0; i < G::NLOAD; ++i)
+        if (i >= ti * G::NLOAD / nslots && i < (ti + 1) * G::NLOAD / nslots) lds_direct_b128(rsrc, lds_stage + i * (SC_THREADS * 16), voff[i]);
+}
+// before the barrier that ends a stage: this wave's loads of the next stage have landed, its reads of this one returned
+__device__ __forceinline__ void stage_settle() {
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_waitcnt(LGKMCNT0);
 }
 // the NCH fragments of one 32-row subtile of a stage
 template <typename G>
 __device__ __forceinline__ void read_frags(u32x4 (&f)[G::NCH], const char* sbuf, int sub, int l32, int half) {
 #pragma unroll
-    for (int c = 0; c < G::NCH; ++c) f[c] = *reinterpret_cast<const u32x4*>(&sbuf[(sub * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+    for (int c = 0; c < G::NCH; ++c) f[c] = *reinterpret_cast<const u32x4*>(&sbuf[G::frag(sub * 32 + l32, c, half)]);
 }
 
 // The scheduler may not move anything across this point: the source order of the pipeline slots below
@@ -212,12 +236,11 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
     const int q_last = min(q0 + G::BLOCK, S) - 1;
     const int nstage = (causal ? q_last : S - 1) / G::TILE + 1;
 
-    const int st_row = tid / G::CPR, st_cc = tid % G::CPR;
     const char* k_head = reinterpret_cast<const char*>(Kb + k_off);  // wave-uniform
     const int k_row_bytes = (int)p.k_ts * (int)sizeof(T);           // host guarantees < 2^24
-    const int st_voff = st_row * k_row_bytes + st_cc * 16;
-    const int st_off = st_row * G::STRIDE + st_cc * 16;
-    u32x4 pre[G::NLOAD];
+    int st_voff[G::NLOAD];
+    stage_offsets<G>(st_voff, k_row_bytes, tid);
+    const unsigned lds_w = lds_offset_of(smem) + (unsigned)__builtin_amdgcn_readfirstlane(wave) * 1024u;
 
     // carry: the last computed tile whose statistics have not been folded in yet (it belongs to the last
     // query subtile); -inf means "none"
@@ -225,18 +248,21 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
 #pragma unroll
     for (int r = 0; r < 16; ++r) carry[r] = -INFINITY;
 
-    stage_fetch<G>(pre, k_head, k_row_bytes, 0, S, st_voff);
-    stage_stash<G>(pre, smem + st_off);
+    stage_load<G>(st_voff, stage_desc<G>(k_head, k_row_bytes, 0, S, true), lds_w);
+    stage_settle();
     for (int t = 0; t < nstage; ++t) {
         __syncthreads();  // stage t is complete; every wave is done reading stage t-1
         const bool more = t + 1 < nstage;
-        if (more) stage_fetch<G>(pre, k_head, k_row_bytes, (t + 1) * G::TILE, S, st_voff);
+        const u32x4 next_desc = stage_desc<G>(k_head, k_row_bytes, (t + 1) * G::TILE, S, more);
+        const unsigned next_lds = lds_w + ((t + 1) & 1) * G::STAGE_BYTES;
         const int k0 = t * G::TILE;
         // wave-uniform classification of this stage of keys against the wave's queries [qw0, qw0+RES-1]
         const bool skip = causal && k0 > qw0 + G::RES - 1;  // every key lies after every query
         const bool clean = causal ? (k0 + G::TILE - 1 <= qw0) : (k0 + G::TILE <= S);
         const char* sbuf = smem + (t & 1) * G::STAGE_BYTES;
-        if (clean && FROZEN && t > 0) {
+        const bool hot = clean && FROZEN && t > 0;
+        if (more && !hot) stage_load<G>(st_voff, next_desc, next_lds);  // (the hot path spreads them over its tiles)
+        if (hot) {
             // pipelined, frozen reference: exp/sum of the previous tile between the MFMAs of tile (ks, qt)
             float nm[NRT];
 #pragma unroll
@@ -260,8 +286,9 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
                     for (int c = 0; c < G::NCH; ++c) {
                         rowstat_frozen_slice<G::NCH>(c, prev, c2, nm[pq], s0, s1);
                         mma_chunk<T>(acc, kf[c], qf[qt][c]);  // acc[key row][query col]
+                        if (c == 1) stage_load_slot<G>(st_voff, next_desc, next_lds, ks * NRT + qt, G::NSUB * NRT);
                         if (qt == NRT - 1 && ks + 1 < G::NSUB)
-                            kn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((ks + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                            kn[c] = *reinterpret_cast<const u32x4*>(&sbuf[G::frag((ks + 1) * 32 + l32, c, half)]);
                         slot_fence();
                     }
                     l[pq] += s0 + s1;
@@ -293,7 +320,7 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
                         rowstat_slice<G::NCH>(c, prev, c2, m[pq], st);
                         mma_chunk<T>(acc, kf[c], qf[qt][c]);
                         if (qt == NRT - 1 && ks + 1 < G::NSUB)
-                            kn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((ks + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                            kn[c] = *reinterpret_cast<const u32x4*>(&sbuf[G::frag((ks + 1) * 32 + l32, c, half)]);
                         slot_fence();
                     }
                     rowstat_finish(st, m[pq], l[pq]);
@@ -335,7 +362,7 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
                 }
             }
         }
-        if (more) stage_stash<G>(pre, smem + ((t + 1) & 1) * G::STAGE_BYTES + st_off);
+        stage_settle();
     }
     rowstat_update(carry, c2, m[NRT - 1], l[NRT - 1]);
 
@@ -424,12 +451,11 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void colsum_k
     const int t_hi = (S - 1) / G::TILE;
     const int t_lo = causal ? key0 / G::TILE : 0;
 
-    const int st_row = tid / G::CPR, st_cc = tid % G::CPR;
     const char* q_head = reinterpret_cast<const char*>(Qb + q_off);  // wave-uniform
     const int q_row_bytes = (int)p.q_ts * (int)sizeof(T);           // host guarantees < 2^24
-    const int st_voff = st_row * q_row_bytes + st_cc * 16;
-    const int st_off = st_row * G::STRIDE + st_cc * 16;
-    u32x4 pre[G::NLOAD];
+    int st_voff[G::NLOAD];
+    stage_offsets<G>(st_voff, q_row_bytes, tid);
+    const unsigned lds_w = lds_offset_of(smem) + (unsigned)__builtin_amdgcn_readfirstlane(wave) * 1024u;
     float pre_l = 0.f;
     // row statistics of a stage: thread tid < TILE owns row tid; beyond the end +inf, so that p = exp2(-inf) = 0
     auto fetch_l = [&](int t) { return tid < G::TILE ? lse[min(t * G::TILE + tid, S - 1)] : 0.f; };
@@ -441,24 +467,25 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void colsum_k
 #pragma unroll
     for (int r = 0; r < 16; ++r) carry_nl[r] = -INFINITY;
 
-    stage_fetch<G>(pre, q_head, q_row_bytes, t_hi * G::TILE, S, st_voff);
+    stage_load<G>(st_voff, stage_desc<G>(q_head, q_row_bytes, t_hi * G::TILE, S, true), lds_w);
     pre_l = fetch_l(t_hi);
-    stage_stash<G>(pre, smem + st_off);
     if (tid < G::TILE) sLbase[tid] = fix_l(t_hi, pre_l);
+    stage_settle();
     int buf = 0;
     for (int t = t_hi; t >= t_lo; --t, buf ^= 1) {
         __syncthreads();
         const bool more = t > t_lo;
-        if (more) {
-            stage_fetch<G>(pre, q_head, q_row_bytes, (t - 1) * G::TILE, S, st_voff);
-            pre_l = fetch_l(t - 1);
-        }
+        const u32x4 next_desc = stage_desc<G>(q_head, q_row_bytes, (t - 1) * G::TILE, S, more);
+        const unsigned next_lds = lds_w + (buf ^ 1) * G::STAGE_BYTES;
+        if (more) pre_l = fetch_l(t - 1);
         const int i0 = t * G::TILE;
         const bool on_diag = i0 <= kw0 + G::RES - 1 && i0 + G::TILE - 1 >= kw0;  // stage meets the diagonal band of this wave
         const bool skip = causal && i0 + G::TILE - 1 < kw0;                     // every query lies before every key
         const char* sbuf = smem + buf * G::STAGE_BYTES;
         const float* lbuf = sLbase + buf * G::TILE;
-        if (!on_diag && !skip) {
+        const bool hot = !on_diag && !skip;
+        if (more && !hot) stage_load<G>(st_voff, next_desc, next_lds);  // (the hot path spreads them over its tiles)
+        if (hot) {
             // pipelined: exp/sum of the previous tile is issued slice by slice between the MFMAs of tile
             // (qs, kt); fragments and row statistics of the next query subtile are read during the last chain
             u32x4 qf[G::NCH];
@@ -481,8 +508,9 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void colsum_k
                         if (kt == 0) colsum_slice<G::NCH>(c, prev, carry_nl, c2, s0, s1);  // the carried tile has its own rows
                         else colsum_slice<G::NCH>(c, prev, nl, c2, s0, s1);
                         mma_chunk<T>(acc, qf[c], kf[kt][c]);  // acc[query row][key col]
+                        if (c == 1) stage_load_slot<G>(st_voff, next_desc, next_lds, qs * NRT + kt, G::NSUB * NRT);
                         if (kt == NRT - 1 && qs + 1 < G::NSUB) {
-                            qn[c] = *reinterpret_cast<const u32x4*>(&sbuf[((qs + 1) * 32 + l32) * G::STRIDE + c * 32 + half * 16]);
+                            qn[c] = *reinterpret_cast<const u32x4*>(&sbuf[G::frag((qs + 1) * 32 + l32, c, half)]);
                             if (c < 4) {
                                 const f32x4 v = *reinterpret_cast<const f32x4*>(&lbuf[(qs + 1) * 32 + c * 8 + half * 4]);
                                 nn[c * 4 + 0] = v[0]; nn[c * 4 + 1] = v[1]; nn[c * 4 + 2] = v[2]; nn[c * 4 + 3] = v[3];
@@ -539,10 +567,8 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void colsum_k
                 }
             }
         }
-        if (more) {
-            stage_stash<G>(pre, smem + (buf ^ 1) * G::STAGE_BYTES + st_off);
-            if (tid < G::TILE) sLbase[(buf ^ 1) * G::TILE + tid] = fix_l(t - 1, pre_l);
-        }
+        if (more && tid < G::TILE) sLbase[(buf ^ 1) * G::TILE + tid] = fix_l(t - 1, pre_l);
+        stage_settle();
     }
     col[NRT - 1] += colsum_tile(carry, carry_nl, c2);
 

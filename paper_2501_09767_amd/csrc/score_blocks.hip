@@ -53,31 +53,6 @@ template <typename T, int D> struct BGeo {
 
 __device__ __forceinline__ void sb_fence() { __builtin_amdgcn_sched_barrier(0); }
 
-// LDS-direct loads: every lane fetches 16 (or 4) bytes at its own offset into the buffer; the wave's 64 pieces land in
-// consecutive LDS bytes starting at the wave-uniform LDS offset.  Written as assembly so that the compiler does not
-// make LDS reads of the OTHER stage wait for them; the kernel awaits completion itself (vmcnt) before the barrier that
-// publishes a stage.
-__device__ __forceinline__ void lds_direct_b128(u32x4 rsrc, unsigned lds_off, int voff) {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_off), "v"(voff), "s"(rsrc) : "memory");
-}
-__device__ __forceinline__ void lds_direct_b32(u32x4 rsrc, unsigned lds_off, int voff) {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(lds_off), "v"(voff), "s"(rsrc) : "memory");
-}
-// raw buffer descriptor over [base, base + bytes): offsets at or past `bytes` read as zero
-__device__ __forceinline__ u32x4 raw_rsrc(const void* base, long long bytes) {
-    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
-    u32x4 r;
-    r[0] = (unsigned)a;
-    r[1] = (unsigned)(a >> 32) & 0xffffu;
-    r[2] = (unsigned)min(bytes, 0x7fffffffLL);
-    r[3] = 0x00020000u;
-    return r;
-}
-
-// s_waitcnt immediate that waits on the vector-memory counter only (gfx9 layout: vmcnt in bits 3:0 and 15:14)
-constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
-constexpr int LGKMCNT0 = 0xC07F;  // waits on the LDS/scalar-memory counter only
-
 // MODE 0: probabilities exp2(s * c2 - lse2_i);  MODE 1: positive part of the raw dot product (scaled at the end)
 template <typename T, int D, int MODE>
 __global__ __launch_bounds__((BGeo<T, D>::THREADS), 1) void tilemax_kernel(BlockParams p) {
