@@ -28,8 +28,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a 1 GiB device copy
 # (2.000 and 1.000 KiB per counter unit); the runs and the raw figures are in profiles/C5_hotpath_kernels.md.
 MEASURED_TRAFFIC_BYTES = {
-    "C5:rowstats": 2421200000, "C5:colsum": 2541300000, "C5:head_mean": 8542899, "C5:select": 237219,
-    "C5:gather_gemm": 1732000000, "C5:scatter": 242879684,
+    "C5:rowstats": 2129783382, "C5:colsum": 2228509924, "C5:head_mean": 8542739, "C5:select": 229023,
+    "C5:gather_gemm": 1732136254, "C5:scatter": 242876184,
 }
 
 
@@ -284,6 +284,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) so that a counter profile of this command "
                          "contains a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
+    ap.add_argument("--step-only", action="store_true",
+                    help="skip the measurements outside the timed step (gather_fold, fused_in_place_add, gemm_backward, "
+                         "kept_attention, block_wise), so that a profile of this command holds the step's kernels only")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU (the path has no cross-GPU step: heads, segments and sequences shard without communication beyond one small all-reduce); "
@@ -402,12 +405,13 @@ def main():
         "roofline": roof,
         "phases": report,
     }
-    out["gather_fold"] = measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, Y)
-    out["fused_in_place_add"] = measure_fused_output_projection(cfg, lemo, ev, stream, kept)
-    out["gemm_backward"] = measure_gemm_backward(cfg, lemo, ev, stream, X, W, kept)
-    if cfg.dtype == "bf16":
-        out["kept_attention"] = measure_kept_attention(cfg, lemo, ev, stream, Q, K, kept)
-    out["block_wise"] = measure_block_scoring(cfg, lemo, ev, stream, Q, K, lse2, flags)
+    if not args.step_only:
+        out["gather_fold"] = measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, Y)
+        out["fused_in_place_add"] = measure_fused_output_projection(cfg, lemo, ev, stream, kept)
+        out["gemm_backward"] = measure_gemm_backward(cfg, lemo, ev, stream, X, W, kept)
+        if cfg.dtype == "bf16":
+            out["kept_attention"] = measure_kept_attention(cfg, lemo, ev, stream, Q, K, kept)
+        out["block_wise"] = measure_block_scoring(cfg, lemo, ev, stream, Q, K, lse2, flags)
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         out["cpu_baseline"] = cpu_baseline(cfg, lay, wl)
