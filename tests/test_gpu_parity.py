@@ -266,7 +266,9 @@ def assert_blocks_close(got, want, what="", atol=1e-6):
 
 
 BLOCK_CASES = [(300, 4, 2, 64, "bf16", 32), (257, 2, 2, 128, "bf16", 64), (1000, 8, 2, 128, "bf16", 128), (129, 2, 1, 64, "f32", 32),
-               (200, 2, 2, 128, "f32", 64), (2100, 4, 4, 128, "bf16", 96), (31, 1, 1, 64, "bf16", 32)]
+               (200, 2, 2, 128, "f32", 64), (2100, 4, 4, 128, "bf16", 96), (31, 1, 1, 64, "bf16", 32),
+               # head counts around the depth of the kernel's head pipeline (three heads in flight, a ring of four statistics)
+               (150, 3, 3, 128, "bf16", 32), (150, 5, 1, 64, "f32", 32), (140, 6, 3, 128, "f32", 32), (130, 7, 7, 64, "bf16", 32)]
 
 
 @pytest.mark.parametrize("mode", [0, 1])
