@@ -45,7 +45,8 @@ __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 
 // and no LDS write instructions are involved.  Written as assembly so that the compiler does not make every later LDS
 // read wait for them; a kernel that uses them awaits completion itself (vmcnt, they complete in issue order) before
 // the barrier that publishes the data, and makes sure (lgkmcnt) that its own reads of the target have returned before
-// the barrier that releases it.
+// the barrier that releases it.  The LDS offset travels in M0, which is set inside the same statement that uses it (the
+// compiler keeps no value of its own in M0 across statements).
 __device__ __forceinline__ void lds_direct_b128(u32x4 rsrc, unsigned lds_off, int voff, int soff = 0) {
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(lds_off), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
 }
