@@ -41,7 +41,9 @@ constexpr int SC_WAVES = 4;
 //   NRT = 4  128 resident rows per wave, 512 per workgroup, one workgroup per CU: every LDS fragment read feeds
 //            four MFMA chains instead of two (half the LDS traffic per flop), but a SIMD then has no second wave
 //            to run while the first waits at a barrier or on LDS
-// Measured on the 32K-token bf16 d=128 layer: NRT = 2 4.20 / 4.25 ms (sweep 1 / sweep 2), NRT = 4 4.45 / 4.57 ms.
+// Measured on the 32K-token bf16 d=128 layer: NRT = 2 4.20 / 4.25 ms (sweep 1 / sweep 2), NRT = 4 4.45 / 4.57 ms; with
+// the stages filled by LDS-direct loads NRT = 2 4.06 ms (sweep 1) against 4.93 ms for NRT = 4 (4.23 ms when NRT = 4 is
+// squeezed into half the register file for two workgroups per CU).
 template <typename T, int D, int NRT_> struct Geo {
     static constexpr int NRT = NRT_;
     static constexpr int RES = 32 * NRT;             // resident rows per wave
