@@ -347,7 +347,7 @@ int lemo_gather_gemm_dw(const void* dY, int64_t ldy, const void* X, int64_t S, i
     const int64_t tiles = (((int64_t)N + 255) / 256) * (((int64_t)C + 255) / 256);
     if (tiles >= (int64_t)1 << 28) return LEMO_ERR_UNSUPPORTED;
     if (M == 0) {  // an empty sum: dW = 0
-        return hip_rc((int)hipMemset2DAsync(dW, (size_t)lddw * esz, 0, (size_t)C * esz, (size_t)N, static_cast<hipStream_t>(stream)));
+        return hip_rc(launch_zero_matrix(dW, lddw, C, N, dt, static_cast<hipStream_t>(stream)));
     }
     return hip_rc(launch_gather_gemm_dw(dY, ldy, X, S, ldx, kept_idx, M, dW, lddw, C, N, dt, workspace, static_cast<hipStream_t>(stream)));
 }

@@ -134,6 +134,7 @@ int launch_select_threshold(const float* token_blocks, int S, int b, float t_hos
                             hipStream_t st);
 int launch_gather_gemm_dw(const void* dY, long long ldy, const void* X, long long S, long long ldx, const int* idx, long long M, void* dW,
                           long long lddw, int C, int N, lemo_dtype_t dt, void* workspace, hipStream_t st);
+int launch_zero_matrix(void* p, long long pitch, int row_elems, int rows, lemo_dtype_t dt, hipStream_t st);  // pitch in elements
 int launch_kept_attention(const void* Q, const void* K, const void* V, long long S, int H, int H_kv, int d, long long q_ts, long long q_hs,
                           long long k_ts, long long k_hs, long long v_ts, long long v_hs, const int* idx, long long M, float c2,
                           unsigned flags, void* O, long long o_ts, long long o_hs, void* workspace, hipStream_t st);

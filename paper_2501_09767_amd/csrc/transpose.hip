@@ -55,6 +55,20 @@ static int launch_transpose(const void* in, long long ld_in, const int* idx, lon
 }
 
 // workspace: dY^T [N, Mpad] then X[idx]^T [C, Mpad], Mpad = M rounded up to 64, each block rounded up to 256 bytes
+// rows x row_elems elements of U set to zero (row pitch in elements): a kernel rather than a memset, so that a caller may
+// capture the call in a HIP graph
+template <typename U>
+__global__ __launch_bounds__(256) void zero_matrix_kernel(U* __restrict__ p, long long pitch, int row_elems) {
+    U* row = p + (long long)blockIdx.x * pitch;
+    for (int c = threadIdx.x; c < row_elems; c += 256) row[c] = 0;
+}
+int launch_zero_matrix(void* p, long long pitch, int row_elems, int rows, lemo_dtype_t dt, hipStream_t st) {
+    if (rows <= 0 || row_elems <= 0) return 0;
+    if (dt == LEMO_BF16) hipLaunchKernelGGL(zero_matrix_kernel<uint16_t>, dim3((unsigned)rows), dim3(256), 0, st, static_cast<uint16_t*>(p), pitch, row_elems);
+    else hipLaunchKernelGGL(zero_matrix_kernel<uint32_t>, dim3((unsigned)rows), dim3(256), 0, st, static_cast<uint32_t*>(p), pitch, row_elems);
+    return (int)hipGetLastError();
+}
+
 int launch_gather_gemm_dw(const void* dY, long long ldy, const void* X, long long S, long long ldx, const int* idx, long long M, void* dW,
                           long long lddw, int C, int N, lemo_dtype_t dt, void* workspace, hipStream_t st) {
     const long long Mpad = (M + 63) / 64 * 64;

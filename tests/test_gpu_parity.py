@@ -701,6 +701,12 @@ def test_gather_gemm_dw_exact_and_edge_cases(lemo):
     z = lemo.lemo_gather_gemm_dw(torch.empty((0, N), dtype=torch.bfloat16, device="cuda"), torch.from_numpy(Xf).to(torch.bfloat16).cuda(),
                                  torch.empty(0, dtype=torch.int32, device="cuda"))
     assert z.shape == (N, C) and not z.any()
+    for dtype in (torch.bfloat16, torch.float32):  # strided output: the columns beside it stay as they are
+        big = torch.full((N, C + 8), 3.0, dtype=dtype, device="cuda")
+        lemo.lemo_gather_gemm_dw(torch.empty((0, N), dtype=dtype, device="cuda"), torch.from_numpy(Xf).to(dtype).cuda(),
+                                 torch.empty(0, dtype=torch.int32, device="cuda"), dW=big[:, :C])
+        torch.cuda.synchronize()
+        assert not big[:, :C].any() and (big[:, C:] == 3.0).all()
     with pytest.raises(lemo.LemoError) as e:  # N must be a multiple of 8 for bf16
         lemo.lemo_gather_gemm_dw(torch.zeros((M, 44), dtype=torch.bfloat16, device="cuda"), torch.from_numpy(Xf).to(torch.bfloat16).cuda(),
                                  torch.from_numpy(idx).cuda())
