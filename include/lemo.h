@@ -28,6 +28,10 @@
  *   - No global mutable state beyond one-time kernel attribute set-up: calls are re-entrant and may be
  *     issued from several host threads.  Calls that are given a workspace use it until their work on
  *     the stream has finished; two calls in flight at once need two workspaces.
+ *   - The calls only launch kernels (no allocation, no memset, no host synchronisation), so a stream
+ *     that carries them may be captured into a HIP graph -- once each entry point has been called
+ *     for its dtype and head size outside a capture: the first such call raises the dynamic-LDS
+ *     limit of its kernels (hipFuncSetAttribute), which is not a stream operation.
  */
 #ifndef LEMO_H
 #define LEMO_H
