@@ -1022,3 +1022,55 @@ def test_randomised_shapes_every_entry_point(lemo):
             O = lemo.lemo_kept_attention(Q.cuda(), K.cuda(), V.cuda(), torch.from_numpy(sidx).cuda(), flags=causal)
             assert_attention_close(wl.to_bf16_bits(O), oracle.kept_attention(Qn, Kn, wl.as_numpy(V), sidx, flags=causal), wl.as_numpy(V)[sidx])
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------ the path replayed from a HIP graph
+
+def test_hot_path_replayed_from_a_hip_graph(lemo):
+    """The calls only launch kernels on the caller's stream, so the whole path can be captured once and replayed.
+    Every replay runs on new inputs (written in place by ordinary eager work between the replays) and must give the
+    bits of the same calls issued eagerly."""
+    S, H, Hkv, d, L, k, C, N = 1500, 4, 2, 128, 256, 100, 256, 264
+    M = lemo.lemo_kept_count(S, L, k)
+    say(f"[graph] S={S} H={H}/{Hkv} d={d} L={L} k={k} C={C} N={N} M={M}")
+    g = torch.Generator(device="cuda").manual_seed(7)
+    rnd = lambda *shape: torch.randn(shape, device="cuda", dtype=torch.float32, generator=g)
+    Q, K = rnd(S, H, d).to(torch.bfloat16), rnd(S, Hkv, d).to(torch.bfloat16)
+    X, W, G = rnd(S, C).to(torch.bfloat16), (rnd(N, C) * 0.05).to(torch.bfloat16), rnd(M, C).to(torch.bfloat16)
+    scores = torch.empty(S, dtype=torch.float32, device="cuda")
+    ws = torch.empty(lemo.lemo_score_workspace_bytes(S, H, Hkv, d, lemo.BF16), dtype=torch.uint8, device="cuda")
+    kept = torch.empty(M, dtype=torch.int32, device="cuda")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((S, C), dtype=torch.bfloat16, device="cuda")
+
+    def path():
+        lemo.lemo_score_segments(Q, K, L, scores=scores, workspace=ws)
+        lemo.lemo_select_topk(scores, L, k, kept_idx=kept)
+        lemo.lemo_gather_gemm(X, kept, W, Y=Y)
+        lemo.lemo_scatter_grad(G, kept, dX, mode=lemo.SCATTER_ZERO_PAD)
+
+    def outputs():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (scores, kept, Y, dX)]
+
+    path()  # eager first: the first call of an entry point sets kernel attributes, which is not a stream operation
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        path()
+    for rep in range(3):
+        say(f"[graph] replay {rep}")
+        Q.copy_(rnd(S, H, d))  # eager work between the replays
+        X.copy_(rnd(S, C))
+        for t in (scores, Y, dX):
+            t.fill_(7.0)
+        kept.fill_(-1)
+        graph.replay()
+        replayed = outputs()
+        for t in (scores, Y, dX):
+            t.fill_(5.0)
+        kept.fill_(-2)
+        path()
+        eager = outputs()
+        for a, b, what in zip(replayed, eager, ("scores", "kept_idx", "Y", "dX")):
+            assert torch.equal(a, b), f"replay {rep}: {what} differs from the eager calls"
