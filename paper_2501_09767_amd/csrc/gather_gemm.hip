@@ -65,8 +65,12 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
     // rows this thread stages: piece i*256+tid -> tile row i*32 + tid/8, 16-byte piece tid%8.
     // Both operands are read through buffer descriptors (X: the whole [S,C] tensor, rows picked by kept_idx;
     // W: this tile's rows): a 32-bit per-thread offset plus a scalar offset per load, no vector address
-    // arithmetic, and the hardware range check returns zero instead of reading past the end, so the steady
-    // state has no branches.  Rows past M are clamped to the last kept row (computed, never stored).
+    // arithmetic, so the steady state has no branches.  The hardware range check compares the PER-THREAD offset
+    // (plus the immediate) with the descriptor's size and ignores the scalar offset, so everything that can run
+    // past the end -- the row -- sits in the per-thread offset: W rows at or past N are answered with zeros and
+    // touch no memory.  The scalar offset only carries the slab's position inside a row, and a slab that does not
+    // lie entirely inside C is never requested through it (see `slab`).  Rows past M are clamped to the last kept
+    // row (computed, never stored).
     const int prow = tid >> 3, pcc = tid & 7;
     const int ldx_bytes = (int)ldx * (int)sizeof(T), ldw_bytes = (int)ldw * (int)sizeof(T);  // host: both < 2^23
     const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -79,9 +83,12 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
         a_voff[i] = row * (unsigned)ldx_bytes + pcc * 16;  // host guarantees S * ldx * sizeof(T) < 2^32
     }
     const int b_rows = min(GG_BN, N - n0);
+    const int w_bytes = (b_rows - 1) * ldw_bytes + cbytes;  // this tile's rows of W, up to the end of the last one
     const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<char*>(reinterpret_cast<const char*>(W + (long long)n0 * ldw)), 0, (b_rows - 1) * ldw_bytes + cbytes, 0x00020000);
-    const int b_voff = prow * ldw_bytes + pcc * 16;
+        const_cast<char*>(reinterpret_cast<const char*>(W + (long long)n0 * ldw)), 0, w_bytes, 0x00020000);
+    int b_voff[GG_NLD];
+#pragma unroll
+    for (int i = 0; i < GG_NLD; ++i) b_voff[i] = (i * 32 + prow) * ldw_bytes + pcc * 16;  // at or past w_bytes for rows >= b_rows
 
     // Global loads take longer than one slab of MFMAs, so two slabs are kept in flight: the pieces of slab s
     // live in register set s & 1 from the moment they are requested (during slab s-2) until they are written
@@ -97,7 +104,7 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
             pb[SET][i] = u32x4{0u, 0u, 0u, 0u};
             if (in_k) {
                 pa[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)a_voff[i], kbyte, 0);
-                pb[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff, kbyte + i * 32 * ldw_bytes, 0);
+                pb[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff[i], kbyte, 0);
             }
         }
     };
@@ -135,13 +142,21 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
         fb[i] = *reinterpret_cast<const u32x4*>(smem + b_lds + i * 32 * GG_STRIDE);
     }
     // One slab kt of the contraction, kt & 1 == PAR.  It always moves set PAR^1 (slab kt+1) to the other LDS
-    // stage and always requests slab kt+2 into set PAR; when those slabs do not exist the writes land in a
-    // stage nobody reads again and the loads are answered with zeros or stale in-range data nobody uses.
+    // stage and always requests slab kt+2 into set PAR.  When slab kt+1 does not exist the writes land in a
+    // stage nobody reads again.  When slab kt+2 does not lie entirely inside C (it is the ragged last slab, which
+    // `fetch` brings in with its pieces past C zeroed, or there is none) the requests go through descriptors of
+    // size zero: they are answered with zeros and read nothing, neither past the end of a row nor past the end
+    // of X or W.
     auto slab = [&](int kt, auto par_tag) {
         constexpr int PAR = decltype(par_tag)::value;
         const char* cur = smem + PAR * GG_STAGE;
         char* nxt = smem + (PAR ^ 1) * GG_STAGE;
         const int kbyte = (kt + 2) * GG_KB;
+        const bool live = kt + 2 < nfull;
+        const __amdgpu_buffer_rsrc_t a_req = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(reinterpret_cast<const char*>(X)), 0, live ? (int)x_bytes : 0, 0x00020000);
+        const __amdgpu_buffer_rsrc_t b_req = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(reinterpret_cast<const char*>(W + (long long)n0 * ldw)), 0, live ? w_bytes : 0, 0x00020000);
 #pragma unroll
         for (int c = 0; c < GG_NCH; ++c) {
             u32x4 nb[4];
@@ -156,8 +171,8 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
                     // back to back by all four waves they would outrun the vector-memory and LDS pipes
                     const int g = c * 16 + q, slot = g / 3;
                     if (g % 3 == 0 && slot < 16) {  // request piece `slot` of slab kt+2: A pieces first, then B pieces
-                        if (slot < 8) pa[PAR][slot] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)a_voff[slot], kbyte, 0);
-                        else pb[PAR][slot - 8] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff, kbyte + (slot - 8) * 32 * ldw_bytes, 0);
+                        if (slot < 8) pa[PAR][slot] = __builtin_amdgcn_raw_buffer_load_b128(a_req, (int)a_voff[slot], kbyte, 0);
+                        else pb[PAR][slot - 8] = __builtin_amdgcn_raw_buffer_load_b128(b_req, b_voff[slot - 8], kbyte, 0);
                     }
                     if (g % 3 == 1 && slot < 16) {  // move piece `slot` of slab kt+1 (requested during the previous slab) to LDS
                         if (slot < 8) *reinterpret_cast<u32x4*>(nxt + st_off + slot * 32 * GG_STRIDE) = pa[PAR ^ 1][slot];

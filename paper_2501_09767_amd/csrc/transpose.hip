@@ -1,4 +1,4 @@
-// Weight gradient of the selective-load GEMM (backward of Sec. 4.4's "load the selected tokens from the original input"):
+// Weight gradient of the selective-load GEMM (backward of the selective load of Sec. 4.4):
 //   dW[n,c] = sum_m dY[m,n] * X[idx[m],c]
 // The contraction runs over the kept tokens, i.e. over the ROW index of both operands, while the MFMA wants each operand
 // contiguous along the contraction.  Both operands are therefore first written transposed into the workspace -- dY^T
