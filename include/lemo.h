@@ -154,6 +154,21 @@ int lemo_score_head_mean(const float* colsum_per_head, const float* diag_per_hea
 int lemo_select_topk(const float* scores, int64_t S, int32_t L, int32_t k, int32_t* kept_idx, void* stream);
 
 /*
+ * lemo_score_head_mean and lemo_select_topk in ONE launch (Sec. 4.2: head aggregation of Eq. 2, then the token-block
+ * elimination): one workgroup per segment reads its [H, L] slab of the per-head column sums and diagonals, adds the
+ * heads in ascending order, writes scores[S] and selects from the same values without a round trip through memory.
+ * `scores` and `kept_idx` receive exactly the bits the two separate calls produce.  Arguments as for those calls.
+ * Both steps are far below one kernel launch in size (4 MB read at S = 32768, 32 heads), so halving the launches
+ * is what this buys.  Supported: 1 <= k <= L <= 32768.
+ */
+int lemo_head_mean_select_topk(const float* colsum_per_head, const float* diag_per_head, int64_t S, int32_t H,
+                               uint32_t flags, int32_t L, int32_t k, float* scores, int32_t* kept_idx, void* stream);
+
+/* Measurement aid: enqueues one empty kernel (one wavefront) on `stream` -- the launch floor that the
+ * microsecond-sized steps (head mean, selection, threshold) are reported against. */
+int lemo_launch_floor(void* stream);
+
+/*
  * Block-wise informativeness (Sec. 4.2 "Block-wise Elimination", Eq. 2, and the token-block scores of
  * "Layer-specific Threshold"):
  *

@@ -168,6 +168,18 @@ int lemo_select_topk(const float* scores, int64_t S, int32_t L, int32_t k, int32
     return launch_select(scores, (int)S, L, k, kept_idx, static_cast<hipStream_t>(stream)) == 0 ? LEMO_OK : LEMO_ERR_HIP;
 }
 
+int lemo_head_mean_select_topk(const float* colsum_per_head, const float* diag_per_head, int64_t S, int32_t H, uint32_t flags,
+                               int32_t L, int32_t k, float* scores, int32_t* kept_idx, void* stream) {
+    if (!colsum_per_head || !diag_per_head || !scores || !kept_idx) return LEMO_ERR_NULL;
+    if (S <= 0 || S >= (int64_t)1 << 31 || H <= 0 || (flags & ~(uint32_t)(LEMO_CAUSAL | LEMO_EXCLUDE_SELF))) return LEMO_ERR_SHAPE;
+    if (L <= 0 || k <= 0 || k > L) return LEMO_ERR_SHAPE;
+    if (L > 32768) return LEMO_ERR_UNSUPPORTED;
+    return hip_rc(launch_head_mean_select(colsum_per_head, diag_per_head, (int)S, H, (flags & LEMO_EXCLUDE_SELF) ? 1 : 0, L, k, scores,
+                                          kept_idx, static_cast<hipStream_t>(stream)));
+}
+
+int lemo_launch_floor(void* stream) { return hip_rc(launch_empty(static_cast<hipStream_t>(stream))); }
+
 int lemo_score_blocks_workspace_bytes(int64_t S, int32_t H, size_t* bytes) {
     if (!bytes) return LEMO_ERR_NULL;
     if (S <= 0 || S >= (int64_t)1 << 31 || H <= 0) return LEMO_ERR_SHAPE;

@@ -129,6 +129,9 @@ int launch_score(const ScoreParams& p, lemo_dtype_t dt, int d, int which, hipStr
 int launch_score_blocks(const BlockParams& p, lemo_dtype_t dt, int d, int mode, int b, float* score_blocks, float* token_blocks,
                         hipStream_t st);  // mode 0: probabilities (p.lse2 filled), 1: positive logits
 int launch_select(const float* scores, int S, int L, int k, int* kept, hipStream_t st);
+int launch_head_mean_select(const float* colsum, const float* diag, int S, int H, int exclude_self, int L, int k, float* scores, int* kept,
+                            hipStream_t st);
+int launch_empty(hipStream_t st);
 int launch_block_mean(const float* token_blocks, int nb, float* out, hipStream_t st);
 int launch_select_threshold(const float* token_blocks, int S, int b, float t_host, const float* t_dev, int* kept, int* kept_count,
                             hipStream_t st);

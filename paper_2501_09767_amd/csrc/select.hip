@@ -21,24 +21,16 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* __restrict__ scores, int S, int L, int k,
-                                                                  int* __restrict__ kept) {
-    extern __shared__ uint32_t keys[];  // [len]
+// The selection proper, shared by the two kernels below: `keys` [len] (LDS) hold the order keys of one segment, the
+// `keep` kept token indices go to kept[out0 ...) in ascending order.  T = threads of the workgroup (a multiple of 256);
+// every thread of the workgroup must call it.
+template <int T>
+__device__ __forceinline__ void select_from_keys(const uint32_t* keys, int len, int keep, long long out0, int start,
+                                                 int* __restrict__ kept) {
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t scan[SEL_THREADS];
+    __shared__ uint32_t scan[T];
     __shared__ uint32_t sh_prefix, sh_need;
-
-    const int seg = blockIdx.x, tid = threadIdx.x;
-    const int start = seg * L;  // host guarantees start < S and no overflow
-    const int len = min(L, S - start);
-    int keep = k;
-    if (len != L) {
-        long long v = ((long long)k * len + L - 1) / L;
-        keep = (int)max(1ll, min((long long)len, v));
-    }
-    const long long out0 = (long long)seg * k;  // every earlier segment is full
-
-    for (int t = tid; t < len; t += SEL_THREADS) keys[t] = order_key(scores[start + t]);
+    const int tid = threadIdx.x;
     if (tid == 0) { sh_prefix = 0u; sh_need = (uint32_t)keep; }
     __syncthreads();
 
@@ -46,29 +38,31 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
     // many elements must still be taken among those sharing that prefix
 #pragma unroll 1
     for (int shift = 24; shift >= 0; shift -= 8) {
-        hist[tid] = 0u;
+        if (tid < 256) hist[tid] = 0u;
         __syncthreads();
         const uint32_t prefix = sh_prefix, need = sh_need;
         const uint32_t himask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
-        for (int t = tid; t < len; t += SEL_THREADS) {
+        for (int t = tid; t < len; t += T) {
             const uint32_t key = keys[t];
             if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
         }
         __syncthreads();
         // suffix sums: scan[b] = number of candidates whose digit is >= b
-        scan[tid] = hist[tid];
+        if (tid < 256) scan[tid] = hist[tid];
         __syncthreads();
 #pragma unroll
         for (int off = 1; off < 256; off <<= 1) {
-            uint32_t v = tid + off < 256 ? scan[tid + off] : 0u;
+            uint32_t v = (tid < 256 && tid + off < 256) ? scan[tid + off] : 0u;
             __syncthreads();
-            scan[tid] += v;
+            if (tid < 256) scan[tid] += v;
             __syncthreads();
         }
-        const uint32_t ge = scan[tid], gt = tid + 1 < 256 ? scan[tid + 1] : 0u;
-        if (gt < need && need <= ge) {  // exactly one digit satisfies this
-            sh_prefix = prefix | ((uint32_t)tid << shift);
-            sh_need = need - gt;
+        if (tid < 256) {
+            const uint32_t ge = scan[tid], gt = tid + 1 < 256 ? scan[tid + 1] : 0u;
+            if (gt < need && need <= ge) {  // exactly one digit satisfies this
+                sh_prefix = prefix | ((uint32_t)tid << shift);
+                sh_need = need - gt;
+            }
         }
         __syncthreads();
     }
@@ -76,7 +70,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
     const uint32_t need_eq = sh_need;   // how many elements equal to the pivot are kept (lowest indices first)
 
     // compaction in index order: thread t owns the contiguous range [t*per, (t+1)*per)
-    const int per = (len + SEL_THREADS - 1) / SEL_THREADS;
+    const int per = (len + T - 1) / T;
     const int lo = min(len, tid * per), hi = min(len, lo + per);
     uint32_t ngt = 0, neq = 0;
     for (int t = lo; t < hi; ++t) {
@@ -87,7 +81,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
     scan[tid] = ngt | (neq << 16);  // len <= 32768 so both counts fit 16 bits, as do their prefix sums
     __syncthreads();
 #pragma unroll
-    for (int off = 1; off < SEL_THREADS; off <<= 1) {
+    for (int off = 1; off < T; off <<= 1) {
         uint32_t v = tid >= off ? scan[tid - off] : 0u;
         __syncthreads();
         scan[tid] += v;
@@ -106,6 +100,70 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
         }
     }
 }
+
+// tokens kept in a segment of length len when full segments of length L keep k
+__device__ __forceinline__ int segment_keep(int len, int L, int k) {
+    if (len == L) return k;
+    const long long v = ((long long)k * len + L - 1) / L;
+    return (int)max(1ll, min((long long)len, v));
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* __restrict__ scores, int S, int L, int k,
+                                                                  int* __restrict__ kept) {
+    extern __shared__ uint32_t keys[];  // [len]
+    const int seg = blockIdx.x, tid = threadIdx.x;
+    const int start = seg * L;  // host guarantees start < S and no overflow
+    const int len = min(L, S - start);
+    for (int t = tid; t < len; t += SEL_THREADS) keys[t] = order_key(scores[start + t]);
+    select_from_keys<SEL_THREADS>(keys, len, segment_keep(len, L, k), (long long)seg * k /* every earlier segment is full */, start, kept);
+}
+
+// Head mean and selection in one launch (one workgroup per segment): the segment's [H, len] slab of per-head column
+// sums and diagonals is read once, coalesced along the tokens, the heads are added in ascending order exactly as
+// head_mean_kernel adds them (same bits), the scores are written out and their order keys go straight to LDS for the
+// selection.  Saves one launch and the round trip of the scores through memory.
+constexpr int FUSED_THREADS = 1024;
+__global__ __launch_bounds__(FUSED_THREADS) void head_mean_select_kernel(const float* __restrict__ colsum, const float* __restrict__ diag,
+                                                                         int S, int H, int exclude_self, int L, int k,
+                                                                         float* __restrict__ scores, int* __restrict__ kept) {
+    extern __shared__ uint32_t keys[];  // [len]
+    const int seg = blockIdx.x, tid = threadIdx.x;
+    const int start = seg * L;
+    const int len = min(L, S - start);
+    for (int t = tid; t < len; t += FUSED_THREADS) {
+        const float* c = colsum + start + t;
+        const float* g = diag + start + t;
+        float acc = 0.f;
+        int h = 0;
+        for (; h + 8 <= H; h += 8) {  // eight heads' loads in flight at a time; the additions stay in head order
+            float cv[8], gv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) cv[u] = c[(size_t)(h + u) * S];
+            if (exclude_self) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) gv[u] = g[(size_t)(h + u) * S];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                float v = cv[u];
+                if (exclude_self) v -= gv[u];
+                acc += v;
+            }
+        }
+        for (; h < H; ++h) {
+            float v = c[(size_t)h * S];
+            if (exclude_self) v -= g[(size_t)h * S];
+            acc += v;
+        }
+        const float sc = acc / (float)H;
+        scores[start + t] = sc;
+        keys[t] = order_key(sc);
+    }
+    select_from_keys<FUSED_THREADS>(keys, len, segment_keep(len, L, k), (long long)seg * k, start, kept);
+}
+
+// nothing: the cost of one launch on a stream (what the microsecond-sized steps of the path are measured against)
+__global__ void empty_kernel() {}
 
 // ------------------------------------------------------------------------------------------------
 // Threshold selection over token blocks (Sec. 4.2 "Layer-specific Threshold"; Alg. 1 step 1).
@@ -170,9 +228,35 @@ int launch_block_mean(const float* token_blocks, int nb, float* out, hipStream_t
 
 int launch_select_threshold(const float* token_blocks, int S, int b, float t_host, const float* t_dev, int* kept, int* kept_count,
                             hipStream_t st) {
-    const int nb = (S + b - 1) / b;  // host checked: nb <= 16384, the offsets fit the default dynamic LDS limit
+    const int nb = (S + b - 1) / b;  // host checked: nb <= 16384
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {  // 16384 block offsets are 64 KB of dynamic LDS on top of the kernel's static 4 KB: above the default limit
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_threshold_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4);
+    });
+    if (attr_err != hipSuccess) return (int)attr_err;
     hipLaunchKernelGGL(select_threshold_kernel, dim3(1), dim3(THR_THREADS), (size_t)nb * sizeof(int), st, token_blocks, S, b, nb, t_host,
                        t_dev, kept, kept_count);
+    return (int)hipGetLastError();
+}
+
+int launch_empty(hipStream_t st) {
+    hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, st);
+    return (int)hipGetLastError();
+}
+
+int launch_head_mean_select(const float* colsum, const float* diag, int S, int H, int exclude_self, int L, int k, float* scores, int* kept,
+                            hipStream_t st) {
+    const int Leff = L < S ? L : S;
+    const int nseg = (S + L - 1) / L;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {  // a 32768-token segment needs 128 KB of dynamic LDS
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&head_mean_select_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
+    });
+    if (attr_err != hipSuccess) return (int)attr_err;
+    hipLaunchKernelGGL(head_mean_select_kernel, dim3(nseg), dim3(FUSED_THREADS), (size_t)Leff * sizeof(uint32_t), st, colsum, diag, S, H,
+                       exclude_self, L, k, scores, kept);
     return (int)hipGetLastError();
 }
 

@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_HERE, "liblemo_hip.so")
 
 EXPORTS = ("lemo_strerror", "lemo_keep_k", "lemo_kept_count", "lemo_score_workspace_bytes",
            "lemo_score_segments", "lemo_score_rowstats", "lemo_score_colsums", "lemo_score_head_mean",
-           "lemo_select_topk", "lemo_gather_gemm", "lemo_gather_gemm_add", "lemo_scatter_grad",
+           "lemo_select_topk", "lemo_head_mean_select_topk", "lemo_launch_floor", "lemo_gather_gemm", "lemo_gather_gemm_add", "lemo_scatter_grad",
            "lemo_score_blocks_workspace_bytes", "lemo_score_blocks", "lemo_threshold_init", "lemo_select_threshold",
            "lemo_kept_attention_workspace_bytes", "lemo_kept_attention",
            "lemo_gather_gemm_dw_workspace_bytes", "lemo_gather_gemm_dw")
@@ -75,6 +75,10 @@ def _load() -> ctypes.CDLL:
     lib.lemo_gather_gemm_dw_workspace_bytes.argtypes = [i64, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
     lib.lemo_gather_gemm_dw.restype = ctypes.c_int
     lib.lemo_gather_gemm_dw.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp, i64, i32, i32, ctypes.c_int, vp, ctypes.c_size_t, vp]
+    lib.lemo_head_mean_select_topk.restype = ctypes.c_int
+    lib.lemo_head_mean_select_topk.argtypes = [vp, vp, i64, i32, u32, i32, i32, vp, vp, vp]
+    lib.lemo_launch_floor.restype = ctypes.c_int
+    lib.lemo_launch_floor.argtypes = [vp]
     lib.lemo_select_topk.restype = ctypes.c_int
     lib.lemo_select_topk.argtypes = [vp, i64, i32, i32, vp, vp]
     lib.lemo_gather_gemm.restype = ctypes.c_int
@@ -310,6 +314,34 @@ def lemo_select_topk(scores: torch.Tensor, L: int, k: int, kept_idx: Optional[to
         raise ValueError("kept_idx must be contiguous int32 [M]")
     _check(_lib.lemo_select_topk(_ptr(scores), S, int(L), int(k), _ptr(kept_idx), _stream()), "lemo_select_topk")
     return kept_idx
+
+
+def lemo_head_mean_select_topk(colsum_per_head: torch.Tensor, diag_per_head: torch.Tensor, L: int, k: int,
+                               flags: int = CAUSAL | EXCLUDE_SELF, scores: Optional[torch.Tensor] = None,
+                               kept_idx: Optional[torch.Tensor] = None):
+    """Head mean + per-segment top-k in one launch -> (scores [S] float32, kept_idx [M] int32)."""
+    H, S = colsum_per_head.shape
+    col = _plane(colsum_per_head, H, S, colsum_per_head.device)
+    dg = _plane(diag_per_head, H, S, colsum_per_head.device)
+    M = lemo_kept_count(S, L, k)
+    if M < 0:
+        raise LemoError(-2, "lemo_kept_count")
+    if scores is None:
+        scores = torch.empty(S, dtype=torch.float32, device=col.device)
+    elif scores.dtype != torch.float32 or tuple(scores.shape) != (S,) or not scores.is_contiguous() or not scores.is_cuda:
+        raise ValueError("scores must be contiguous float32 [S] on the GPU")
+    if kept_idx is None:
+        kept_idx = torch.empty(M, dtype=torch.int32, device=col.device)
+    elif kept_idx.dtype != torch.int32 or kept_idx.numel() != M or not kept_idx.is_contiguous() or not kept_idx.is_cuda:
+        raise ValueError("kept_idx must be contiguous int32 [M] on the GPU")
+    _check(_lib.lemo_head_mean_select_topk(_ptr(col), _ptr(dg), S, H, int(flags), int(L), int(k), _ptr(scores), _ptr(kept_idx), _stream()),
+           "lemo_head_mean_select_topk")
+    return scores, kept_idx
+
+
+def lemo_launch_floor() -> None:
+    """One empty kernel on the current stream (measurement aid)."""
+    _check(_lib.lemo_launch_floor(_stream()), "lemo_launch_floor")
 
 
 def lemo_gather_gemm(X: torch.Tensor, kept_idx: Optional[torch.Tensor], W: torch.Tensor,
