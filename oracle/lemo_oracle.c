@@ -289,7 +289,8 @@ int oracle_score_blocks(const void* Q, const void* K, int64_t S, int32_t H, int3
 }
 
 /* The score blocks I(B^S_mn), n < nb, of the listed block rows only (row_out is [n_rows, nb]): the same
- * arithmetic as oracle_score_blocks, for spot checks at sizes where the whole matrix would take hours. */
+ * arithmetic as oracle_score_blocks, for quick spot checks (the whole 32K-token, 32-head matrix takes the full routine
+ * about a minute on 16 threads). */
 int oracle_score_block_rows(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, int dtype,
                             int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
                             double scale, uint32_t flags, int32_t b, int mode, const int64_t* rows, int32_t n_rows, double* row_out) {
@@ -578,7 +579,7 @@ static void attention_one_query(const void* Q, const void* K, const void* V, int
 }
 
 /* rows == NULL: every kept query m < M, written to O row m.  rows != NULL: only the listed kept queries, written to O
- * rows 0 .. n_rows-1 (spot checks at sizes where all M queries would take hours). */
+ * rows 0 .. n_rows-1 (quick spot checks; all 9856 kept queries of the 32K-token layer take about a minute on 16 threads). */
 int oracle_kept_attention(const void* Q, const void* K, const void* V, int64_t S, int32_t H, int32_t H_kv, int32_t d, int dtype,
                           int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
                           int64_t v_tok_stride, int64_t v_head_stride, const int32_t* idx, int64_t M, double scale,

@@ -208,22 +208,67 @@ def test_score_config_C2_full(lemo):
     say(f"    heavy-key tokens kept: {int(np.isin(heavy, kept).sum())} of {len(heavy)}")
 
 
-@pytest.mark.parametrize("name,heads", [("C4", [4, 5, 6, 7]), ("C5", [9, 30])])
-def test_score_full_length_head_subset(lemo, name, heads):
-    """Full sequence length of the large configurations on a few heads (the oracle is O(S^2 d) per head):
-    per-head column sums and diagonals against the oracle, plus the sum-to-S invariant."""
+def assert_gemm_close_by_rows(got_bits, want_bits, Xrows, W, rows_per_chunk=1024):
+    """assert_gemm_close over every output, a block of rows at a time (the magnitude matrix of the accumulation bound is
+    float64 [rows, N]); returns the share of outputs whose bits equal the oracle's."""
+    same = 0
+    for r0 in range(0, got_bits.shape[0], rows_per_chunk):
+        r1 = min(got_bits.shape[0], r0 + rows_per_chunk)
+        assert_gemm_close(got_bits[r0:r1], want_bits[r0:r1], Xrows[r0:r1], W)
+        same += int((got_bits[r0:r1] == want_bits[r0:r1]).sum())
+    return same / got_bits.size
+
+
+@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
+def test_config_whole_path_full_size(lemo, name):
+    """The large configurations exactly as bench.py launches them -- full sequence, ALL heads, the consumer GEMM at its
+    real width -- every output of every stage against the oracle: scores, per-head column sums and diagonals element
+    by element; the kept set from the GPU's own scores equal to the oracle's up to swaps inside the tolerance band at
+    the cut; every element of the gathered GEMM on that kept set; the backward scatter bit for bit (configurations
+    that have one)."""
     cfg = wl.CONFIGS[name]
-    say(f"[score] {name} S={cfg.S} heads={heads}: inputs")
-    lay = wl.make_layer(cfg, heads=heads, want_gemm=False, want_grad=False)
-    say(f"[score] {name}: GPU")
+    say(f"[config] {name} S={cfg.S} H={cfg.H}/{cfg.H_kv} N={cfg.N} L={cfg.L} k={cfg.k} M={cfg.M}: inputs")
+    lay = wl.make_layer(cfg, device="cuda")
+    Qn, Kn, Xn, Wn = (wl.as_numpy(lay[n]) for n in ("Q", "K", "X", "W"))
+    say(f"[config] {name}: GPU score (all {cfg.H} heads)")
     got, col, dg = run_score(lemo, lay["Q"], lay["K"], cfg.L, 3)
     np.testing.assert_allclose(col.astype(np.float64).sum(axis=1), cfg.S, rtol=1e-4)
-    say(f"[score] {name}: oracle")
-    want, wcol, wdg = oracle.score(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), flags=3, per_head=True)
+    assert got[-1] == 0.0
+    say(f"[config] {name}: oracle score on {oracle.num_threads()} threads")
+    want, wcol, wdg = oracle.score(Qn, Kn, flags=3, per_head=True)
     worst = assert_scores_close(got, want, f"{name} scores")
     assert_scores_close(col.ravel(), wcol.ravel(), f"{name} colsum")
     assert_scores_close(dg.ravel(), wdg.ravel(), f"{name} diag")
-    say(f"    worst relative error {worst:.2e}")
+    del col, dg, wcol, wdg
+    say(f"    worst relative score error {worst:.2e}")
+    scores_d = torch.from_numpy(got).cuda()
+    kept_d = lemo.lemo_select_topk(scores_d, cfg.L, cfg.k)
+    kept = kept_d.cpu().numpy()
+    assert len(kept) == cfg.M
+    np.testing.assert_array_equal(kept, oracle.select_topk(got, cfg.L, cfg.k))   # the selection itself is bit-exact
+    nswap = assert_selection_equivalent(kept, want, cfg.L, cfg.k)                 # and valid against the oracle's scores
+    heavy = np.nonzero(lay["mult"].numpy() >= 4)[0]
+    say(f"    kept set equals the oracle's up to {nswap} in-band swaps; x4-key tokens kept: {int(np.isin(heavy, kept).sum())} of {len(heavy)}")
+    say(f"[config] {name}: GPU gather-GEMM on the kept set")
+    Y = lemo.lemo_gather_gemm(lay["X"], kept_d, lay["W"])
+    torch.cuda.synchronize()
+    Yb = wl.to_bf16_bits(Y)
+    del Y
+    say(f"[config] {name}: oracle gather-GEMM, all {cfg.M} x {cfg.N} outputs")
+    want_Y = oracle.gather_gemm(Xn, kept, Wn)
+    share = assert_gemm_close_by_rows(Yb, want_Y, Xn[kept], Wn)
+    say(f"    {100 * share:.2f} % of the GEMM outputs carry the oracle's bits, the rest are within one bf16 step")
+    del Yb, want_Y
+    if cfg.backward:
+        say(f"[config] {name}: backward scatter of G [{cfg.M},{cfg.C}] at the kept rows")
+        R = torch.from_numpy(np.random.default_rng(cfg.seed + 9).standard_normal((cfg.S, cfg.C), dtype=np.float32)).to(torch.bfloat16)
+        for init in (torch.zeros_like(R), R):
+            Dd = init.cuda()
+            lemo.lemo_scatter_grad(lay["G"], kept_d, Dd)
+            torch.cuda.synchronize()
+            want_D = wl.as_numpy(init).copy()
+            oracle.scatter_add(wl.as_numpy(lay["G"]), kept, want_D)
+            np.testing.assert_array_equal(wl.as_numpy(Dd), want_D)
 
 
 # ------------------------------------------------------------------------------------ selection
@@ -252,6 +297,33 @@ def test_select_all_equal_and_extremes(lemo):
     for k in (1, 17, 64, 128):
         got = lemo.lemo_select_topk(torch.from_numpy(ext).cuda(), 128, k).cpu().numpy()
         np.testing.assert_array_equal(got, oracle.select_topk(ext, 128, k))
+
+
+@pytest.mark.parametrize("S,H,L,k,flags", [(1024, 4, 128, 64, 3), (1000, 3, 128, 64, 1), (7, 1, 4, 3, 2), (8192, 32, 512, 205, 3), (32768, 32, 1024, 308, 3),
+                                           (20000, 9, 8192, 3000, 0), (32768, 8, 32768, 9831, 3), (513, 17, 512, 205, 3), (70000, 2, 20000, 7000, 2)])
+def test_head_mean_and_select_in_one_launch(lemo, S, H, L, k, flags):
+    """lemo_head_mean_select_topk == lemo_score_head_mean followed by lemo_select_topk, bit for bit (scores and kept
+    indices), and its kept set is the oracle's selection on those scores."""
+    say(f"[fused select] S={S} H={H} L={L} k={k} flags={flags}")
+    rng = np.random.default_rng(S + H + L)
+    col = rng.random((H, S)).astype(np.float32) * 3
+    dg = (rng.random((H, S)).astype(np.float32) * 0.5)
+    col[:, rng.integers(0, S, S // 4)] = np.float32(0.75)   # columns with equal sums in every head: exact ties after the mean
+    dg[:, rng.integers(0, S, S // 4)] = np.float32(0.25)
+    cold, dgd = torch.from_numpy(col).cuda(), torch.from_numpy(dg).cuda()
+    want_scores = lemo.lemo_score_head_mean(cold, dgd, flags=flags)
+    want_kept = lemo.lemo_select_topk(want_scores, L, k)
+    scores = torch.full((S,), -3.0, dtype=torch.float32, device="cuda")
+    kept = torch.full((lemo.lemo_kept_count(S, L, k),), -1, dtype=torch.int32, device="cuda")
+    lemo.lemo_head_mean_select_topk(cold, dgd, L, k, flags=flags, scores=scores, kept_idx=kept)
+    torch.cuda.synchronize()
+    assert torch.equal(scores, want_scores) and torch.equal(kept, want_kept)
+    np.testing.assert_array_equal(kept.cpu().numpy(), oracle.select_topk(scores.cpu().numpy(), L, k))
+    # the head mean itself: float32 adds in head order, as numpy does them
+    ref = np.zeros(S, dtype=np.float32)
+    for h in range(H):
+        ref = ref + ((col[h] - dg[h]) if flags & 2 else col[h])
+    np.testing.assert_array_equal(scores.cpu().numpy(), ref / np.float32(H))
 
 
 # ------------------------------------------------------------------------------------ block-wise informativeness, thresholds
@@ -333,10 +405,10 @@ def test_score_blocks_config_C2_heads_subset(lemo):
     assert_blocks_close(tb.cpu().numpy(), want_tb, "C2 token blocks")
 
 
-def test_score_blocks_full_size_sampled_rows(lemo):
-    """The 32K-token, 32-head configuration in the launch shape the bench times (b = 64): sampled block rows against the
-    oracle, plus what holds for every entry: blocks above the diagonal are 0, every other block lies in (0, 1], and the
-    token-block scores are the column sums of the matrix."""
+def test_score_blocks_full_size(lemo):
+    """The 32K-token, 32-head configuration in the launch shape the bench times (b = 64): EVERY score block and token
+    block against the oracle, plus what holds by construction: blocks above the diagonal are 0, every other block lies
+    in (0, 1], and the token-block scores are the column sums of the matrix."""
     cfg = wl.CONFIGS["C5"]
     lay = wl.make_layer(cfg, want_gemm=False, device="cuda")
     say("[blocks] C5: GPU")
@@ -349,13 +421,13 @@ def test_score_blocks_full_size_sampled_rows(lemo):
     low = sbn[np.tril_indices(nb)]
     assert (low > 0).all() and (low <= 1.0 + 1e-6).all()
     np.testing.assert_allclose(tbn, sbn.astype(np.float64).sum(axis=0), rtol=1e-5)
-    rows = [0, 1, 200, nb - 1]
-    say(f"[blocks] C5: oracle on block rows {rows}")
-    want = oracle.score_block_rows(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), 64, rows)
-    assert_blocks_close(sbn[rows], want, "C5 sampled block rows")
+    say(f"[blocks] C5: oracle, all {nb} x {nb} score blocks, {oracle.num_threads()} threads")
+    want_sb, want_tb = oracle.score_blocks(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), 64)
+    assert_blocks_close(sbn, want_sb, "C5 score blocks")
+    assert_blocks_close(tbn, want_tb, "C5 token blocks")
 
 
-@pytest.mark.parametrize("S,b", [(1000, 32), (4096, 64), (40000, 32), (77, 128), (32768, 1024)])
+@pytest.mark.parametrize("S,b", [(1000, 32), (4096, 64), (40000, 32), (77, 128), (32768, 1024), (16384, 1), (49150, 3)])  # the last two: the largest block count the kernel takes
 def test_select_threshold_bit_exact(lemo, S, b):
     say(f"[threshold] S={S} b={b}")
     rng = np.random.default_rng(S + b)
@@ -473,47 +545,6 @@ def test_gather_gemm_fp32_config_C1(lemo):
     assert empty.shape == (0, cfg.N)
 
 
-def test_gather_gemm_llama_shape_sampled(lemo):
-    """C3-shaped consumer GEMM (M=3280 kept rows of 8192, C=4096, N=11008): sampled output rows against
-    the oracle, all columns of each sampled row."""
-    cfg = wl.CONFIGS["C3"]
-    say("[gemm] C3 shape: inputs")
-    rng = np.random.default_rng(cfg.seed)
-    X = torch.from_numpy(rng.standard_normal((cfg.S, cfg.C), dtype=np.float32)).to(torch.bfloat16)
-    W = torch.from_numpy(rng.standard_normal((cfg.N, cfg.C), dtype=np.float32) * np.float32(0.02)).to(torch.bfloat16)
-    scores = rng.random(cfg.S).astype(np.float32)
-    idx = oracle.select_topk(scores, cfg.L, cfg.k)
-    assert len(idx) == cfg.M == 3280
-    say("[gemm] C3 shape: GPU")
-    Y = lemo.lemo_gather_gemm(X.cuda(), torch.from_numpy(idx).cuda(), W.cuda())
-    torch.cuda.synchronize()
-    rows = np.unique(np.concatenate([[0, 1, 255, 256, 3071, 3072, 3279], rng.integers(0, cfg.M, 25)]))
-    say(f"[gemm] C3 shape: oracle on {len(rows)} rows")
-    want = oracle.gather_gemm(wl.as_numpy(X), idx[rows], wl.as_numpy(W))
-    assert_gemm_close(wl.to_bf16_bits(Y)[rows], want, wl.as_numpy(X)[idx[rows]], wl.as_numpy(W))
-
-
-@pytest.mark.parametrize("name", ["C4", "C5"])
-def test_gather_gemm_bench_shapes_sampled(lemo, name):
-    """The consumer GEMM at the sizes bench.py times (C4: M=8192 of 16384, N=14336; C5: M=9856 of 32768, N=11008;
-    C=4096), same launch configuration: sampled output rows, all columns, against the oracle; the rows around tile
-    edges and the ragged last tile are always in the sample."""
-    cfg = wl.CONFIGS[name]
-    say(f"[gemm] {name} shape: inputs")
-    rng = np.random.default_rng(cfg.seed + 100)
-    X = torch.from_numpy(rng.standard_normal((cfg.S, cfg.C), dtype=np.float32)).to(torch.bfloat16)
-    W = torch.from_numpy(rng.standard_normal((cfg.N, cfg.C), dtype=np.float32) * np.float32(0.02)).to(torch.bfloat16)
-    idx = oracle.select_topk(rng.random(cfg.S).astype(np.float32), cfg.L, cfg.k)
-    assert len(idx) == cfg.M
-    say(f"[gemm] {name} shape: GPU")
-    Y = lemo.lemo_gather_gemm(X.cuda(), torch.from_numpy(idx).cuda(), W.cuda())
-    torch.cuda.synchronize()
-    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, cfg.M - 257, cfg.M - 256, cfg.M - 129, cfg.M - 1], rng.integers(0, cfg.M, 16)]))
-    say(f"[gemm] {name} shape: oracle on {len(rows)} rows")
-    want = oracle.gather_gemm(wl.as_numpy(X), idx[rows], wl.as_numpy(W))
-    assert_gemm_close(wl.to_bf16_bits(Y)[rows], want, wl.as_numpy(X)[idx[rows]], wl.as_numpy(W))
-
-
 # ------------------------------------------------------------------------------------ fused gather-GEMM + in-place add
 
 def assert_gemm_add_close(got_bits, want_bits, before_bits, Xrows, W, out_rows, bias=None):
@@ -604,7 +635,7 @@ def test_gather_gemm_add_exact_cases(lemo):
 
 def test_gather_gemm_add_as_backward_of_the_selective_load(lemo):
     """Backward of Y = X[idx] W^T with respect to X: dX[idx[m],:] += dY[m,:] W.  With the weight's transpose stored as a
-    [C,N] matrix this is the same call (compact rows in, indexed rows out); checked against numpy float64 on a dyadic grid."""
+    [C,N] matrix this is the same call (compact rows in, indexed rows out); bit-exact against the oracle on a dyadic grid."""
     say("[gemm+add] backward form")
     rng = np.random.default_rng(23)
     S, C, N, M = 300, 96, 160, 120
@@ -612,13 +643,12 @@ def test_gather_gemm_add_as_backward_of_the_selective_load(lemo):
     W = (rng.integers(-8, 9, (N, C)) / 8.0).astype(np.float32)
     dX = (rng.integers(-64, 65, (S, C)) / 4.0).astype(np.float32)
     idx = np.sort(rng.permutation(S)[:M]).astype(np.int32)
-    want = dX.astype(np.float64)
-    want[idx] += dY.astype(np.float64) @ W.astype(np.float64)
-    Wt = torch.from_numpy(W).to(torch.bfloat16).t().contiguous().cuda()  # [C,N]
-    got = lemo.lemo_gather_gemm_add(torch.from_numpy(dY).to(torch.bfloat16).cuda(), None, Wt,
+    Wt = torch.from_numpy(W).to(torch.bfloat16).t().contiguous()  # [C,N]
+    want = oracle.gather_gemm_add(bf16(dY), None, wl.as_numpy(Wt), bf16(dX).copy(), idx)
+    got = lemo.lemo_gather_gemm_add(torch.from_numpy(dY).to(torch.bfloat16).cuda(), None, Wt.cuda(),
                                     torch.from_numpy(dX).to(torch.bfloat16).cuda(), torch.from_numpy(idx).cuda())
     torch.cuda.synchronize()
-    np.testing.assert_array_equal(wl.to_bf16_bits(got), bf16(want))
+    np.testing.assert_array_equal(wl.to_bf16_bits(got), want)
 
 
 def bf16(x):
@@ -797,9 +827,9 @@ def test_kept_attention_options(lemo):
     assert lemo.lemo_kept_attention(Qd, Kd, Vd, torch.empty(0, dtype=torch.int32, device="cuda")).shape == (0, H, d)
 
 
-def test_kept_attention_full_size_sampled(lemo):
-    """The 32K-token layer with its 9856 kept tokens and all 32 heads, as the bench runs it: sampled kept queries (all
-    heads, all value columns) against the oracle; every output finite."""
+def test_kept_attention_full_size(lemo):
+    """The 32K-token layer with its 9856 kept tokens and all 32 heads, as the bench runs it: EVERY kept query (all heads,
+    all value columns) against the oracle."""
     cfg = wl.CONFIGS["C5"]
     lay = wl.make_layer(cfg, want_gemm=False, device="cuda")
     say("[attention] C5: inputs")
@@ -811,11 +841,10 @@ def test_kept_attention_full_size_sampled(lemo):
     torch.cuda.synchronize()
     got = wl.to_bf16_bits(O)
     assert np.isfinite(widen(got)).all()
-    rows = np.unique(np.concatenate([[0, 1, 63, 64, 255, 256, cfg.M - 257, cfg.M - 1], rng.integers(0, cfg.M, 8)]))
-    say(f"[attention] C5: oracle on {len(rows)} kept queries")
+    say(f"[attention] C5: oracle on all {cfg.M} kept queries, {oracle.num_threads()} threads")
     Vn = wl.as_numpy(V)
-    want = oracle.kept_attention(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), Vn, idx, rows=rows)
-    assert_attention_close(got[rows], want, Vn[idx])
+    want = oracle.kept_attention(wl.as_numpy(lay["Q"]), wl.as_numpy(lay["K"]), Vn, idx)
+    assert_attention_close(got, want, Vn[idx])
 
 
 # ------------------------------------------------------------------------------------ scatter-add
