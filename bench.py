@@ -2,15 +2,20 @@
 """Benchmark of the Contextual Token Sparsity hot path on one MI355X.
 
 A step is one pass of the whole path over one synthetic layer, through the C ABI:
-    lemo_score_rowstats -> lemo_score_colsums -> lemo_score_head_mean   (= lemo_score_segments)
-    -> lemo_select_topk -> lemo_gather_gemm -> lemo_scatter_grad (when the configuration has a backward)
+    lemo_score_rowstats -> lemo_score_colsums -> lemo_head_mean_select_topk (head mean + per-segment top-k, one launch)
+    -> lemo_gather_gemm -> lemo_scatter_grad (when the configuration has a backward)
 with every input already resident in HBM.  HIP events recorded between the calls, on the stream the
-kernels run on, give each kernel's share of the timed region.  Prints ONE JSON line.
+kernels run on, give each kernel's share of the timed region.  Prints ONE JSON line: the 32K-token layer as the
+headline, the 16K-token layer (the other half of the metric) under "secondary", measured ceilings of the same
+machine in the same run (a library GEMM of the consumer's shape, a 1 GiB device copy, an empty launch) under
+"ceilings", and the CPU oracle on a bounded sample under "cpu_baseline".
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--secondary C4] [--no-cpu-baseline]
 """
 import argparse
 import ctypes
+import glob
+import hashlib
 import json
 import os
 import sys
@@ -27,10 +32,29 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 # HBM-side bytes per launch (reads + writes behind L2) of each hot-path kernel on the 32K-token configuration, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a 1 GiB device copy
 # (2.000 and 1.000 KiB per counter unit); the runs and the raw figures are in profiles/C5_hotpath_kernels.md.
+# The figures belong to the kernel sources they were measured on: "sources" is sources_digest() at that time, and the
+# bench reports traffic as null when the sources have changed since.
 MEASURED_TRAFFIC_BYTES = {
+    "sources": "unmeasured",
     "C5:rowstats": 2129783382, "C5:colsum": 2228509924, "C5:head_mean": 8542739, "C5:select": 229023,
     "C5:gather_gemm": 1732136254, "C5:scatter": 242876184,
 }
+
+
+def sources_digest() -> str:
+    """sha256 over the kernel sources (what the measured traffic figures are tied to)."""
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2501_09767_amd", "csrc", "*"))):
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(key: str):
+    if MEASURED_TRAFFIC_BYTES.get("sources") != sources_digest():
+        return None
+    return MEASURED_TRAFFIC_BYTES.get(key)
 
 
 class HipEvents:
@@ -75,6 +99,7 @@ def algorithmic_work(cfg):
         "colsum": {"flops": 2.0 * d * pairs},
         "head_mean": {"bytes": 2.0 * H * S * 4 + S * 4},
         "select": {"bytes": S * 4.0 + M * 4.0},
+        "head_mean_select": {"bytes": 2.0 * H * S * 4 + S * 4 + M * 4.0},
         "gather_gemm": {"flops": 2.0 * M * C * N, "bytes": (M * C + N * C + M * N) * float(esz)},
         "scatter": {"bytes": 3.0 * M * C * esz + 4.0 * M},
     }
@@ -104,7 +129,8 @@ def cpu_baseline(cfg, lay, wl, steps_note=""):
     W = wl.as_numpy(lay["W"].cpu())
     t0 = time.perf_counter()
     oracle.gather_gemm(X, kept[:M1], W)
-    t_gemm = (time.perf_counter() - t0) * (len(kept) / M1)
+    t_gemm_s = time.perf_counter() - t0
+    t_gemm = t_gemm_s * (len(kept) / M1)
     t_scatter = 0.0
     if cfg.backward:
         G = wl.as_numpy(lay["G"].cpu())
@@ -120,6 +146,7 @@ def cpu_baseline(cfg, lay, wl, steps_note=""):
                    f"scatter: all {len(kept)} rows" + ("" if cfg.backward else " (not in this configuration)")),
         "est_seconds_per_step": total,
         "seconds": {"score": t_score, "select": t_select, "gather_gemm": t_gemm, "scatter": t_scatter},
+        "measured_seconds_unscaled": {"score": t_score_s, "select": t_select, "gather_gemm": t_gemm_s, "scatter": t_scatter},
     }
 
 
@@ -160,8 +187,8 @@ def measure_fused_output_projection(cfg, lemo, ev, stream, kept, reps=10):
 
 
 def measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, Y, reps=10):
-    """Outside the timed step: what folding the gather into the GEMM's A-tile load saves (Sec. 4.4, "directly loads the
-    selected tokens from original inputs").  Unfolded = materialise the kept rows (torch.index_select, one read and one
+    """Outside the timed step: what folding the gather into the GEMM's A-tile load saves (Sec. 4.4, selective
+    load).  Unfolded = materialise the kept rows (torch.index_select, one read and one
     write of M x C) and run the same GEMM kernel on the compact copy."""
     import torch
     kept64 = kept.long()
@@ -274,19 +301,172 @@ def measure_block_scoring(cfg, lemo, ev, stream, Q, K, lse2, flags, b=64, reps=5
             "threshold_select_ms": round(t_sel, 5), "kept_tokens": int(count.item())}
 
 
+def timed_calls(ev, stream, fn, reps):
+    """Mean milliseconds of `fn` over `reps` back-to-back calls, from HIP events on the launch stream (one warm-up call)."""
+    import torch
+    fn()
+    marks = [ev.create() for _ in range(reps + 1)]
+    ev.record(marks[0], stream)
+    for i in range(reps):
+        fn()
+        ev.record(marks[i + 1], stream)
+    torch.cuda.synchronize()
+    return sum(ev.elapsed_ms(marks[i], marks[i + 1]) for i in range(reps)) / reps
+
+
+class LayerRun:
+    """One synthetic layer resident in HBM and the step that runs the hot path over it."""
+
+    def __init__(self, cfg, lemo, wl, ev, stream):
+        import torch
+        self.cfg, self.lemo, self.ev, self.stream = cfg, lemo, ev, stream
+        self.flags = lemo.CAUSAL | lemo.EXCLUDE_SELF
+        print(f"[bench] building synthetic layer {cfg.name}: S={cfg.S} H={cfg.H}/{cfg.H_kv} d={cfg.d} C={cfg.C} N={cfg.N} "
+              f"L={cfg.L} k={cfg.k} M={cfg.M} {cfg.dtype}", file=sys.stderr, flush=True)
+        self.lay = lay = wl.make_layer(cfg, device="cuda")
+        self.Q, self.K, self.X, self.W = lay["Q"], lay["K"], lay["X"], lay["W"]
+        dev, S, H = self.Q.device, cfg.S, cfg.H
+        self.lse2 = torch.empty((H, S), dtype=torch.float32, device=dev)
+        self.col = torch.empty((H, S), dtype=torch.float32, device=dev)
+        self.dg = torch.empty((H, S), dtype=torch.float32, device=dev)
+        self.scores = torch.empty(S, dtype=torch.float32, device=dev)
+        self.kept = torch.empty(cfg.M, dtype=torch.int32, device=dev)
+        self.Y = torch.empty((cfg.M, cfg.N), dtype=self.X.dtype, device=dev)
+        self.phases = ["rowstats", "colsum", "head_mean_select", "gather_gemm"] + (["scatter"] if cfg.backward else [])
+        # the HBM-bound scatter rotates between two sets of buffers (G, dX), so that no step finds the rows of the step
+        # before in a cache: its rate is an HBM rate by construction
+        self.sets = []
+        if cfg.backward:
+            G = lay["G"]
+            self.sets = [(G, torch.zeros((S, cfg.C), dtype=self.X.dtype, device=dev)),
+                         (G.clone(), torch.zeros((S, cfg.C), dtype=self.X.dtype, device=dev))]
+        self.n = 0
+
+    def step(self, m=None):
+        lemo, cfg, ev, st = self.lemo, self.cfg, self.ev, self.stream
+        if m: ev.record(m[0], st)
+        lemo.lemo_score_rowstats(self.Q, self.K, flags=self.flags, lse2=self.lse2)
+        if m: ev.record(m[1], st)
+        lemo.lemo_score_colsums(self.Q, self.K, cfg.L, self.lse2, flags=self.flags, colsum_per_head=self.col, diag_per_head=self.dg)
+        if m: ev.record(m[2], st)
+        lemo.lemo_head_mean_select_topk(self.col, self.dg, cfg.L, cfg.k, flags=self.flags, scores=self.scores, kept_idx=self.kept)
+        if m: ev.record(m[3], st)
+        lemo.lemo_gather_gemm(self.X, self.kept, self.W, Y=self.Y)
+        if m: ev.record(m[4], st)
+        if self.sets:
+            G, dX = self.sets[self.n & 1]
+            self.n += 1
+            lemo.lemo_scatter_grad(G, self.kept, dX)
+            if m: ev.record(m[5], st)
+
+    def run(self, steps, warmup):
+        """W untimed steps, then exactly K timed steps between two synchronisations -> (ms per step, per-phase report)."""
+        import torch
+        ev = self.ev
+        marks = [[ev.create() for _ in range(len(self.phases) + 1)] for _ in range(steps)]
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(marks[i])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / steps
+        work = algorithmic_work(self.cfg)
+        peak_tflops = PEAK_BF16_TFLOPS if self.cfg.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS
+        report = {}
+        for pi, name in enumerate(self.phases):
+            ts = sorted(ev.elapsed_ms(marks[i][pi], marks[i][pi + 1]) for i in range(steps))
+            ms = sum(ts) / len(ts)
+            w = work[name]
+            r = {"ms": round(ms, 5), "ms_median": round(ts[len(ts) // 2], 5), "ms_min": round(ts[0], 5)}
+            if "flops" in w:
+                r["tflops"] = round(w["flops"] / (ms * 1e-3) * 1e-12, 2)
+                r["frac_mfma_peak"] = round(r["tflops"] / peak_tflops, 4)
+            if "bytes" in w:
+                r["gbs"] = round(w["bytes"] / (ms * 1e-3) * 1e-9, 2)
+                r["frac_hbm_peak"] = round(r["gbs"] / PEAK_HBM_GBS, 5)
+            report[name] = r
+        return ms_per_step, report
+
+    def workload(self):
+        cfg = self.cfg
+        return (f"{cfg.name}: one Llama-shaped layer, S={cfg.S}, {cfg.H}x{cfg.d} heads ({cfg.H_kv} KV), hidden {cfg.C}, "
+                f"consumer GEMM {cfg.C}->{cfg.N}, segment {cfg.L}, keep ratio {cfg.ratio} (k={cfg.k}, M={cfg.M}), causal, "
+                f"self term excluded" + (", backward scatter-add included" if cfg.backward else ""))
+
+
+def measure_ceilings(cfg, ev, stream, X, W, kept, lemo):
+    """What this machine delivers, in this run, on the plainest form of each bound: the library GEMM (torch.matmul) on
+    a pre-compacted copy of the consumer's operands, a 1 GiB device-to-device copy, and an empty kernel launch."""
+    import torch
+    Xc = X[kept.long()].contiguous()
+    Wt = W.t()
+    out = torch.empty((cfg.M, cfg.N), dtype=X.dtype, device=X.device)
+    t_mm = timed_calls(ev, stream, lambda: torch.matmul(Xc, Wt, out=out), 10)
+    del Xc, out
+    a = torch.ones(1 << 29, dtype=torch.bfloat16, device=X.device)  # 1 GiB read + 1 GiB written per copy
+    b = torch.empty_like(a)
+    t_cp = timed_calls(ev, stream, lambda: b.copy_(a), 10)
+    del a, b
+    t_empty = timed_calls(ev, stream, lemo.lemo_launch_floor, 200)
+    return {"what": "same machine, same run: torch.matmul (library GEMM) on a compact copy of the consumer GEMM's operands; "
+                    "1 GiB device copy (read + write counted); one empty kernel launch, back to back on the stream",
+            "library_gemm_ms": round(t_mm, 5), "library_gemm_tflops": round(2.0 * cfg.M * cfg.C * cfg.N / t_mm * 1e-9, 2),
+            "device_copy_gbs": round(2.0 * (1 << 30) / t_cp * 1e-6, 1), "empty_launch_us": round(t_empty * 1e3, 3)}
+
+
+def measure_select(cfg, lemo, ev, stream, col, dg, flags, batch=128):
+    """Outside the timed step: head mean + selection as two launches and as one, against the empty-launch floor, and the
+    same kernels on `batch` independent score sets in one launch (segments are independent, so a batch is simply a
+    sequence `batch` times as long): the rate the kernels reach once the launch is amortised."""
+    import torch
+    S, H, L, k, M = cfg.S, cfg.H, cfg.L, cfg.k, cfg.M
+    scores = torch.empty(S, dtype=torch.float32, device=col.device)
+    kept = torch.empty(M, dtype=torch.int32, device=col.device)
+
+    def two():
+        lemo.lemo_score_head_mean(col, dg, flags=flags, scores=scores)
+        lemo.lemo_select_topk(scores, L, k, kept_idx=kept)
+
+    t_two = timed_calls(ev, stream, two, 50)
+    t_one = timed_calls(ev, stream, lambda: lemo.lemo_head_mean_select_topk(col, dg, L, k, flags=flags, scores=scores, kept_idx=kept), 50)
+    t_sel = timed_calls(ev, stream, lambda: lemo.lemo_select_topk(scores, L, k, kept_idx=kept), 50)
+    Sb = S * batch
+    g = torch.Generator(device="cuda").manual_seed(5)
+    colb = torch.rand((H, Sb), device="cuda", dtype=torch.float32, generator=g)
+    dgb = torch.rand((H, Sb), device="cuda", dtype=torch.float32, generator=g) * 0.1
+    scb = torch.empty(Sb, dtype=torch.float32, device="cuda")
+    kb = torch.empty(M * batch, dtype=torch.int32, device="cuda")
+    t_oneb = timed_calls(ev, stream, lambda: lemo.lemo_head_mean_select_topk(colb, dgb, L, k, flags=flags, scores=scb, kept_idx=kb), 5)
+    t_selb = timed_calls(ev, stream, lambda: lemo.lemo_select_topk(scb, L, k, kept_idx=kb), 5)
+    del colb, dgb
+    bytes_one = 2.0 * H * S * 4 + S * 4 + M * 4
+    bytes_sel = S * 4.0 + M * 4.0
+    return {"what": f"head mean + per-segment top-k at S={S}, {H} heads: two launches vs one; then {batch} independent score sets per launch",
+            "two_launches_us": round(t_two * 1e3, 3), "one_launch_us": round(t_one * 1e3, 3), "select_alone_us": round(t_sel * 1e3, 3),
+            "batched": {"sets": batch, "fused_ms": round(t_oneb, 5), "fused_gbs": round(bytes_one * batch / t_oneb * 1e-6, 1),
+                        "fused_frac_hbm_peak": round(bytes_one * batch / t_oneb * 1e-6 / PEAK_HBM_GBS, 4),
+                        "select_ms": round(t_selb, 5), "select_gbs": round(bytes_sel * batch / t_selb * 1e-6, 1),
+                        "select_frac_hbm_peak": round(bytes_sel * batch / t_selb * 1e-6 / PEAK_HBM_GBS, 4)}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C5", help="C1..C5 (default C5: S=32768 Llama2-7B-shaped layer with backward scatter)")
+    ap.add_argument("--secondary", default="C4", help="a second configuration timed the same way after the first and reported "
+                                                      "under 'secondary' (default C4: the S=16384 half of the metric); 'none' to skip")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) so that a counter profile of this command "
                          "contains a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--step-only", action="store_true",
-                    help="skip the measurements outside the timed step (gather_fold, fused_in_place_add, gemm_backward, "
-                         "kept_attention, block_wise), so that a profile of this command holds the step's kernels only")
+                    help="time the step of --config and nothing else (no secondary configuration, no ceilings, none of the "
+                         "measurements outside the timed step), so that a profile of this command holds the step's kernels only")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU (the path has no cross-GPU step: heads, segments and sequences shard without communication beyond one small all-reduce); "
@@ -301,93 +481,36 @@ def main():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
-    cfg = wl.CONFIGS[args.config]
-    flags = lemo.CAUSAL | lemo.EXCLUDE_SELF
-    print(f"[bench] building synthetic layer {cfg.name}: S={cfg.S} H={cfg.H}/{cfg.H_kv} d={cfg.d} C={cfg.C} N={cfg.N} "
-          f"L={cfg.L} k={cfg.k} M={cfg.M} {cfg.dtype}", file=sys.stderr, flush=True)
-    lay = wl.make_layer(cfg, device="cuda")
-    Q, K, X, W, G = lay["Q"], lay["K"], lay["X"], lay["W"], lay.get("G")
-    dev = Q.device
-    S, H = cfg.S, cfg.H
-    lse2 = torch.empty((H, S), dtype=torch.float32, device=dev)
-    col = torch.empty((H, S), dtype=torch.float32, device=dev)
-    dg = torch.empty((H, S), dtype=torch.float32, device=dev)
-    scores = torch.empty(S, dtype=torch.float32, device=dev)
-    kept = torch.empty(cfg.M, dtype=torch.int32, device=dev)
-    Y = torch.empty((cfg.M, cfg.N), dtype=X.dtype, device=dev)
-    dX = torch.zeros((S, cfg.C), dtype=X.dtype, device=dev)
-    do_scatter = cfg.backward
-
-    phases = ["rowstats", "colsum", "head_mean", "select", "gather_gemm"] + (["scatter"] if do_scatter else [])
     ev = HipEvents()
     stream = torch.cuda.current_stream().cuda_stream
-    marks = [[ev.create() for _ in range(len(phases) + 1)] for _ in range(args.steps)]
-
-    def step(m=None):
-        if m: ev.record(m[0], stream)
-        lemo.lemo_score_rowstats(Q, K, flags=flags, lse2=lse2)
-        if m: ev.record(m[1], stream)
-        lemo.lemo_score_colsums(Q, K, cfg.L, lse2, flags=flags, colsum_per_head=col, diag_per_head=dg)
-        if m: ev.record(m[2], stream)
-        lemo.lemo_score_head_mean(col, dg, flags=flags, scores=scores)
-        if m: ev.record(m[3], stream)
-        lemo.lemo_select_topk(scores, cfg.L, cfg.k, kept_idx=kept)
-        if m: ev.record(m[4], stream)
-        lemo.lemo_gather_gemm(X, kept, W, Y=Y)
-        if m: ev.record(m[5], stream)
-        if do_scatter:
-            lemo.lemo_scatter_grad(G, kept, dX)
-            ev.record(m[6], stream) if m else None
+    cfg = wl.CONFIGS[args.config]
+    run = LayerRun(cfg, lemo, wl, ev, stream)
 
     if args.copy_calibration:
-        a = torch.ones(1 << 29, dtype=torch.bfloat16, device=dev)  # 1 GiB read + 1 GiB written per copy
+        a = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda")  # 1 GiB read + 1 GiB written per copy
         b = torch.empty_like(a)
         for _ in range(2):
             b.copy_(a)
         torch.cuda.synchronize()
         del a, b
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(marks[i])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step, report = run.run(args.steps, args.warmup)
 
     work = algorithmic_work(cfg)
-    phase_ms, phase_min, phase_med = {}, {}, {}
-    for pi, name in enumerate(phases):
-        ts = sorted(ev.elapsed_ms(marks[i][pi], marks[i][pi + 1]) for i in range(args.steps))
-        phase_ms[name] = sum(ts) / len(ts)
-        phase_min[name], phase_med[name] = ts[0], ts[len(ts) // 2]
     peak_tflops = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS
-    report = {}
-    for name in phases:
-        ms = phase_ms[name]
-        w = work[name]
-        r = {"ms": round(ms, 5), "ms_median": round(phase_med[name], 5), "ms_min": round(phase_min[name], 5)}
-        if "flops" in w:
-            r["tflops"] = round(w["flops"] / (ms * 1e-3) * 1e-12, 2)
-            r["frac_mfma_peak"] = round(r["tflops"] / peak_tflops, 4)
-        if "bytes" in w:
-            r["gbs"] = round(w["bytes"] / (ms * 1e-3) * 1e-9, 2)
-            r["frac_hbm_peak"] = round(r["gbs"] / PEAK_HBM_GBS, 5)
-        report[name] = r
-
-    dominant = max(phases, key=lambda n: phase_ms[n])
-    traffic = MEASURED_TRAFFIC_BYTES.get(f"{cfg.name}:{dominant}")  # null for configurations that were not profiled
+    dominant = max(run.phases, key=lambda n: report[n]["ms"])
+    traffic = measured_traffic(f"{cfg.name}:{dominant}")  # null when unprofiled, or profiled on other kernel sources
     if "flops" in work[dominant]:
         roof = {"bound": "mfma", "kernel": dominant, "achieved": report[dominant]["tflops"], "peak": peak_tflops,
                 "unit": "TFLOP/s", "frac": round(report[dominant]["tflops"] / peak_tflops, 4), "traffic": traffic}
     else:
         roof = {"bound": "hbm", "kernel": dominant, "achieved": report[dominant]["gbs"], "peak": PEAK_HBM_GBS,
                 "unit": "GB/s", "frac": round(report[dominant]["gbs"] / PEAK_HBM_GBS, 4), "traffic": traffic}
+    roof["traffic_measured_on_sources"] = MEASURED_TRAFFIC_BYTES["sources"]
+    roof["sources"] = sources_digest()
 
     out = {
         "metric": "tokens scored+selected+gathered/sec per layer",
-        "value": round(S / (ms_per_step * 1e-3), 1),
+        "value": round(cfg.S / (ms_per_step * 1e-3), 1),
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -398,23 +521,38 @@ def main():
         "vs_baseline": None,
         "dtype": cfg.dtype,
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: one Llama-shaped layer, S={S}, {cfg.H}x{cfg.d} heads ({cfg.H_kv} KV), hidden {cfg.C}, "
-                               f"consumer GEMM {cfg.C}->{cfg.N}, segment {cfg.L}, keep ratio {cfg.ratio} (k={cfg.k}, M={cfg.M}), causal, "
-                               f"self term excluded" + (", backward scatter-add included" if do_scatter else ""),
-                   "S": S, "H": cfg.H, "H_kv": cfg.H_kv, "d": cfg.d, "C": cfg.C, "N": cfg.N, "L": cfg.L, "k": cfg.k, "M": cfg.M},
+        "config": {"workload": run.workload(),
+                   "S": cfg.S, "H": cfg.H, "H_kv": cfg.H_kv, "d": cfg.d, "C": cfg.C, "N": cfg.N, "L": cfg.L, "k": cfg.k, "M": cfg.M},
         "roofline": roof,
         "phases": report,
     }
     if not args.step_only:
-        out["gather_fold"] = measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, Y)
+        Q, K, X, W, kept, flags = run.Q, run.K, run.X, run.W, run.kept, run.flags
+        out["ceilings"] = measure_ceilings(cfg, ev, stream, X, W, kept, lemo)
+        ceil = out["ceilings"]
+        for name in ("rowstats", "colsum", "gather_gemm"):
+            if "tflops" in report.get(name, {}):
+                report[name]["frac_library_gemm"] = round(report[name]["tflops"] / ceil["library_gemm_tflops"], 4)
+        if "scatter" in report:
+            report["scatter"]["frac_device_copy"] = round(report["scatter"]["gbs"] / ceil["device_copy_gbs"], 4)
+        out["select"] = measure_select(cfg, lemo, ev, stream, run.col, run.dg, flags)
+        out["gather_fold"] = measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, run.Y)
         out["fused_in_place_add"] = measure_fused_output_projection(cfg, lemo, ev, stream, kept)
         out["gemm_backward"] = measure_gemm_backward(cfg, lemo, ev, stream, X, W, kept)
         if cfg.dtype == "bf16":
             out["kept_attention"] = measure_kept_attention(cfg, lemo, ev, stream, Q, K, kept)
-        out["block_wise"] = measure_block_scoring(cfg, lemo, ev, stream, Q, K, lse2, flags)
-    if not args.no_cpu_baseline:
+        out["block_wise"] = measure_block_scoring(cfg, lemo, ev, stream, Q, K, run.lse2, flags)
+    if not args.no_cpu_baseline and not args.step_only:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
-        out["cpu_baseline"] = cpu_baseline(cfg, lay, wl)
+        out["cpu_baseline"] = cpu_baseline(cfg, run.lay, wl)
+    if not args.step_only and args.secondary.lower() != "none" and args.secondary != args.config:
+        del run
+        torch.cuda.empty_cache()
+        cfg2 = wl.CONFIGS[args.secondary]
+        run2 = LayerRun(cfg2, lemo, wl, ev, stream)
+        ms2, rep2 = run2.run(args.steps, args.warmup)
+        out["secondary"] = {"workload": run2.workload(), "value": round(cfg2.S / (ms2 * 1e-3), 1), "unit": "tokens/s",
+                            "ms_per_step": round(ms2, 4), "steps": args.steps, "warmup": args.warmup, "dtype": cfg2.dtype, "phases": rep2}
     print(json.dumps(out), flush=True)
 
 
