@@ -19,6 +19,8 @@ SCATTER_ACCUMULATE, SCATTER_ZERO_PAD = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lemo_oracle.c")
 _LIB = os.path.join(_HERE, "liblemo_oracle.so")
+# a prebuilt library to load instead (the sanitizer run of the test suite points this at an instrumented build)
+_OVERRIDE = os.environ.get("LEMO_ORACLE_LIB")
 _lock = threading.Lock()
 _lib = None
 
@@ -37,7 +39,7 @@ def _load():
     global _lib
     with _lock:
         if _lib is None:
-            lib = ctypes.CDLL(build())
+            lib = ctypes.CDLL(_OVERRIDE if _OVERRIDE else build())
             i64, i32, u32, dbl, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_double, ctypes.c_void_p
             lib.oracle_keep_k.restype = i32
             lib.oracle_keep_k.argtypes = [i32, dbl]
