@@ -119,6 +119,26 @@ int lemo_score_segments(const void* Q, const void* K, int64_t S, int32_t H, int3
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * lemo_score_segments for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the
+ * same bits in `scores`; the three [H, S] float planes live in a fixed array inside the library's code object
+ * instead of a workspace, so the per-head outputs are not offered.
+ *
+ *   Limit: H * S <= 1048576 (12 MiB of scratch, held by every GPU the library runs on until the process
+ *   ends); larger shapes return LEMO_ERR_UNSUPPORTED and launch nothing.
+ *   The call allocates and frees nothing.  Its first call on a device looks the array's device address up
+ *   (hipGetSymbolAddress, once per device, with that device current; LEMO_ERR_HIP if that fails) -- make that
+ *   first call outside a stream capture, like the first call of any entry point.
+ *   All calls on one GPU share the one array: two calls whose work overlaps in time on the same GPU (different
+ *   streams, or different host threads) race; calls on one stream are ordered and safe.  The array keeps the
+ *   last call's contents; the kernels write every element they later read, so nothing needs clearing.
+ */
+int lemo_score_segments_static(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d,
+                               lemo_dtype_t dt, int64_t q_tok_stride, int64_t q_head_stride,
+                               int64_t k_tok_stride, int64_t k_head_stride, float scale, int32_t L,
+                               uint32_t flags, float* scores, void* stream);
+
+/*
  * The three steps lemo_score_segments runs back to back, callable one at a time (same kernels, same
  * bits) so that each can be timed or reused.  Arguments mean what they mean above.
  *

@@ -1,9 +1,19 @@
 // Host side of the C ABI declared in lemo.h: argument validation and kernel launches only.
 #include <cmath>
+#include <mutex>
 
 #include "lemo_common.hpp"
 
 using namespace lemo;
+
+// Scratch of lemo_score_segments_static: the three [H, S] float planes (row log-sum-exp, per-head column sums,
+// per-head diagonal) that lemo_score_segments takes from the caller's workspace, for H * S up to LEMO_STATIC_MAX_HS.
+// Every GPU the library runs on holds its own copy of this array, at its own address, until the process ends.  In host
+// code the name below is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+// (No `used` attribute here: the compiler gives a static device variable external linkage in the code object -- which
+// the runtime's lookup by name needs -- when it sees the host reference below; `used` would emit it earlier, local.)
+constexpr long long LEMO_STATIC_MAX_HS = 1ll << 20;
+static __device__ __align__(256) unsigned char scratch[3 * LEMO_STATIC_MAX_HS * sizeof(float)];
 
 namespace {
 
@@ -11,6 +21,24 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline bool valid_dtype(int dt) { return dt == LEMO_F32 || dt == LEMO_BF16; }
 inline int elems_per_16B(int dt) { return dt == LEMO_BF16 ? 8 : 4; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// device address of the current device's copy of `scratch`, looked up once per device
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void* scratch_address[MAX_DEVICES];
+
+int scratch_of_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return LEMO_ERR_HIP;
+    std::lock_guard<std::mutex> guard(scratch_mutex);
+    if (!scratch_address[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LEMO_ERR_HIP;
+        scratch_address[dev] = p;
+    }
+    *out = scratch_address[dev];
+    return LEMO_OK;
+}
 
 int32_t seg_keep(int64_t len, int32_t L, int32_t k) {
     if (len == L) return k;
@@ -159,6 +187,30 @@ int lemo_score_segments(const void* Q, const void* K, int64_t S, int32_t H, int3
     p.diag = diag_per_head ? diag_per_head : reinterpret_cast<float*>(ws + 2 * plane);
     p.scores = scores;
     return hip_rc(launch_score(p, dt, d, 7, static_cast<hipStream_t>(stream)));  // the three steps, back to back
+}
+
+int lemo_score_segments_static(const void* Q, const void* K, int64_t S, int32_t H, int32_t H_kv, int32_t d, lemo_dtype_t dt,
+                               int64_t q_tok_stride, int64_t q_head_stride, int64_t k_tok_stride, int64_t k_head_stride,
+                               float scale, int32_t L, uint32_t flags, float* scores, void* stream) {
+    ScoreParams p;
+    const int rc = check_qk(Q, K, S, H, H_kv, d, dt, q_tok_stride, q_head_stride, k_tok_stride, k_head_stride, scale, flags, p);
+    if (rc != LEMO_OK) return rc;
+    if (!scores) return LEMO_ERR_NULL;
+    if (L <= 0) return LEMO_ERR_SHAPE;
+    if ((long long)H * (long long)S > LEMO_STATIC_MAX_HS) return LEMO_ERR_UNSUPPORTED;  // beyond the built-in scratch
+    void* base = nullptr;
+    const int src = scratch_of_current_device(&base);
+    if (src != LEMO_OK) return src;
+    // Every element of the three planes that a later step reads is written by the step before it (row statistics
+    // for all S queries, column sums and diagonals for all S keys), so nothing has to be cleared between calls.
+    const size_t plane = round_up((size_t)H * (size_t)S * sizeof(float), 256);
+    char* ws = static_cast<char*>(base);
+    p.L = L;
+    p.lse2 = reinterpret_cast<float*>(ws);
+    p.colsum = reinterpret_cast<float*>(ws + plane);
+    p.diag = reinterpret_cast<float*>(ws + 2 * plane);
+    p.scores = scores;
+    return hip_rc(launch_score(p, dt, d, 7, static_cast<hipStream_t>(stream)));
 }
 
 int lemo_select_topk(const float* scores, int64_t S, int32_t L, int32_t k, int32_t* kept_idx, void* stream) {

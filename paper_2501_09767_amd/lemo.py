@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblemo_hip.so")
 
 EXPORTS = ("lemo_strerror", "lemo_keep_k", "lemo_kept_count", "lemo_score_workspace_bytes",
-           "lemo_score_segments", "lemo_score_rowstats", "lemo_score_colsums", "lemo_score_head_mean",
+           "lemo_score_segments", "lemo_score_segments_static", "lemo_score_rowstats", "lemo_score_colsums", "lemo_score_head_mean",
            "lemo_select_topk", "lemo_head_mean_select_topk", "lemo_launch_floor", "lemo_gather_gemm", "lemo_gather_gemm_add", "lemo_scatter_grad",
            "lemo_score_blocks_workspace_bytes", "lemo_score_blocks", "lemo_threshold_init", "lemo_select_threshold",
            "lemo_kept_attention_workspace_bytes", "lemo_kept_attention",
@@ -51,6 +51,8 @@ def _load() -> ctypes.CDLL:
     lib.lemo_score_segments.restype = ctypes.c_int
     lib.lemo_score_segments.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, f32, i32, u32,
                                         vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.lemo_score_segments_static.restype = ctypes.c_int
+    lib.lemo_score_segments_static.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, f32, i32, u32, vp, vp]
     lib.lemo_score_rowstats.restype = ctypes.c_int
     lib.lemo_score_rowstats.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, f32, u32, vp, vp]
     lib.lemo_score_colsums.restype = ctypes.c_int
@@ -162,6 +164,19 @@ def lemo_score_segments(Q: torch.Tensor, K: torch.Tensor, L: int, flags: int = C
                                     K.stride(1), float(scale), int(L), int(flags), _ptr(scores), _ptr(colsum_per_head),
                                     _ptr(diag_per_head), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                     _stream()), "lemo_score_segments")
+    return scores
+
+
+def lemo_score_segments_static(Q: torch.Tensor, K: torch.Tensor, L: int, scores: torch.Tensor,
+                               flags: int = CAUSAL | EXCLUDE_SELF, scale: float = 0.0) -> torch.Tensor:
+    """lemo_score_segments without a workspace (the library's built-in scratch; H*S <= 2**20).  Allocates nothing:
+    `scores` [S] float32 must be passed in."""
+    a = _qk_args(Q, K)
+    _dev(scores)
+    if scores.dtype != torch.float32 or tuple(scores.shape) != (a[2],) or not scores.is_contiguous():
+        raise ValueError("scores must be contiguous float32 [S]")
+    _check(_lib.lemo_score_segments_static(*a, float(scale), int(L), int(flags), _ptr(scores), _stream()),
+           "lemo_score_segments_static")
     return scores
 
 

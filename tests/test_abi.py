@@ -175,3 +175,22 @@ def test_block_score_threshold_attention_and_gradient_argument_errors(lib):
     assert dw(dW=None) == -1 and dw(dY=None) == -1 and dw(ws=None) == -1
     assert dw(ldy=16) == -2 and dw(idx=None, M=200) == -2
     assert dw(N=36, ldy=40) == -6 and dw(ldx=68) == -5 and dw(wsb=64) == -4 and dw(dt=2) == -3
+
+
+def test_static_scratch_and_fused_select_argument_errors(lib):
+    """lemo_score_segments_static and lemo_head_mean_select_topk refuse bad arguments on the host (no GPU needed: every
+    case returns before the first HIP call)."""
+    lib.lemo_score_segments_static.argtypes = [vp, vp, i64, i32, i32, i32, ctypes.c_int, i64, i64, i64, i64, f32, i32, u32, vp, vp]
+    st = _caller(lib.lemo_score_segments_static, ("Q", "K", "S", "H", "Hkv", "d", "dt", "qts", "qhs", "kts", "khs", "scale", "L", "flags", "scores", "st"),
+                 dict(Q=A, K=B, S=1024, H=4, Hkv=4, d=64, dt=0, qts=256, qhs=64, kts=256, khs=64, scale=0.0, L=128, flags=3, scores=C_, st=None))
+    assert st(Q=None) == -1 and st(scores=None) == -1
+    assert st(S=0) == -2 and st(L=0) == -2 and st(Hkv=3) == -2
+    assert st(dt=2) == -3 and st(qts=258) == -5 and st(d=80) == -6
+    assert st(S=(1 << 20) // 4 + 1) == -6          # H * S beyond the built-in scratch
+    assert st(S=32769, H=32, Hkv=32, qts=2048, kts=2048) == -6
+    lib.lemo_head_mean_select_topk.argtypes = [vp, vp, i64, i32, u32, i32, i32, vp, vp, vp]
+    hs = _caller(lib.lemo_head_mean_select_topk, ("col", "dg", "S", "H", "flags", "L", "k", "scores", "kept", "st"),
+                 dict(col=A, dg=B, S=1024, H=4, flags=3, L=128, k=64, scores=C_, kept=D, st=None))
+    assert hs(col=None) == -1 and hs(dg=None) == -1 and hs(scores=None) == -1 and hs(kept=None) == -1
+    assert hs(S=0) == -2 and hs(H=0) == -2 and hs(flags=4) == -2 and hs(k=0) == -2 and hs(k=129) == -2 and hs(L=0) == -2
+    assert hs(L=40000, k=5) == -6
