@@ -193,13 +193,13 @@ __device__ __forceinline__ void rowstat_frozen_slice(int c, const f32x16& raw, f
     }
 }
 
-// FROZEN = true: the first launch.  The running maximum is tracked through the first stage (and through every
-// masked tile); from then on unmasked tiles add exp2(s*c2 - m) against the maximum frozen at that point, which
-// saves the maximum search and the rescale.  Should a later logit exceed the frozen reference by more than the
-// binary32 exponent range the sum overflows and lse2 comes out non-finite.
-// FROZEN = false: the second launch, same grid.  A workgroup whose rows all have a finite lse2 exits at once;
-// otherwise it recomputes its rows with the running maximum everywhere.
-template <typename T, int D, int NRT, bool FROZEN>
+// First pass, frozen reference: the running maximum is tracked through the first stage (and through every masked
+// tile); from then on unmasked tiles add exp2(s*c2 - m) against the maximum frozen at that point, which saves the
+// maximum search and the rescale.  Should a later logit exceed the frozen reference by more than the binary32
+// exponent range the sum overflows and lse2 comes out non-finite.  A workgroup that finds such a row among its own
+// (normally none does) goes through its keys a second time with the running maximum everywhere, before it stores
+// anything: no second launch, no extra traffic when there is nothing to repair.
+template <typename T, int D, int NRT>
 __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats_kernel(ScoreParams p) {
     using G = Geo<T, D, NRT>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -217,11 +217,6 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
     const float c2 = p.c2;
     const int q0 = qb * G::BLOCK;        // first query of the workgroup
     const int qw0 = q0 + wave * G::RES;  // first query of this wave
-    if (!FROZEN) {
-        bool bad = false;
-        for (int r = tid; r < G::BLOCK; r += SC_THREADS) bad |= q0 + r < S && !isfinite(p.lse2[(size_t)h * S + q0 + r]);
-        if (!__syncthreads_or(bad)) return;
-    }
 
     // resident operand: this wave's queries as MFMA B fragments
     u32x4 qf[NRT][G::NCH];
@@ -229,10 +224,6 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
     for (int qt = 0; qt < NRT; ++qt)
 #pragma unroll
         for (int c = 0; c < G::NCH; ++c) qf[qt][c] = load_piece(Qb, p.q_ts, q_off, qw0 + qt * 32 + l32, S, c * 32 + half * 16);
-
-    float m[NRT], l[NRT];  // statistics of the queries qw0 + qt*32 + l32 this lane keeps
-#pragma unroll
-    for (int qt = 0; qt < NRT; ++qt) { m[qt] = -INFINITY; l[qt] = 0.f; }
 
     // key stages [0, nstage): under a causal mask only keys up to the block's last query matter
     const int q_last = min(q0 + G::BLOCK, S) - 1;
@@ -243,6 +234,13 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
     int st_voff[G::NLOAD];
     stage_offsets<G>(st_voff, k_row_bytes, tid);
     const unsigned lds_w = lds_offset_of(smem) + (unsigned)__builtin_amdgcn_readfirstlane(wave) * 1024u;
+
+    float lse[NRT];       // the result: lse2 of query qw0 + qt*32 + l32
+    bool frozen = true;   // wave-uniform (in fact workgroup-uniform): which pass this is
+    for (;;) {
+    float m[NRT], l[NRT];  // statistics of the queries qw0 + qt*32 + l32 this lane keeps
+#pragma unroll
+    for (int qt = 0; qt < NRT; ++qt) { m[qt] = -INFINITY; l[qt] = 0.f; }
 
     // carry: the last computed tile whose statistics have not been folded in yet (it belongs to the last
     // query subtile); -inf means "none"
@@ -262,15 +260,17 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
         const bool skip = causal && k0 > qw0 + G::RES - 1;  // every key lies after every query
         const bool clean = causal ? (k0 + G::TILE - 1 <= qw0) : (k0 + G::TILE <= S);
         const char* sbuf = smem + (t & 1) * G::STAGE_BYTES;
-        const bool hot = clean && FROZEN && t > 0;
+        const bool hot = clean && frozen && t > 0;
         if (more && !hot) stage_load<G>(st_voff, next_desc, next_lds);  // (the hot path spreads them over its tiles)
         if (hot) {
             // pipelined, frozen reference: exp/sum of the previous tile between the MFMAs of tile (ks, qt)
-            float nm[NRT];
+            // (the sum of a query is kept in two halves, l and l2, that the exponentials are added to directly)
+            float nm[NRT], l2[NRT];
 #pragma unroll
             for (int q = 0; q < NRT; ++q) {
                 m[q] = m[q] == -INFINITY ? 0.f : m[q];  // nothing seen yet: take 0 as the reference
                 nm[q] = -m[q];
+                l2[q] = 0.f;
             }
             u32x4 kf[G::NCH];
             read_frags<G>(kf, sbuf, 0, l32, half);
@@ -282,18 +282,16 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
                 for (int qt = 0; qt < NRT; ++qt) {  // tile (ks, qt) while the tile before it is summed
                     const int pq = (qt + NRT - 1) % NRT;  // query subtile of the tile before
                     f32x16 acc = {0};
-                    float s0 = 0.f, s1 = 0.f;
                     slot_fence();
 #pragma unroll
                     for (int c = 0; c < G::NCH; ++c) {
-                        rowstat_frozen_slice<G::NCH>(c, prev, c2, nm[pq], s0, s1);
+                        rowstat_frozen_slice<G::NCH>(c, prev, c2, nm[pq], l[pq], l2[pq]);
                         mma_chunk<T>(acc, kf[c], qf[qt][c]);  // acc[key row][query col]
                         if (c == 1) stage_load_slot<G>(st_voff, next_desc, next_lds, ks * NRT + qt, G::NSUB * NRT);
                         if (qt == NRT - 1 && ks + 1 < G::NSUB)
                             kn[c] = *reinterpret_cast<const u32x4*>(&sbuf[G::frag((ks + 1) * 32 + l32, c, half)]);
                         slot_fence();
                     }
-                    l[pq] += s0 + s1;
                     prev = acc;
                 }
                 carry = prev;
@@ -302,6 +300,8 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
                     for (int c = 0; c < G::NCH; ++c) kf[c] = kn[c];
                 }
             }
+#pragma unroll
+            for (int q = 0; q < NRT; ++q) l[q] += l2[q];
         } else if (clean) {
             // pipelined, running maximum: the statistics update of the previous tile is issued slice by slice
             // between the MFMAs of tile (ks, qt); fragments of the next key subtile are read during the last chain
@@ -369,14 +369,24 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void rowstats
     rowstat_update(carry, c2, m[NRT - 1], l[NRT - 1]);
 
     // the two half-waves hold disjoint key rows of the same queries: merge, then lse2 = m + log2(l)
+    bool bad = false;
 #pragma unroll
     for (int qt = 0; qt < NRT; ++qt) {
         const float mo = __shfl_xor(m[qt], 32), lo = __shfl_xor(l[qt], 32);
         const float mt = fmaxf(m[qt], mo);
         const float ms = mt == -INFINITY ? 0.f : mt;
         const float lt = l[qt] * __builtin_amdgcn_exp2f(m[qt] - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
+        lse[qt] = mt + __builtin_amdgcn_logf(lt);
+        bad |= qw0 + qt * 32 + l32 < S && !isfinite(lse[qt]);
+    }
+    // every wave is past its last read of the stages here as well, so a second pass may refill them
+    if (!frozen || !__syncthreads_or(bad)) break;
+    frozen = false;
+    }
+#pragma unroll
+    for (int qt = 0; qt < NRT; ++qt) {
         const int q = qw0 + qt * 32 + l32;
-        if (half == 0 && q < S) p.lse2[(size_t)h * S + q] = mt + __builtin_amdgcn_logf(lt);
+        if (half == 0 && q < S) p.lse2[(size_t)h * S + q] = lse[qt];
     }
 }
 
@@ -444,9 +454,9 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void colsum_k
 #pragma unroll
         for (int c = 0; c < G::NCH; ++c) kf[kt][c] = load_piece(Kb, p.k_ts, k_off, kw0 + kt * 32 + l32, kend, c * 32 + half * 16);
 
-    float col[NRT], dg[NRT];  // column kw0 + kt*32 + l32
+    float col[NRT], col2[NRT], dg[NRT];  // column kw0 + kt*32 + l32 (its sum kept in two halves, col and col2)
 #pragma unroll
-    for (int kt = 0; kt < NRT; ++kt) { col[kt] = 0.f; dg[kt] = 0.f; }
+    for (int kt = 0; kt < NRT; ++kt) { col[kt] = 0.f; col2[kt] = 0.f; dg[kt] = 0.f; }
 
     // query stages run from the end of the sequence DOWN to the first stage that can see this block, so
     // that all key blocks of a head walk the same query rows at about the same time (shared through L2)
@@ -503,12 +513,11 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void colsum_k
                 for (int kt = 0; kt < NRT; ++kt) {  // tile (qs, kt) while the tile before it is summed
                     const int pk = (kt + NRT - 1) % NRT;  // key subtile of the tile before
                     f32x16 acc = {0};
-                    float s0 = 0.f, s1 = 0.f;
                     slot_fence();
 #pragma unroll
                     for (int c = 0; c < G::NCH; ++c) {
-                        if (kt == 0) colsum_slice<G::NCH>(c, prev, carry_nl, c2, s0, s1);  // the carried tile has its own rows
-                        else colsum_slice<G::NCH>(c, prev, nl, c2, s0, s1);
+                        if (kt == 0) colsum_slice<G::NCH>(c, prev, carry_nl, c2, col[pk], col2[pk]);  // the carried tile has its own rows
+                        else colsum_slice<G::NCH>(c, prev, nl, c2, col[pk], col2[pk]);
                         mma_chunk<T>(acc, qf[c], kf[kt][c]);  // acc[query row][key col]
                         if (c == 1) stage_load_slot<G>(st_voff, next_desc, next_lds, qs * NRT + kt, G::NSUB * NRT);
                         if (kt == NRT - 1 && qs + 1 < G::NSUB) {
@@ -520,7 +529,6 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void colsum_k
                         }
                         slot_fence();
                     }
-                    col[pk] += s0 + s1;
                     prev = acc;
                 }
                 carry = prev;
@@ -576,6 +584,7 @@ __global__ __launch_bounds__(SC_THREADS, (Geo<T, D, NRT>::MIN_WG)) void colsum_k
 
 #pragma unroll
     for (int kt = 0; kt < NRT; ++kt) {
+        col[kt] += col2[kt];
         const float c = col[kt] + __shfl_xor(col[kt], 32);
         const float dd = dg[kt] + __shfl_xor(dg[kt], 32);
         const int key = kw0 + kt * 32 + l32;
@@ -620,20 +629,16 @@ static int launch_sweeps(const ScoreParams& p_in, int which, hipStream_t st) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {  // the kernels use more dynamic LDS than the default limit
-        const void* ks[3] = {reinterpret_cast<const void*>(&rowstats_kernel<T, D, NRT, true>),
-                             reinterpret_cast<const void*>(&rowstats_kernel<T, D, NRT, false>),
+        const void* ks[2] = {reinterpret_cast<const void*>(&rowstats_kernel<T, D, NRT>),
                              reinterpret_cast<const void*>(&colsum_kernel<T, D, NRT>)};
-        const int bytes[3] = {G::LDS_ROWSTATS, G::LDS_ROWSTATS, G::LDS_COLSUM};
-        for (int i = 0; i < 3 && attr_err == hipSuccess; ++i)
+        const int bytes[2] = {G::LDS_ROWSTATS, G::LDS_COLSUM};
+        for (int i = 0; i < 2 && attr_err == hipSuccess; ++i)
             attr_err = hipFuncSetAttribute(ks[i], hipFuncAttributeMaxDynamicSharedMemorySize, bytes[i]);
     });
     if (attr_err != hipSuccess) return (int)attr_err;
     const unsigned g1 = (unsigned)(NUM_XCD * p.heads_per_xcd * p.n_query_blocks);
     const unsigned g2 = (unsigned)(NUM_XCD * p.heads_per_xcd * p.n_key_blocks);
-    if (which & 1) {  // frozen-reference sweep, then the (normally empty) repair pass over rows that overflowed
-        hipLaunchKernelGGL((rowstats_kernel<T, D, NRT, true>), dim3(g1), dim3(SC_THREADS), G::LDS_ROWSTATS, st, p);
-        hipLaunchKernelGGL((rowstats_kernel<T, D, NRT, false>), dim3(g1), dim3(SC_THREADS), G::LDS_ROWSTATS, st, p);
-    }
+    if (which & 1) hipLaunchKernelGGL((rowstats_kernel<T, D, NRT>), dim3(g1), dim3(SC_THREADS), G::LDS_ROWSTATS, st, p);
     if (which & 2) hipLaunchKernelGGL((colsum_kernel<T, D, NRT>), dim3(g2), dim3(SC_THREADS), G::LDS_COLSUM, st, p);
     return (int)hipGetLastError();
 }

@@ -167,17 +167,22 @@ def test_score_steps_compose_to_the_full_call(lemo):
             assert abs(float(lse2[h, i]) - want) < 1e-4 * max(1.0, abs(want))
 
 
-def test_score_reference_overflow_is_repaired(lemo):
+@pytest.mark.parametrize("dominant", [450, 690, 3])
+def test_score_reference_overflow_is_repaired(lemo, dominant):
     """Sweep 1 freezes its reference maximum after the first stage of keys; a key far later whose logit exceeds that
-    reference by more than the binary32 exponent range overflows the frozen sum, and the repair pass must recompute
-    those rows with a running maximum.  Logits of ~360 nats against a first-stage maximum near 0 force that path."""
-    say("[score] frozen-reference overflow -> repair pass")
+    reference by more than the binary32 exponent range overflows the frozen sum, and the workgroup must then go through
+    its keys again with a running maximum.  Logits of ~360 nats against a first-stage maximum near 0 force that path.
+    dominant = 450: unmasked stages of the later query blocks overflow (causal), or of every block (full attention), and
+    the block [256, 512) holds rows that overflow next to rows that do not; 690: under the causal mask the key is only
+    ever met in masked diagonal tiles, which track the maximum, so nothing overflows there; 3: the key lies in the first
+    stage, whose maximum is tracked, so the frozen reference already covers it."""
+    say(f"[score] frozen-reference overflow -> second pass, dominant key {dominant}")
     S, H, d = 700, 2, 128
     rng = np.random.default_rng(123)
     q = np.full((S, H, d), 4.0, dtype=np.float32)
     q[:300] = rng.standard_normal((300, H, d)).astype(np.float32)      # ordinary rows as well
     k = (rng.standard_normal((S, H, d)) * 0.05).astype(np.float32)
-    k[450] = 8.0                                                       # scale * <q, k> = 128*32/sqrt(128) = 362
+    k[dominant] = 8.0                                                  # scale * <q, k> = 128*32/sqrt(128) = 362
     k[611] = -8.0
     Q = torch.from_numpy(q).to(torch.bfloat16)
     K = torch.from_numpy(k).to(torch.bfloat16)
@@ -187,7 +192,8 @@ def test_score_reference_overflow_is_repaired(lemo):
         want, wcol, wdg = oracle.score(wl.as_numpy(Q), wl.as_numpy(K), flags=flags, per_head=True)
         assert_scores_close(col.ravel(), wcol.ravel(), "colsum after repair")
         assert_scores_close(got, want, "scores after repair")
-        assert want[450] > 100  # the dominant key really collects the later queries
+        if dominant < S - 20 or flags == 0:
+            assert want[dominant] > 5  # the dominant key really collects the later queries
 
 
 def test_score_config_C2_full(lemo):
