@@ -411,10 +411,21 @@ def measure_ceilings(cfg, ev, stream, X, W, kept, lemo):
     t_cp = timed_calls(ev, stream, lambda: b.copy_(a), 10)
     del a, b
     t_empty = timed_calls(ev, stream, lemo.lemo_launch_floor, 200)
+    sink = torch.zeros(1, dtype=torch.float32, device=X.device)
+    tiles, waves = 40000, [0]
+
+    def mix():
+        waves[0] = lemo.lemo_probe_sweep_issue_mix(tiles, sink)
+
+    t_mix = timed_calls(ev, stream, mix, 3)
+    mix_tflops = 8 * 32768.0 * tiles * waves[0] / t_mix * 1e-9
     return {"what": "same machine, same run: torch.matmul (library GEMM) on a compact copy of the consumer GEMM's operands; "
-                    "1 GiB device copy (read + write counted); one empty kernel launch, back to back on the stream",
+                    "1 GiB device copy (read + write counted); one empty kernel launch, back to back on the stream; "
+                    "sweep_issue_mix = the sweeps' minimal instruction mix per 32x32 logit tile (8 dependent MFMAs + 16 x (fma, exp2, add), "
+                    "two waves per SIMD) from registers only, quoted as the MFMA flops of the tiles",
             "library_gemm_ms": round(t_mm, 5), "library_gemm_tflops": round(2.0 * cfg.M * cfg.C * cfg.N / t_mm * 1e-9, 2),
-            "device_copy_gbs": round(2.0 * (1 << 30) / t_cp * 1e-6, 1), "empty_launch_us": round(t_empty * 1e3, 3)}
+            "device_copy_gbs": round(2.0 * (1 << 30) / t_cp * 1e-6, 1), "empty_launch_us": round(t_empty * 1e3, 3),
+            "sweep_issue_mix_tflops": round(mix_tflops, 1)}
 
 
 def measure_select(cfg, lemo, ev, stream, col, dg, flags, batch=128):
@@ -533,6 +544,9 @@ def main():
         for name in ("rowstats", "colsum", "gather_gemm"):
             if "tflops" in report.get(name, {}):
                 report[name]["frac_library_gemm"] = round(report[name]["tflops"] / ceil["library_gemm_tflops"], 4)
+        for name in ("rowstats", "colsum"):
+            if "tflops" in report.get(name, {}):
+                report[name]["frac_sweep_issue_mix"] = round(report[name]["tflops"] / ceil["sweep_issue_mix_tflops"], 4)
         if "scatter" in report:
             report["scatter"]["frac_device_copy"] = round(report["scatter"]["gbs"] / ceil["device_copy_gbs"], 4)
         out["select"] = measure_select(cfg, lemo, ev, stream, run.col, run.dg, flags)

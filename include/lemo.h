@@ -188,6 +188,15 @@ int lemo_head_mean_select_topk(const float* colsum_per_head, const float* diag_p
  * microsecond-sized steps (head mean, selection, threshold) are reported against. */
 int lemo_launch_floor(void* stream);
 
+/* Measurement aid: the instruction mix of the scoring sweeps (Sec. 4.2, Eq. 1) with everything else taken away.  Per
+ * 32 x 32 logit tile at head_dim 128 a sweep must issue a chain of 8 dependent 32x32x16 bf16 MFMAs and, per logit, one
+ * fma, one exp2 and one add in binary32; this enqueues a register-only kernel that issues exactly that, two wavefronts
+ * per SIMD on every compute unit, `tiles_per_wave` tiles each (even, at most 2^24).  Timed by the caller, it gives the
+ * rate at which the matrix cores and the vector ALU together get through this mix on the machine at hand:
+ * 8 * 32768 flops * tiles_per_wave * *waves / seconds.  `sink`: one float of device memory (not written in practice);
+ * `waves` (host, out): wavefronts launched. */
+int lemo_probe_sweep_issue_mix(int32_t tiles_per_wave, float* sink, int32_t* waves /* host, out */, void* stream);
+
 /*
  * Block-wise informativeness (Sec. 4.2 "Block-wise Elimination", Eq. 2, and the token-block scores of
  * "Layer-specific Threshold"):

@@ -33,8 +33,11 @@ namespace lemo {
 #define LEMO_NRT_BF16_128 2
 #endif
 
-constexpr int SC_THREADS = 256;  // 4 waves
-constexpr int SC_WAVES = 4;
+#ifndef LEMO_SC_WAVES
+#define LEMO_SC_WAVES 4
+#endif
+constexpr int SC_WAVES = LEMO_SC_WAVES;
+constexpr int SC_THREADS = 64 * SC_WAVES;
 
 // Geometry of one instantiation.  NRT = 32-row MFMA subtiles of the RESIDENT operand a wave keeps in registers:
 //   NRT = 2  64 resident rows per wave, 256 per workgroup, two workgroups per CU (two waves per SIMD)
@@ -64,7 +67,7 @@ template <typename T, int D, int NRT_> struct Geo {
     static constexpr int STAGE_BYTES = TILE * STRIDE;
     static constexpr int LDS_ROWSTATS = 2 * STAGE_BYTES;
     static constexpr int LDS_COLSUM = 2 * STAGE_BYTES + 2 * TILE * (int)sizeof(float);
-    static constexpr int MIN_WG = (ROWB > 256 || NRT > 2) ? 1 : 2;  // workgroups per CU the register budget is set for
+    static constexpr int MIN_WG = (ROWB > 256 || NRT > 2 || SC_WAVES > 4) ? 1 : 2;  // workgroups per CU the register budget is set for
     static_assert(TILE * CPR % SC_THREADS == 0, "tile must split evenly over the workgroup");
 };
 

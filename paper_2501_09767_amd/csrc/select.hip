@@ -21,25 +21,36 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// inclusive prefix sum over the 64 lanes of a wave (DPP-free: five shuffles and a last one across the halves)
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t u = __shfl_up(v, off);
+        if (lane >= off) v += u;
+    }
+    return v;
+}
+
 // The selection proper, shared by the two kernels below: `keys` [len] (LDS) hold the order keys of one segment, the
 // `keep` kept token indices go to kept[out0 ...) in ascending order.  T = threads of the workgroup (a multiple of 256);
-// every thread of the workgroup must call it.
+// every thread of the workgroup must call it.  Scans run inside wavefronts (shuffles) with one pass through LDS for
+// the wave totals, so a radix pass costs four barriers and the compaction two.
 template <int T>
 __device__ __forceinline__ void select_from_keys(const uint32_t* keys, int len, int keep, long long out0, int start,
                                                  int* __restrict__ kept) {
+    constexpr int NW = T / 64;
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t scan[T];
+    __shared__ uint32_t wave_total[NW];
     __shared__ uint32_t sh_prefix, sh_need;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) { sh_prefix = 0u; sh_need = (uint32_t)keep; }
+    if (tid < 256) hist[tid] = 0u;
     __syncthreads();
 
     // radix select: after the pass for `shift`, sh_prefix holds the top bits of the pivot and sh_need how
     // many elements must still be taken among those sharing that prefix
 #pragma unroll 1
     for (int shift = 24; shift >= 0; shift -= 8) {
-        if (tid < 256) hist[tid] = 0u;
-        __syncthreads();
         const uint32_t prefix = sh_prefix, need = sh_need;
         const uint32_t himask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
         for (int t = tid; t < len; t += T) {
@@ -47,20 +58,20 @@ __device__ __forceinline__ void select_from_keys(const uint32_t* keys, int len, 
             if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
         }
         __syncthreads();
-        // suffix sums: scan[b] = number of candidates whose digit is >= b
-        if (tid < 256) scan[tid] = hist[tid];
-        __syncthreads();
-#pragma unroll
-        for (int off = 1; off < 256; off <<= 1) {
-            uint32_t v = (tid < 256 && tid + off < 256) ? scan[tid + off] : 0u;
-            __syncthreads();
-            if (tid < 256) scan[tid] += v;
-            __syncthreads();
-        }
+        // suffix sums over the 256 digits: ge = number of candidates whose digit is >= tid.  Waves 0..3 hold the
+        // digits in DESCENDING order (thread t holds digit 255 - t), so a prefix sum over threads is the suffix sum.
+        uint32_t incl = 0;
         if (tid < 256) {
-            const uint32_t ge = scan[tid], gt = tid + 1 < 256 ? scan[tid + 1] : 0u;
+            incl = wave_inclusive_scan(hist[255 - tid], lane);
+            if (lane == 63) wave_total[wave] = incl;
+        }
+        __syncthreads();
+        if (tid < 256) {
+            for (int w = 0; w < wave; ++w) incl += wave_total[w];
+            const uint32_t ge = incl, gt = incl - hist[255 - tid];
+            hist[255 - tid] = 0u;  // cleared for the next pass (every thread is past its atomics)
             if (gt < need && need <= ge) {  // exactly one digit satisfies this
-                sh_prefix = prefix | ((uint32_t)tid << shift);
+                sh_prefix = prefix | ((uint32_t)(255 - tid) << shift);
                 sh_need = need - gt;
             }
         }
@@ -78,16 +89,11 @@ __device__ __forceinline__ void select_from_keys(const uint32_t* keys, int len, 
         ngt += key > pivot;
         neq += key == pivot;
     }
-    scan[tid] = ngt | (neq << 16);  // len <= 32768 so both counts fit 16 bits, as do their prefix sums
+    // len <= 32768 so both counts fit 16 bits, as do their prefix sums: one scan carries both
+    uint32_t incl = wave_inclusive_scan(ngt | (neq << 16), lane);
+    if (lane == 63) wave_total[wave] = incl;
     __syncthreads();
-#pragma unroll
-    for (int off = 1; off < T; off <<= 1) {
-        uint32_t v = tid >= off ? scan[tid - off] : 0u;
-        __syncthreads();
-        scan[tid] += v;
-        __syncthreads();
-    }
-    const uint32_t incl = scan[tid];
+    for (int w = 0; w < wave; ++w) incl += wave_total[w];
     uint32_t gt_before = (incl & 0xffffu) - ngt, eq_before = (incl >> 16) - neq;
     for (int t = lo; t < hi; ++t) {
         const uint32_t key = keys[t];

@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_HERE, "liblemo_hip.so")
 
 EXPORTS = ("lemo_strerror", "lemo_keep_k", "lemo_kept_count", "lemo_score_workspace_bytes",
            "lemo_score_segments", "lemo_score_segments_static", "lemo_score_rowstats", "lemo_score_colsums", "lemo_score_head_mean",
-           "lemo_select_topk", "lemo_head_mean_select_topk", "lemo_launch_floor", "lemo_gather_gemm", "lemo_gather_gemm_add", "lemo_scatter_grad",
+           "lemo_select_topk", "lemo_head_mean_select_topk", "lemo_launch_floor", "lemo_probe_sweep_issue_mix", "lemo_gather_gemm", "lemo_gather_gemm_add", "lemo_scatter_grad",
            "lemo_score_blocks_workspace_bytes", "lemo_score_blocks", "lemo_threshold_init", "lemo_select_threshold",
            "lemo_kept_attention_workspace_bytes", "lemo_kept_attention",
            "lemo_gather_gemm_dw_workspace_bytes", "lemo_gather_gemm_dw")
@@ -81,6 +81,8 @@ def _load() -> ctypes.CDLL:
     lib.lemo_head_mean_select_topk.argtypes = [vp, vp, i64, i32, u32, i32, i32, vp, vp, vp]
     lib.lemo_launch_floor.restype = ctypes.c_int
     lib.lemo_launch_floor.argtypes = [vp]
+    lib.lemo_probe_sweep_issue_mix.restype = ctypes.c_int
+    lib.lemo_probe_sweep_issue_mix.argtypes = [i32, vp, ctypes.POINTER(i32), vp]
     lib.lemo_select_topk.restype = ctypes.c_int
     lib.lemo_select_topk.argtypes = [vp, i64, i32, i32, vp, vp]
     lib.lemo_gather_gemm.restype = ctypes.c_int
@@ -357,6 +359,16 @@ def lemo_head_mean_select_topk(colsum_per_head: torch.Tensor, diag_per_head: tor
 def lemo_launch_floor() -> None:
     """One empty kernel on the current stream (measurement aid)."""
     _check(_lib.lemo_launch_floor(_stream()), "lemo_launch_floor")
+
+
+def lemo_probe_sweep_issue_mix(tiles_per_wave: int, sink: torch.Tensor) -> int:
+    """Enqueue the register-only instruction mix of the scoring sweeps (measurement aid) -> wavefronts launched."""
+    _dev(sink)
+    if sink.dtype != torch.float32 or sink.numel() < 1:
+        raise ValueError("sink must hold one float32")
+    waves = ctypes.c_int32(0)
+    _check(_lib.lemo_probe_sweep_issue_mix(int(tiles_per_wave), _ptr(sink), ctypes.byref(waves), _stream()), "lemo_probe_sweep_issue_mix")
+    return int(waves.value)
 
 
 def lemo_gather_gemm(X: torch.Tensor, kept_idx: Optional[torch.Tensor], W: torch.Tensor,
