@@ -216,32 +216,27 @@ def measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, Y, reps=10):
 
 
 def measure_gemm_backward(cfg, lemo, ev, stream, X, W, kept, reps=5):
-    """Outside the timed step: both gradients of the consumer GEMM Y = X[kept] W^T at the layer's shape.
-    dX[kept] += dY W  (the in-place-add GEMM with W^T kept as a [C,N] matrix) and dW = dY^T X[kept]."""
+    """Outside the timed step: both gradients of the consumer GEMM Y = X[kept] W^T at the layer's shape, neither with a
+    transposed copy of anything: dX[kept] += dY W with W as stored, and dW = dY^T X[kept] with the kept rows read in place."""
     import torch
     M, C, N = cfg.M, cfg.C, cfg.N
     g = torch.Generator(device="cuda").manual_seed(13)
     dY = (torch.randn((M, N), device="cuda", dtype=torch.float32, generator=g) * 0.05).to(X.dtype)
-    Wt = W.t().contiguous()
     dX = torch.zeros_like(X)
     dW = torch.empty((N, C), dtype=X.dtype, device="cuda")
-    ws = torch.empty(lemo.lemo_gather_gemm_dw_workspace_bytes(M, C, N, lemo.BF16 if cfg.dtype == "bf16" else lemo.F32), dtype=torch.uint8, device="cuda")
-
-    def timed(fn):
-        fn()
-        marks = [ev.create() for _ in range(reps + 1)]
-        ev.record(marks[0], stream)
-        for i in range(reps):
-            fn()
-            ev.record(marks[i + 1], stream)
-        torch.cuda.synchronize()
-        return sum(ev.elapsed_ms(marks[i], marks[i + 1]) for i in range(reps)) / reps
-
-    t_dx = timed(lambda: lemo.lemo_gather_gemm_add(dY, None, Wt, dX, kept))
-    t_dw = timed(lambda: lemo.lemo_gather_gemm_dw(dY, X, kept, dW=dW, workspace=ws))
+    dt = lemo.BF16 if cfg.dtype == "bf16" else lemo.F32
+    need = lemo.lemo_gather_gemm_dw_workspace_bytes(M, C, N, dt)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+    if cfg.dtype == "bf16":
+        t_dx = timed_calls(ev, stream, lambda: lemo.lemo_gather_gemm_dx(dY, W, dX, kept), reps)
+    else:
+        Wt = W.t().contiguous()
+        t_dx = timed_calls(ev, stream, lambda: lemo.lemo_gather_gemm_add(dY, None, Wt, dX, kept), reps)
+    t_dw = timed_calls(ev, stream, lambda: lemo.lemo_gather_gemm_dw(dY, X, kept, dW=dW, workspace=ws), reps)
     flops = 2.0 * M * C * N
-    return {"what": f"gradients of the consumer GEMM, M={M} C={C} N={N}", "dX_ms": round(t_dx, 5), "dX_tflops": round(flops / t_dx * 1e-9, 2),
-            "dW_ms": round(t_dw, 5), "dW_tflops": round(flops / t_dw * 1e-9, 2)}
+    return {"what": f"gradients of the consumer GEMM, M={M} C={C} N={N}, operands read as stored", "dX_ms": round(t_dx, 5),
+            "dX_tflops": round(flops / t_dx * 1e-9, 2), "dW_ms": round(t_dw, 5), "dW_tflops": round(flops / t_dw * 1e-9, 2),
+            "dW_workspace_bytes": need}
 
 
 def measure_kept_attention(cfg, lemo, ev, stream, Q, K, kept, reps=5):

@@ -12,7 +12,7 @@
  * Beside them: the paper's block-wise criterion and threshold rule (lemo_score_blocks, lemo_threshold_init,
  * lemo_select_threshold; Sec. 4.2 Eq. 2, Alg. 1 step 1), the attention block over the kept tokens with its
  * projection added back in place (lemo_kept_attention, lemo_gather_gemm_add; Sec. 4.4), and the gradients
- * of the selective-load GEMM (lemo_gather_gemm_add with the transposed weight, lemo_gather_gemm_dw).
+ * of the selective-load GEMM (lemo_gather_gemm_dx, lemo_gather_gemm_dw).
  *
  * Conventions shared by every call
  *   - Pointers are DEVICE pointers unless the comment says "host".  The caller owns every buffer;
@@ -288,20 +288,32 @@ int lemo_gather_gemm_add(const void* X, int64_t S, int64_t ldx, const int32_t* k
                          const int32_t* out_idx, int32_t C, int32_t N, lemo_dtype_t dt, void* stream);
 
 /*
- * Weight gradient of the selective-load GEMM Y = X[kept_idx] W^T (the backward of Sec. 4.4's selective load with
- * respect to the weights; the gather sits on the contraction axis):
+ * Gradients of the selective-load GEMM Y = X[kept_idx] W^T (the backward of Sec. 4.4's selective load), permutation-free
+ * on this pass as well: neither a transposed copy of the weight nor transposed copies of dY and of the kept rows are made.
  *
- *     dW[n, c] = sum over m < M of dY[m, n] * X[kept_idx[m], c]            n < N, c < C
+ *   lemo_gather_gemm_dx   dX[out_idx[m], c] += sum_n dY[m, n] * W[n, c]         m < M, c < C      (input gradient)
+ *   lemo_gather_gemm_dw   dW[n, c]           = sum over m < M of dY[m, n] * X[kept_idx[m], c]    (weight gradient)
  *
- *   dY [M, N] row stride ldy;  X [S, C] row stride ldx;  dW [N, C] row stride lddw (overwritten);  all of dtype dt;
- *   kept_idx [M] rows of X in [0,S) (not checked on the device), or NULL for rows 0..M-1.  M == 0 writes zeros.
- *   workspace: lemo_gather_gemm_dw_workspace_bytes(M,C,N,dt) bytes, 256-byte aligned, device memory.  It receives
- *   dY and the kept rows of X transposed (the kept rows are read in place; the token axis is padded to a multiple of 64).
+ *   dY [M, N] row stride ldy (compact rows, one per kept token);  W [N, C] row stride ldw, as lemo_gather_gemm takes it;
+ *   dX [S_out, C] row stride lddx, read and written (rows that out_idx does not name are not touched; out_idx NULL means
+ *   rows 0..M-1; each row at most once, values outside [0, S_out) drop the row);  X [S, C] row stride ldx;  dW [N, C] row
+ *   stride lddw (overwritten; M == 0 writes zeros);  kept_idx [M] rows of X in [0,S) (not checked on the device) or NULL
+ *   for rows 0..M-1.  All of dtype dt.
  *
- * binary32 accumulation, one rounding at the store.  Supported: C % 8 == 0 and N % 8 == 0 (bf16) / % 4 (fp32);
- * dY and X follow the 16-byte rule; M below 4M (bf16) / 2M (fp32) tokens and N * M * element size below 4 GiB.
- * (The input gradient of the same GEMM, dX[kept_idx] += dY W, is lemo_gather_gemm_add with W^T stored as [C, N].)
+ * Both products contract over an axis along which the stored operand is NOT contiguous (W over n, dY and X over the
+ * tokens).  For bf16 the kernels stage the operand tiles as they lie in memory and take their matrix-core fragments with
+ * the transposing LDS read of gfx950; the kept rows of X are picked inside the tile load.  binary32 accumulation, one
+ * rounding at the store (for dX after the old value has been added).
+ *
+ * Supported: lemo_gather_gemm_dx: LEMO_BF16 only (fp32: lemo_gather_gemm_add with W^T stored as [C, N]); C % 8 == 0 and
+ * N % 8 == 0; dY, W follow the 16-byte rule; row pitches below 8 MiB; dY and dX spanning less than 4 GiB, W less than
+ * 2 GiB.  lemo_gather_gemm_dw: C % 8 == 0 and N % 8 == 0 (bf16) / % 4 (fp32); bf16 needs no workspace
+ * (lemo_gather_gemm_dw_workspace_bytes reports 0, `workspace` may be NULL) with dY spanning less than 2 GiB and X less than
+ * 4 GiB; fp32 goes through transposed copies of both operands in the workspace (256-byte aligned device memory of the
+ * reported size; M below 2M tokens and N * M * 4 below 4 GiB).
  */
+int lemo_gather_gemm_dx(const void* dY, int64_t ldy, int64_t M, const void* W, int64_t ldw, void* dX, int64_t lddx,
+                        int64_t S_out, const int32_t* out_idx, int32_t C, int32_t N, lemo_dtype_t dt, void* stream);
 int lemo_gather_gemm_dw_workspace_bytes(int64_t M, int32_t C, int32_t N, lemo_dtype_t dt, size_t* bytes);
 int lemo_gather_gemm_dw(const void* dY, int64_t ldy, const void* X, int64_t S, int64_t ldx, const int32_t* kept_idx, int64_t M,
                         void* dW, int64_t lddw, int32_t C, int32_t N, lemo_dtype_t dt, void* workspace,

@@ -26,8 +26,14 @@ namespace lemo {
 // Eight waves per workgroup (two per SIMD: while one wave does its softmax arithmetic the other has the matrix core),
 // each keeping ONE 32-query subtile: 64 accumulator registers for O^T, everything within 256 registers.  One workgroup
 // per CU with two LDS stages of 128 keys: a barrier every four tiles, and a stage of K and V^T is shared by 256 queries.
-constexpr int AT_THREADS = 512;
-constexpr int AT_NQ = 1;                            // 32-query subtiles per wave
+#ifndef LEMO_AT_THREADS
+#define LEMO_AT_THREADS 512
+#endif
+#ifndef LEMO_AT_NQ
+#define LEMO_AT_NQ 1
+#endif
+constexpr int AT_THREADS = LEMO_AT_THREADS;
+constexpr int AT_NQ = LEMO_AT_NQ;                   // 32-query subtiles per wave
 constexpr int AT_BQ = (AT_THREADS / 64) * 32 * AT_NQ;  // queries per workgroup
 constexpr int AT_KT = 128;                          // keys per LDS stage
 constexpr int AT_MPAD = 128;         // the transposed V is padded to a multiple of this many kept tokens

@@ -25,6 +25,24 @@ constexpr int GG_LDS = 2 * GG_STAGE;     // 147456 bytes of the CU's 160 KB
 constexpr int GG_NLD = GG_BM * GG_CPR / GG_THREADS;  // 8 loads per thread per operand per stage
 constexpr int GG_GROUP_M = 4;            // tile rows walked together (keeps a die's 32 tiles to a 4 x 8 patch)
 
+// How the operands lie in memory (an MFMA lane always wants 8 consecutive contraction elements of one operand row):
+//   GG_NT  A rows and B rows run along the contraction (X[idx] [M,C] against an nn.Linear weight [N,C]); 16-byte reads.
+//   GG_NN  A as above; B is stored contraction-major, [C, N] (the same weight used the other way round, as the input
+//          gradient needs it).  Its slabs go to LDS as they are, 64 contraction rows x 256 columns, and the fragments
+//          come out through the transposing LDS read (ds_read_b64_tr_b16: inside a group of 16 lanes, lane l receives
+//          element l % 4 of the 8 bytes addressed by lanes l / 4, 4 + l / 4, 8 + l / 4 and 12 + l / 4 -- with lane
+//          4 j + q pointed at row j, column quad q of a 4-row x 16-column block, lane l gets 4 consecutive rows of
+//          column l).  Two such reads make one 16-byte fragment: the same bytes from LDS as before, no transposed copy
+//          anywhere.
+//   GG_TN  both operands contraction-major: A [C, M], B [C, N] with B's rows picked by idx (the weight gradient: the
+//          contraction runs over the kept tokens).  bf16 only for GG_NN and GG_TN.
+enum { GG_NT = 0, GG_NN = 1, GG_TN = 2 };
+constexpr int GG_KROWS = 64;             // contraction rows per slab of a contraction-major operand
+constexpr int GG_KPITCH = 512 + 32;      // LDS pitch of such a row (256 columns + pad): 136 dwords, so the 4 rows x 4 column
+                                         // quads one 16-lane group reads fall into 32 distinct banks
+static_assert(GG_KROWS * GG_KPITCH <= GG_BM * GG_STRIDE, "a contraction-major slab must fit the operand's LDS region");
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
 // exchange with the neighbouring lane (l ^ 1) inside a quad: DPP quad_perm [1,0,3,2]
 __device__ __forceinline__ float swap_with_neighbour(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
@@ -33,14 +51,17 @@ __device__ __forceinline__ float swap_with_neighbour(float v) {
 // ADD = false: Y[m,:] = result row m.
 // ADD = true:  Y is the residual stream [out_rows, N]; result row m is ADDED in place to row oidx[m] (row m when
 //              oidx is null) -- the zero padding and the residual addition of Sec. 4.4 in one step, one rounding.
-template <typename T, bool ADD>
+// GG_TN: `w_bytes_all` is the span of the whole B tensor (its rows are picked by idx); unused otherwise.
+template <typename T, bool ADD, int LAYOUT>
 __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __restrict__ X, long long ldx,
                                                                     const int* __restrict__ idx, long long M,
                                                                     const T* __restrict__ W, long long ldw,
                                                                     const T* __restrict__ bias, T* __restrict__ Y,
                                                                     long long ldy, int C, int N, int tiles_m, int tiles_n,
                                                                     unsigned x_bytes, const int* __restrict__ oidx,
-                                                                    long long out_rows, unsigned r_bytes) {
+                                                                    long long out_rows, unsigned r_bytes, unsigned w_bytes_all) {
+    static_assert(LAYOUT == GG_NT || sizeof(T) == 2, "the contraction-major layouts are built for 16-bit elements");
+    constexpr bool A_KMAJOR = LAYOUT == GG_TN, B_KMAJOR = LAYOUT != GG_NT;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     // tile assignment: die x = b % 8 takes a contiguous run of tiles in grouped order (GROUP_M tile rows
@@ -75,40 +96,112 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
     const int ldx_bytes = (int)ldx * (int)sizeof(T), ldw_bytes = (int)ldw * (int)sizeof(T);  // host: both < 2^23
     const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<char*>(reinterpret_cast<const char*>(X)), 0, (int)x_bytes, 0x00020000);
+    // A contraction-major operand is staged slab by slab as it lies in memory: piece i*256+tid -> contraction row
+    // i*8 + tid/32 of the slab, 16-byte piece tid%32 of the tile's 256 columns.  Its descriptor is rebuilt per slab: it
+    // starts at the slab's first row (and the tile's first column) and ends with the operand's last row, so rows past
+    // the end of the contraction are refused by the range check and arrive as zeros, and a slab past the end gets a
+    // descriptor of size zero.  (Columns past the operand's width are only refused in the last row; elsewhere they
+    // read the neighbouring row's first elements, which only ever reach output columns that are not stored.)
+    const int krow = tid >> 5, kpiece = tid & 31;
+    auto kmajor_rsrc = [&](const T* base, long long ld, long long col0, long long ncols, int kslab) {
+        const long long k0 = (long long)kslab * GG_KROWS;
+        long long span = k0 < C ? ((C - k0 - 1) * ld + (ncols - col0)) * (long long)sizeof(T) : 0;  // host: the operand spans < 2^31 bytes
+        if (span < 0) span = 0;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(reinterpret_cast<const char*>(base + k0 * ld + col0)), 0, (int)span, 0x00020000);
+    };
     unsigned a_voff[GG_NLD];
 #pragma unroll
     for (int i = 0; i < GG_NLD; ++i) {
-        const long long m = min(m0 + i * 32 + prow, M - 1);
-        const unsigned row = idx ? (unsigned)idx[m] : (unsigned)m;
-        a_voff[i] = row * (unsigned)ldx_bytes + pcc * 16;  // host guarantees S * ldx * sizeof(T) < 2^32
+        if constexpr (A_KMAJOR) {
+            a_voff[i] = (unsigned)(i * 8 + krow) * (unsigned)ldx_bytes + kpiece * 16;
+        } else {
+            const long long m = min(m0 + i * 32 + prow, M - 1);
+            const unsigned row = idx ? (unsigned)idx[m] : (unsigned)m;
+            a_voff[i] = row * (unsigned)ldx_bytes + pcc * 16;  // host guarantees S * ldx * sizeof(T) < 2^32
+        }
     }
     const int b_rows = min(GG_BN, N - n0);
-    const int w_bytes = (b_rows - 1) * ldw_bytes + cbytes;  // this tile's rows of W, up to the end of the last one
+    const int w_bytes = (b_rows - 1) * ldw_bytes + cbytes;  // (GG_NT) this tile's rows of W, up to the end of the last one
     const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<char*>(reinterpret_cast<const char*>(W + (long long)n0 * ldw)), 0, w_bytes, 0x00020000);
+        const_cast<char*>(reinterpret_cast<const char*>(W + (LAYOUT == GG_NT ? (long long)n0 * ldw : 0ll))), 0,
+        LAYOUT == GG_TN ? (int)w_bytes_all : w_bytes, 0x00020000);
     int b_voff[GG_NLD];
 #pragma unroll
-    for (int i = 0; i < GG_NLD; ++i) b_voff[i] = (i * 32 + prow) * ldw_bytes + pcc * 16;  // at or past w_bytes for rows >= b_rows
+    for (int i = 0; i < GG_NLD; ++i) {
+        if constexpr (LAYOUT == GG_NT) b_voff[i] = (i * 32 + prow) * ldw_bytes + pcc * 16;  // at or past w_bytes for rows >= b_rows
+        else if constexpr (LAYOUT == GG_NN) b_voff[i] = (i * 8 + krow) * ldw_bytes + kpiece * 16;
+        else b_voff[i] = (int)w_bytes_all;  // GG_TN: set per slab from the kept rows' indices (refused until then)
+    }
+    // GG_TN: the rows of B are the kept tokens of the slab, idx[slab * 64 + i*8 + krow]; their indices are fetched one
+    // slab ahead of the rows (tokn holds those of the slab that is requested next), tokens past the end are refused
+    unsigned tokn[LAYOUT == GG_TN ? GG_NLD : 1];
+    auto load_tokens = [&](int kslab) {
+        if constexpr (LAYOUT == GG_TN) {
+#pragma unroll
+            for (int i = 0; i < GG_NLD; ++i) {
+                const long long m = (long long)kslab * GG_KROWS + i * 8 + krow;
+                const long long mc = min(m, (long long)C - 1);
+                const unsigned row = idx ? (unsigned)idx[mc] : (unsigned)mc;
+                tokn[i] = m < C ? row * (unsigned)ldw_bytes + (unsigned)n0 * 2u + (unsigned)kpiece * 16u : w_bytes_all;
+            }
+        }
+    };
+    auto take_tokens = [&]() {
+        if constexpr (LAYOUT == GG_TN) {
+#pragma unroll
+            for (int i = 0; i < GG_NLD; ++i) b_voff[i] = (int)tokn[i];
+        }
+    };
 
     // Global loads take longer than one slab of MFMAs, so two slabs are kept in flight: the pieces of slab s
     // live in register set s & 1 from the moment they are requested (during slab s-2) until they are written
     // to LDS (during slab s-1).
     u32x4 pa[2][GG_NLD], pb[2][GG_NLD];
     // pieces of one slab, all at once (prologue and the ragged last slab: pieces past C are zero in BOTH operands)
-    auto fetch = [&](int kbyte, auto set_tag) {
+    auto fetch = [&](int kslab, auto set_tag) {  // GG_TN: b_voff must hold the slab's rows (take_tokens)
         constexpr int SET = decltype(set_tag)::value;
+        const int kbyte = kslab * GG_KB;
         const bool in_k = kbyte + pcc * 16 + 16 <= cbytes;  // C is a multiple of 16 bytes: a piece is all in or all out
+        const __amdgpu_buffer_rsrc_t a_k = kmajor_rsrc(X, ldx, m0, M, kslab), b_k = kmajor_rsrc(W, ldw, n0, N, kslab);
 #pragma unroll
         for (int i = 0; i < GG_NLD; ++i) {
             pa[SET][i] = u32x4{0u, 0u, 0u, 0u};
             pb[SET][i] = u32x4{0u, 0u, 0u, 0u};
-            if (in_k) {
-                pa[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)a_voff[i], kbyte, 0);
-                pb[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff[i], kbyte, 0);
-            }
+            if constexpr (A_KMAJOR) pa[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(a_k, (int)a_voff[i], 0, 0);
+            else if (in_k) pa[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)a_voff[i], kbyte, 0);
+            if constexpr (LAYOUT == GG_NN) pb[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(b_k, b_voff[i], 0, 0);
+            else if constexpr (LAYOUT == GG_TN) pb[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff[i], 0, 0);
+            else if (in_k) pb[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff[i], kbyte, 0);
         }
     };
-    const int st_off = prow * GG_STRIDE + pcc * 16;
+    // where this thread's pieces go in an operand's LDS region
+    const int st_off = prow * GG_STRIDE + pcc * 16;        // + i * 32 rows: row-major along the contraction
+    const int st_koff = krow * GG_KPITCH + kpiece * 16;    // + i * 8 rows: contraction-major
+    auto a_store = [&](char* stage, int i, const u32x4& v) {
+        if constexpr (A_KMAJOR) *reinterpret_cast<u32x4*>(stage + st_koff + i * 8 * GG_KPITCH) = v;
+        else *reinterpret_cast<u32x4*>(stage + st_off + i * 32 * GG_STRIDE) = v;
+    };
+    auto b_store = [&](char* stage, int i, const u32x4& v) {
+        if constexpr (B_KMAJOR) *reinterpret_cast<u32x4*>(stage + GG_BM * GG_STRIDE + st_koff + i * 8 * GG_KPITCH) = v;
+        else *reinterpret_cast<u32x4*>(stage + GG_BM * GG_STRIDE + st_off + i * 32 * GG_STRIDE) = v;
+    };
+    // fragment (32-row subtile i of the wave's 128 rows, chunk c of the slab) of an operand
+    const int tr_off = (8 * half + ((l32 & 15) >> 2)) * GG_KPITCH + ((l32 >> 4) * 16 + (l32 & 3) * 4) * 2;  // this lane's corner of a 4 x 16 block
+    auto tr_frag = [&](const char* region, int col0, int c) {
+        const char* at = region + tr_off + c * 16 * GG_KPITCH + col0 * 2;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(at));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(at + 4 * GG_KPITCH));
+        const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+        return u32x4{l2.x, l2.y, h2.x, h2.y};
+    };
+    auto a_frag = [&](const char* stage, int i, int c) {
+        if constexpr (A_KMAJOR) return tr_frag(stage, wm * 128 + i * 32, c);
+        else return *reinterpret_cast<const u32x4*>(stage + (wm * 128 + l32) * GG_STRIDE + half * 16 + i * 32 * GG_STRIDE + c * 32);
+    };
+    auto b_frag = [&](const char* stage, int j, int c) {
+        if constexpr (B_KMAJOR) return tr_frag(stage + GG_BM * GG_STRIDE, wn * 128 + j * 32, c);
+        else return *reinterpret_cast<const u32x4*>(stage + GG_BM * GG_STRIDE + (wn * 128 + l32) * GG_STRIDE + half * 16 + j * 32 * GG_STRIDE + c * 32);
+    };
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -123,23 +216,26 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
     //   chunks 0-2: LDS reads of the next chunk's fragments;  after chunk 3: barrier, then the next slab's first chunk
     const int nk = (cbytes + GG_KB - 1) / GG_KB;
     const int nfull = cbytes / GG_KB;  // slabs that lie entirely inside C
-    const int a_lds = (wm * 128 + l32) * GG_STRIDE + half * 16;
-    const int b_lds = GG_BM * GG_STRIDE + (wn * 128 + l32) * GG_STRIDE + half * 16;
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
+    load_tokens(0);
+    take_tokens();
+    load_tokens(1);
     fetch(0, I0{});
 #pragma unroll
     for (int i = 0; i < GG_NLD; ++i) {
-        *reinterpret_cast<u32x4*>(smem + st_off + i * 32 * GG_STRIDE) = pa[0][i];
-        *reinterpret_cast<u32x4*>(smem + GG_BM * GG_STRIDE + st_off + i * 32 * GG_STRIDE) = pb[0][i];
+        a_store(smem, i, pa[0][i]);
+        b_store(smem, i, pb[0][i]);
     }
-    fetch(GG_KB, I1{});  // slab 1 (all zero if there is none)
+    take_tokens();
+    load_tokens(2);
+    fetch(1, I1{});  // slab 1 (all zero if there is none)
     __syncthreads();
     u32x4 fa[4], fb[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        fa[i] = *reinterpret_cast<const u32x4*>(smem + a_lds + i * 32 * GG_STRIDE);
-        fb[i] = *reinterpret_cast<const u32x4*>(smem + b_lds + i * 32 * GG_STRIDE);
+        fa[i] = a_frag(smem, i, 0);
+        fb[i] = b_frag(smem, i, 0);
     }
     // One slab kt of the contraction, kt & 1 == PAR.  It always moves set PAR^1 (slab kt+1) to the other LDS
     // stage and always requests slab kt+2 into set PAR.  When slab kt+1 does not exist the writes land in a
@@ -153,10 +249,13 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
         char* nxt = smem + (PAR ^ 1) * GG_STAGE;
         const int kbyte = (kt + 2) * GG_KB;
         const bool live = kt + 2 < nfull;
-        const __amdgpu_buffer_rsrc_t a_req = __builtin_amdgcn_make_buffer_rsrc(
+        const __amdgpu_buffer_rsrc_t a_req = A_KMAJOR ? kmajor_rsrc(X, ldx, m0, M, kt + 2) : __builtin_amdgcn_make_buffer_rsrc(
             const_cast<char*>(reinterpret_cast<const char*>(X)), 0, live ? (int)x_bytes : 0, 0x00020000);
-        const __amdgpu_buffer_rsrc_t b_req = __builtin_amdgcn_make_buffer_rsrc(
+        const __amdgpu_buffer_rsrc_t b_req = LAYOUT == GG_NN ? kmajor_rsrc(W, ldw, n0, N, kt + 2) : LAYOUT == GG_TN ? b_rsrc : __builtin_amdgcn_make_buffer_rsrc(
             const_cast<char*>(reinterpret_cast<const char*>(W + (long long)n0 * ldw)), 0, live ? w_bytes : 0, 0x00020000);
+        const int a_soff = A_KMAJOR ? 0 : kbyte, b_soff = B_KMAJOR ? 0 : kbyte;
+        take_tokens();         // GG_TN: the rows of slab kt+2, fetched during the slab before
+        load_tokens(kt + 3);
 #pragma unroll
         for (int c = 0; c < GG_NCH; ++c) {
             u32x4 nb[4];
@@ -171,18 +270,18 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
                     // back to back by all four waves they would outrun the vector-memory and LDS pipes
                     const int g = c * 16 + q, slot = g / 3;
                     if (g % 3 == 0 && slot < 16) {  // request piece `slot` of slab kt+2: A pieces first, then B pieces
-                        if (slot < 8) pa[PAR][slot] = __builtin_amdgcn_raw_buffer_load_b128(a_req, (int)a_voff[slot], kbyte, 0);
-                        else pb[PAR][slot - 8] = __builtin_amdgcn_raw_buffer_load_b128(b_req, b_voff[slot - 8], kbyte, 0);
+                        if (slot < 8) pa[PAR][slot] = __builtin_amdgcn_raw_buffer_load_b128(a_req, (int)a_voff[slot], a_soff, 0);
+                        else pb[PAR][slot - 8] = __builtin_amdgcn_raw_buffer_load_b128(b_req, b_voff[slot - 8], b_soff, 0);
                     }
                     if (g % 3 == 1 && slot < 16) {  // move piece `slot` of slab kt+1 (requested during the previous slab) to LDS
-                        if (slot < 8) *reinterpret_cast<u32x4*>(nxt + st_off + slot * 32 * GG_STRIDE) = pa[PAR ^ 1][slot];
-                        else *reinterpret_cast<u32x4*>(nxt + GG_BM * GG_STRIDE + st_off + (slot - 8) * 32 * GG_STRIDE) = pb[PAR ^ 1][slot - 8];
+                        if (slot < 8) a_store(nxt, slot, pa[PAR ^ 1][slot]);
+                        else b_store(nxt, slot - 8, pb[PAR ^ 1][slot - 8]);
                     }
                     if (c < GG_NCH - 1) {
                         // fragments of the next chunk: row i of A is done after its fourth MFMA and is refilled in
                         // place; the B fragments are live to the end of the chunk, so they go to a second set
-                        if (j == 3) fa[i] = *reinterpret_cast<const u32x4*>(cur + a_lds + i * 32 * GG_STRIDE + (c + 1) * 32);
-                        if (i == 2) nb[j] = *reinterpret_cast<const u32x4*>(cur + b_lds + j * 32 * GG_STRIDE + (c + 1) * 32);
+                        if (j == 3) fa[i] = a_frag(cur, i, c + 1);
+                        if (i == 2) nb[j] = b_frag(cur, j, c + 1);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -195,17 +294,17 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            fa[i] = *reinterpret_cast<const u32x4*>(nxt + a_lds + i * 32 * GG_STRIDE);
-            fb[i] = *reinterpret_cast<const u32x4*>(nxt + b_lds + i * 32 * GG_STRIDE);
+            fa[i] = a_frag(nxt, i, 0);
+            fb[i] = b_frag(nxt, i, 0);
         }
     };
     // the ragged last slab (if any) is slab nfull; it must be fetched with zero fill once its register set is free
     int kt = 0;
     for (; kt + 1 < nk; kt += 2) {
         slab(kt, I0{});
-        if (kt + 2 == nfull && nfull < nk) fetch((kt + 2) * GG_KB, I0{});
+        if (!A_KMAJOR && kt + 2 == nfull && nfull < nk) fetch(kt + 2, I0{});  // (never GG_TN: its b_voff runs ahead, and rows past the end are refused anyway)
         slab(kt + 1, I1{});
-        if (kt + 3 == nfull && nfull < nk) fetch((kt + 3) * GG_KB, I1{});
+        if (!A_KMAJOR && kt + 3 == nfull && nfull < nk) fetch(kt + 3, I1{});
     }
     if (kt < nk) slab(kt, I0{});
 
@@ -390,23 +489,24 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
     }
 }
 
-template <typename T, bool ADD>
+template <typename T, bool ADD, int LAYOUT = GG_NT>
 static int launch_gg_t(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W, long long ldw,
-                       const void* bias, void* Y, long long ldy, int C, int N, const int* oidx, long long out_rows, hipStream_t st) {
-    const unsigned x_bytes = (unsigned)(((S - 1) * ldx + C) * (long long)sizeof(T));  // host checked: fits 32 bits
+                       const void* bias, void* Y, long long ldy, int C, int N, const int* oidx, long long out_rows, hipStream_t st,
+                       unsigned w_bytes_all = 0) {
+    const unsigned x_bytes = (unsigned)(((S - 1) * ldx + (LAYOUT == GG_TN ? M : (long long)C)) * (long long)sizeof(T));  // host checked: fits 32 bits
     const unsigned r_bytes = ADD ? (unsigned)(((out_rows - 1) * ldy + N) * (long long)sizeof(T)) : 0u;  // likewise
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_gemm_kernel<T, ADD>),
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_gemm_kernel<T, ADD, LAYOUT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, GG_LDS);
     });
     if (attr_err != hipSuccess) return (int)attr_err;
     const int tiles_m = (int)((M + GG_BM - 1) / GG_BM), tiles_n = (N + GG_BN - 1) / GG_BN;
     const int per_xcd = (tiles_m * tiles_n + NUM_XCD - 1) / NUM_XCD;
-    hipLaunchKernelGGL((gather_gemm_kernel<T, ADD>), dim3((unsigned)(per_xcd * NUM_XCD)), dim3(GG_THREADS), GG_LDS, st,
+    hipLaunchKernelGGL((gather_gemm_kernel<T, ADD, LAYOUT>), dim3((unsigned)(per_xcd * NUM_XCD)), dim3(GG_THREADS), GG_LDS, st,
                        static_cast<const T*>(X), ldx, idx, M, static_cast<const T*>(W), ldw, static_cast<const T*>(bias),
-                       static_cast<T*>(Y), ldy, C, N, tiles_m, tiles_n, x_bytes, oidx, out_rows, r_bytes);
+                       static_cast<T*>(Y), ldy, C, N, tiles_m, tiles_n, x_bytes, oidx, out_rows, r_bytes, w_bytes_all);
     return (int)hipGetLastError();
 }
 
@@ -423,6 +523,23 @@ int launch_gather_gemm_add(const void* X, long long S, long long ldx, const int*
     if (M == 0) return 0;
     if (dt == LEMO_BF16) return launch_gg_t<bf16_t, true>(X, S, ldx, idx, M, W, ldw, bias, R, ldr, C, N, oidx, out_rows, st);
     return launch_gg_t<float, true>(X, S, ldx, idx, M, W, ldw, bias, R, ldr, C, N, oidx, out_rows, st);
+}
+
+// Input gradient of Y = X[idx] W^T:  dX[oidx[m], c] += sum_n dY[m, n] W[n, c], W as stored ([N, C], contraction-major
+// for this product).  bf16.  dY [M, N] compact rows; dX [out_rows, C].
+int launch_gather_gemm_dx(const void* dY, long long ldy, long long M, const void* W, long long ldw, void* dX, long long lddx, long long out_rows,
+                          const int* oidx, int C, int N, hipStream_t st) {
+    if (M == 0) return 0;
+    return launch_gg_t<bf16_t, true, GG_NN>(dY, M, ldy, nullptr, M, W, ldw, nullptr, dX, lddx, /*contraction*/ N, /*columns*/ C, oidx, out_rows, st);
+}
+
+// Weight gradient dW[n, c] = sum_m dY[m, n] X[idx[m], c], both operands read as they are stored (contraction-major),
+// the kept rows of X picked inside the B-tile load.  bf16.
+int launch_gather_gemm_dw_direct(const void* dY, long long ldy, const void* X, long long S, long long ldx, const int* idx, long long M, void* dW,
+                                 long long lddw, int C, int N, hipStream_t st) {
+    const unsigned x_span = (unsigned)(((S - 1) * ldx + C) * 2);  // host checked: fits 32 bits
+    return launch_gg_t<bf16_t, false, GG_TN>(dY, M, ldy, idx, /*output rows*/ N, X, ldx, nullptr, dW, lddw, /*contraction*/ (int)M, /*columns*/ C, nullptr, 0, st,
+                                             x_span);
 }
 
 }  // namespace lemo

@@ -392,10 +392,37 @@ int lemo_gather_gemm_add(const void* X, int64_t S, int64_t ldx, const int32_t* k
                ? LEMO_OK : LEMO_ERR_HIP;
 }
 
+int lemo_gather_gemm_dx(const void* dY, int64_t ldy, int64_t M, const void* W, int64_t ldw, void* dX, int64_t lddx, int64_t S_out,
+                        const int32_t* out_idx, int32_t C, int32_t N, lemo_dtype_t dt, void* stream) {
+    if (!valid_dtype(dt)) return LEMO_ERR_DTYPE;
+    if (M == 0) return LEMO_OK;  // nothing to add
+    if (!dY || !W || !dX) return LEMO_ERR_NULL;
+    if (S_out <= 0 || M < 0 || C <= 0 || N <= 0 || ldy < N || ldw < C || lddx < C) return LEMO_ERR_SHAPE;
+    if (M > S_out || M >= (int64_t)1 << 31 || S_out >= (int64_t)1 << 31) return LEMO_ERR_SHAPE;
+    if (dt != LEMO_BF16) return LEMO_ERR_UNSUPPORTED;  // fp32: lemo_gather_gemm_add with the transposed weight
+    if (C % 8 || N % 8) return LEMO_ERR_UNSUPPORTED;
+    if (!aligned16(dY) || !aligned16(W) || ldy % 8 || ldw % 8) return LEMO_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(dX) % 2 || (out_idx && (reinterpret_cast<uintptr_t>(out_idx) & 3u))) return LEMO_ERR_ALIGN;
+    if (ldy * 2 >= (1 << 23) || ldw * 2 >= (1 << 23) || lddx * 2 >= (1 << 23)) return LEMO_ERR_UNSUPPORTED;  // row pitches below 8 MiB
+    if (((M - 1) * ldy + N) * 2 >= ((int64_t)1 << 32)) return LEMO_ERR_UNSUPPORTED;               // dY is addressed with 32-bit offsets
+    if (((int64_t)(N - 1) * ldw + C) * 2 >= ((int64_t)1 << 31)) return LEMO_ERR_UNSUPPORTED;     // W: signed 32-bit spans
+    if (((S_out - 1) * lddx + C) * 2 >= ((int64_t)1 << 32) - 16) return LEMO_ERR_UNSUPPORTED;     // so is dX
+    const int64_t tiles = ((M + 255) / 256) * (((int64_t)C + 255) / 256);
+    if (tiles >= (int64_t)1 << 28) return LEMO_ERR_UNSUPPORTED;
+    return hip_rc(launch_gather_gemm_dx(dY, ldy, M, W, ldw, dX, lddx, S_out, out_idx, C, N, static_cast<hipStream_t>(stream)));
+}
+
+// bf16 takes the kernel that reads both operands as they are stored when their spans fit its 32-bit offsets
+static bool dw_direct(int64_t ldy, int64_t S, int64_t ldx, int64_t M, int32_t C, int32_t N, lemo_dtype_t dt) {
+    return dt == LEMO_BF16 && ldy * 2 < (1 << 23) && ldx * 2 < (1 << 23) && ((M - 1) * ldy + N) * 2 < ((int64_t)1 << 31) &&
+           ((S - 1) * ldx + C) * 2 < ((int64_t)1 << 32) - 16;
+}
+
 int lemo_gather_gemm_dw_workspace_bytes(int64_t M, int32_t C, int32_t N, lemo_dtype_t dt, size_t* bytes) {
     if (!bytes) return LEMO_ERR_NULL;
     if (!valid_dtype(dt)) return LEMO_ERR_DTYPE;
     if (M < 0 || M >= (int64_t)1 << 31 || C <= 0 || N <= 0) return LEMO_ERR_SHAPE;
+    if (dt == LEMO_BF16) { *bytes = 0; return LEMO_OK; }  // both operands are read where they lie
     const size_t Mpad = (size_t)((M + 63) / 64) * 64, esz = dt == LEMO_BF16 ? 2 : 4;
     *bytes = round_up((size_t)N * Mpad * esz, 256) + round_up((size_t)C * Mpad * esz, 256);
     if (*bytes == 0) *bytes = 256;
@@ -405,24 +432,30 @@ int lemo_gather_gemm_dw_workspace_bytes(int64_t M, int32_t C, int32_t N, lemo_dt
 int lemo_gather_gemm_dw(const void* dY, int64_t ldy, const void* X, int64_t S, int64_t ldx, const int32_t* kept_idx, int64_t M, void* dW,
                         int64_t lddw, int32_t C, int32_t N, lemo_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
     if (!valid_dtype(dt)) return LEMO_ERR_DTYPE;
-    if (!dW || !workspace || (M > 0 && (!dY || !X))) return LEMO_ERR_NULL;
+    if (!dW || (M > 0 && (!dY || !X))) return LEMO_ERR_NULL;
     if (S <= 0 || M < 0 || C <= 0 || N <= 0 || ldy < N || ldx < C || lddw < C) return LEMO_ERR_SHAPE;
     if ((!kept_idx && M > S) || M >= (int64_t)1 << 31 || S >= (int64_t)1 << 31) return LEMO_ERR_SHAPE;
     const int e16 = elems_per_16B(dt);
     if (C % e16 || N % e16) return LEMO_ERR_UNSUPPORTED;
     if ((M > 0 && (!aligned16(dY) || !aligned16(X))) || ldy % e16 || ldx % e16) return LEMO_ERR_ALIGN;
-    if (reinterpret_cast<uintptr_t>(dW) % (dt == LEMO_BF16 ? 2 : 4) || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return LEMO_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(dW) % (dt == LEMO_BF16 ? 2 : 4)) return LEMO_ERR_ALIGN;
     if (kept_idx && (reinterpret_cast<uintptr_t>(kept_idx) & 3u)) return LEMO_ERR_ALIGN;
-    size_t need = 0;
-    lemo_gather_gemm_dw_workspace_bytes(M, C, N, dt, &need);
+    if (M > 0 && dw_direct(ldy, S, ldx, M, C, N, dt)) {  // both operands read where they lie: no workspace
+        const int64_t tiles = (((int64_t)N + 255) / 256) * (((int64_t)C + 255) / 256);
+        if (tiles >= (int64_t)1 << 28) return LEMO_ERR_UNSUPPORTED;
+        return hip_rc(launch_gather_gemm_dw_direct(dY, ldy, X, S, ldx, kept_idx, M, dW, lddw, C, N, static_cast<hipStream_t>(stream)));
+    }
+    if (M == 0) return hip_rc(launch_zero_matrix(dW, lddw, C, N, dt, static_cast<hipStream_t>(stream)));  // an empty sum: dW = 0
+    if (dt == LEMO_BF16) return LEMO_ERR_UNSUPPORTED;  // operands beyond the 32-bit offsets of the kernel
+    if (!workspace) return LEMO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return LEMO_ERR_ALIGN;
+    const size_t Mp = (size_t)((M + 63) / 64) * 64, es = dt == LEMO_BF16 ? 2 : 4;
+    const size_t need = round_up((size_t)N * Mp * es, 256) + round_up((size_t)C * Mp * es, 256);  // transposed copies of both operands
     if (workspace_bytes < need) return LEMO_ERR_WORKSPACE;
     const int64_t esz = dt == LEMO_BF16 ? 2 : 4, Mpad = (M + 63) / 64 * 64;
     if (Mpad * esz >= (1 << 23) || (int64_t)N * Mpad * esz >= ((int64_t)1 << 32)) return LEMO_ERR_UNSUPPORTED;  // limits of the GEMM on the transposed operands
     const int64_t tiles = (((int64_t)N + 255) / 256) * (((int64_t)C + 255) / 256);
     if (tiles >= (int64_t)1 << 28) return LEMO_ERR_UNSUPPORTED;
-    if (M == 0) {  // an empty sum: dW = 0
-        return hip_rc(launch_zero_matrix(dW, lddw, C, N, dt, static_cast<hipStream_t>(stream)));
-    }
     return hip_rc(launch_gather_gemm_dw(dY, ldy, X, S, ldx, kept_idx, M, dW, lddw, C, N, dt, workspace, static_cast<hipStream_t>(stream)));
 }
 

@@ -147,6 +147,10 @@ int launch_scatter(const void* G, long long ldg, const int* idx, long long M, vo
 int launch_gather_gemm(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W,
                        long long ldw, const void* bias, void* Y, long long ldy, int C, int N, lemo_dtype_t dt,
                        hipStream_t st);
+int launch_gather_gemm_dx(const void* dY, long long ldy, long long M, const void* W, long long ldw, void* dX, long long lddx, long long out_rows,
+                          const int* oidx, int C, int N, hipStream_t st);
+int launch_gather_gemm_dw_direct(const void* dY, long long ldy, const void* X, long long S, long long ldx, const int* idx, long long M, void* dW,
+                                 long long lddw, int C, int N, hipStream_t st);
 int launch_gather_gemm_add(const void* X, long long S, long long ldx, const int* idx, long long M, const void* W,
                            long long ldw, const void* bias, void* R, long long ldr, long long out_rows, const int* oidx,
                            int C, int N, lemo_dtype_t dt, hipStream_t st);

@@ -25,7 +25,7 @@ EXPORTS = ("lemo_strerror", "lemo_keep_k", "lemo_kept_count", "lemo_score_worksp
            "lemo_select_topk", "lemo_head_mean_select_topk", "lemo_launch_floor", "lemo_probe_sweep_issue_mix", "lemo_gather_gemm", "lemo_gather_gemm_add", "lemo_scatter_grad",
            "lemo_score_blocks_workspace_bytes", "lemo_score_blocks", "lemo_threshold_init", "lemo_select_threshold",
            "lemo_kept_attention_workspace_bytes", "lemo_kept_attention",
-           "lemo_gather_gemm_dw_workspace_bytes", "lemo_gather_gemm_dw")
+           "lemo_gather_gemm_dw_workspace_bytes", "lemo_gather_gemm_dw", "lemo_gather_gemm_dx")
 
 
 class LemoError(RuntimeError):
@@ -83,6 +83,8 @@ def _load() -> ctypes.CDLL:
     lib.lemo_launch_floor.argtypes = [vp]
     lib.lemo_probe_sweep_issue_mix.restype = ctypes.c_int
     lib.lemo_probe_sweep_issue_mix.argtypes = [i32, vp, ctypes.POINTER(i32), vp]
+    lib.lemo_gather_gemm_dx.restype = ctypes.c_int
+    lib.lemo_gather_gemm_dx.argtypes = [vp, i64, i64, vp, i64, vp, i64, i64, vp, i32, i32, ctypes.c_int, vp]
     lib.lemo_select_topk.restype = ctypes.c_int
     lib.lemo_select_topk.argtypes = [vp, i64, i32, i32, vp, vp]
     lib.lemo_gather_gemm.restype = ctypes.c_int
@@ -458,6 +460,21 @@ def lemo_kept_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, kept_
     return O
 
 
+def lemo_gather_gemm_dx(dY: torch.Tensor, W: torch.Tensor, dX: torch.Tensor, out_idx: Optional[torch.Tensor]) -> torch.Tensor:
+    """In place: dX[out_idx[m],:] += dY[m,:] @ W.  dY [M,N], W [N,C] (as stored for the forward), dX [S_out,C]."""
+    _dev(dY, W, dX, out_idx)
+    if dY.dim() != 2 or W.dim() != 2 or dX.dim() != 2 or _dt(dY) != _dt(W) or _dt(dX) != _dt(W) or W.stride(1) != 1 or dX.stride(1) != 1 \
+            or dY.shape[1] != W.shape[0] or dX.shape[1] != W.shape[1] or (dY.shape[0] > 0 and dY.stride(1) != 1):
+        raise ValueError("dY must be [M,N], W [N,C], dX [S_out,C], same dtype, rows contiguous")
+    M, N = dY.shape
+    C = W.shape[1]
+    if out_idx is not None and (out_idx.dtype != torch.int32 or out_idx.dim() != 1 or out_idx.numel() != M or not out_idx.is_contiguous()):
+        raise ValueError("out_idx must be contiguous int32 [M]")
+    _check(_lib.lemo_gather_gemm_dx(_ptr(dY), dY.stride(0) if M > 0 else N, M, _ptr(W), W.stride(0), _ptr(dX), dX.stride(0), dX.shape[0],
+                                    _ptr(out_idx), C, N, _dt(W), _stream()), "lemo_gather_gemm_dx")
+    return dX
+
+
 def lemo_gather_gemm_dw_workspace_bytes(M: int, C: int, N: int, dtype: int) -> int:
     n = ctypes.c_size_t(0)
     _check(_lib.lemo_gather_gemm_dw_workspace_bytes(M, C, N, dtype, ctypes.byref(n)), "lemo_gather_gemm_dw_workspace_bytes")
@@ -479,9 +496,11 @@ def lemo_gather_gemm_dw(dY: torch.Tensor, X: torch.Tensor, kept_idx: Optional[to
     elif dW.dtype != X.dtype or tuple(dW.shape) != (N, C) or dW.stride(1) != 1:
         raise ValueError("dW must be [N,C] of the input dtype, rows contiguous")
     if workspace is None:
-        workspace = torch.empty(lemo_gather_gemm_dw_workspace_bytes(M, C, N, _dt(X)), dtype=torch.uint8, device=X.device)
+        need = lemo_gather_gemm_dw_workspace_bytes(M, C, N, _dt(X))
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device) if need else None
     _check(_lib.lemo_gather_gemm_dw(_ptr(dY), dY.stride(0) if M > 0 else N, _ptr(X), S, X.stride(0), _ptr(kept_idx), M, _ptr(dW),
-                                    dW.stride(0), C, N, _dt(X), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                    dW.stride(0), C, N, _dt(X), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size() if workspace is not None else 0,
                                     _stream()), "lemo_gather_gemm_dw")
     return dW
 

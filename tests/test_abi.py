@@ -169,12 +169,22 @@ def test_block_score_threshold_attention_and_gradient_argument_errors(lib):
 
     lib.lemo_gather_gemm_dw.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp, i64, i32, i32, ctypes.c_int, vp, ctypes.c_size_t, vp]
     lib.lemo_gather_gemm_dw_workspace_bytes.argtypes = [i64, i32, i32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
-    assert lib.lemo_gather_gemm_dw_workspace_bytes(100, 64, 32, 1, ctypes.byref(n)) == 0 and n.value == (32 + 64) * 128 * 2
+    assert lib.lemo_gather_gemm_dw_workspace_bytes(100, 64, 32, 1, ctypes.byref(n)) == 0 and n.value == 0   # bf16: operands read in place
+    assert lib.lemo_gather_gemm_dw_workspace_bytes(100, 64, 32, 0, ctypes.byref(n)) == 0 and n.value == (32 + 64) * 128 * 4
     dw = _caller(lib.lemo_gather_gemm_dw, ("dY", "ldy", "X", "S", "ldx", "idx", "M", "dW", "lddw", "C", "N", "dt", "ws", "wsb", "st"),
-                 dict(dY=A, ldy=32, X=B, S=100, ldx=64, idx=C_, M=10, dW=D, lddw=64, C=64, N=32, dt=1, ws=E, wsb=1 << 20, st=None))
+                 dict(dY=A, ldy=32, X=B, S=100, ldx=64, idx=C_, M=10, dW=D, lddw=64, C=64, N=32, dt=0, ws=E, wsb=1 << 20, st=None))
     assert dw(dW=None) == -1 and dw(dY=None) == -1 and dw(ws=None) == -1
     assert dw(ldy=16) == -2 and dw(idx=None, M=200) == -2
-    assert dw(N=36, ldy=40) == -6 and dw(ldx=68) == -5 and dw(wsb=64) == -4 and dw(dt=2) == -3
+    assert dw(N=34, ldy=40) == -6 and dw(ldx=66) == -5 and dw(wsb=64) == -4 and dw(dt=2) == -3
+    assert dw(dt=1, N=36, ldy=40) == -6 and dw(dt=1, ldx=68) == -5 and dw(dt=1, dW=None) == -1
+    lib.lemo_gather_gemm_dx.argtypes = [vp, i64, i64, vp, i64, vp, i64, i64, vp, i32, i32, ctypes.c_int, vp]
+    dx = _caller(lib.lemo_gather_gemm_dx, ("dY", "ldy", "M", "W", "ldw", "dX", "lddx", "So", "oidx", "C", "N", "dt", "st"),
+                 dict(dY=A, ldy=32, M=10, W=B, ldw=64, dX=C_, lddx=64, So=100, oidx=D, C=64, N=32, dt=1, st=None))
+    assert dx(dY=None) == -1 and dx(W=None) == -1 and dx(dX=None) == -1
+    assert dx(ldy=16) == -2 and dx(ldw=32) == -2 and dx(M=101) == -2 and dx(So=0) == -2
+    assert dx(dt=0) == -6 and dx(dt=4) == -3 and dx(C=60, ldw=64) == -6 and dx(N=36, ldy=40) == -6
+    assert dx(ldw=68) == -5 and dx(oidx=D + 2) == -5
+    assert dx(M=0) == 0
 
 
 def test_static_scratch_and_fused_select_argument_errors(lib):

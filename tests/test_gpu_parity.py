@@ -693,6 +693,83 @@ def test_gather_gemm_add_output_projection_shape_sampled(lemo):
     assert (g == o).mean() > 0.98
 
 
+# ------------------------------------------------------------------------------------ input gradient of the selective-load GEMM
+
+@pytest.mark.parametrize("S,C,N,M,pad", [(300, 64, 40, 130, 0), (1000, 256, 304, 517, 8), (513, 1000, 264, 513, 0), (64, 8, 8, 1, 0),
+                                         (700, 512, 4096, 300, 0), (900, 520, 72, 900, 16), (400, 264, 1000, 257, 0)])
+def test_gather_gemm_dx_bf16(lemo, S, C, N, M, pad):
+    """dX[idx[m],:] += dY[m,:] W with W as stored [N,C]: against the oracle's fused GEMM + in-place add fed the transposed
+    weight (a host-side copy of the same bits); rows that idx does not name keep their bits; padded leading dimensions."""
+    say(f"[gemm dX] bf16 S={S} C={C} N={N} M={M} pad={pad}")
+    rng = np.random.default_rng(S + C + N + 3)
+    dY = torch.from_numpy((rng.standard_normal((M, N)) * 0.5).astype(np.float32)).to(torch.bfloat16)
+    W = torch.from_numpy((rng.standard_normal((N, C)) * 0.05).astype(np.float32)).to(torch.bfloat16)
+    R = torch.from_numpy(rng.standard_normal((S, C)).astype(np.float32)).to(torch.bfloat16)
+    idx = rng.permutation(S)[:M].astype(np.int32)
+    Wbig = torch.full((N, C + pad), 3.0, dtype=torch.bfloat16, device="cuda")
+    Wbig[:, :C] = W.cuda()
+    Rbig = torch.full((S, C + pad), 7.0, dtype=torch.bfloat16, device="cuda")
+    Rd = Rbig[:, :C]
+    Rd.copy_(R)
+    lemo.lemo_gather_gemm_dx(dY.cuda(), Wbig[:, :C], Rd, torch.from_numpy(idx).cuda())
+    torch.cuda.synchronize()
+    assert (Rbig[:, C:] == 7.0).all()
+    before = wl.as_numpy(R)
+    Wt = np.ascontiguousarray(wl.as_numpy(W).T)  # [C,N]: the same bits, the other way round
+    want = oracle.gather_gemm_add(wl.as_numpy(dY), None, Wt, before.copy(), idx)
+    assert_gemm_add_close(wl.to_bf16_bits(Rd.contiguous()), want, before, wl.as_numpy(dY), Wt, idx)
+
+
+def test_gather_gemm_dx_exact_and_edge_cases(lemo):
+    say("[gemm dX] exact cases")
+    rng = np.random.default_rng(31)
+    S, C, N, M = 300, 96, 160, 120
+    dY = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32)
+    W = (rng.integers(-8, 9, (N, C)) / 8.0).astype(np.float32)
+    dX = (rng.integers(-64, 65, (S, C)) / 4.0).astype(np.float32)
+    idx = np.sort(rng.permutation(S)[:M]).astype(np.int32)
+    Wb = torch.from_numpy(W).to(torch.bfloat16)
+    for oi in (idx, None):
+        want = oracle.gather_gemm_add(bf16(dY), None, np.ascontiguousarray(wl.as_numpy(Wb).T), bf16(dX).copy(), oi)
+        got = lemo.lemo_gather_gemm_dx(torch.from_numpy(dY).to(torch.bfloat16).cuda(), Wb.cuda(), torch.from_numpy(dX).to(torch.bfloat16).cuda(),
+                                       None if oi is None else torch.from_numpy(oi).cuda())
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(wl.to_bf16_bits(got), want)   # dyadic grid: every partial sum is exact
+    # the same bits as the transposed-weight form of the in-place-add GEMM on non-dyadic data is NOT promised (other
+    # summation order); but it equals that form on the dyadic grid above.  No kept rows: nothing happens.
+    D0 = torch.from_numpy(dX).to(torch.bfloat16).cuda()
+    same = lemo.lemo_gather_gemm_dx(torch.empty((0, N), dtype=torch.bfloat16, device="cuda"), Wb.cuda(), D0.clone(), torch.empty(0, dtype=torch.int32, device="cuda"))
+    assert torch.equal(same, D0)
+    with pytest.raises(lemo.LemoError) as e:  # fp32 is served by lemo_gather_gemm_add with the transposed weight
+        lemo.lemo_gather_gemm_dx(torch.zeros((M, N), device="cuda"), torch.zeros((N, C), device="cuda"), torch.zeros((S, C), device="cuda"), None)
+    assert e.value.code == -6
+
+
+def test_gather_gemm_dx_bench_shape_sampled(lemo):
+    """The 32K layer's consumer GEMM backward with respect to the input: M = 9856 kept rows, N = 11008, C = 4096, added into
+    dX [32768, 4096]; sampled kept rows (all columns) against the oracle, every other row untouched."""
+    cfg = wl.CONFIGS["C5"]
+    say("[gemm dX] C5 shape: inputs")
+    rng = np.random.default_rng(cfg.seed + 500)
+    dY = torch.from_numpy(rng.standard_normal((cfg.M, cfg.N), dtype=np.float32) * np.float32(0.05)).to(torch.bfloat16)
+    W = torch.from_numpy(rng.standard_normal((cfg.N, cfg.C), dtype=np.float32) * np.float32(0.02)).to(torch.bfloat16)
+    R = torch.from_numpy(rng.standard_normal((cfg.S, cfg.C), dtype=np.float32)).to(torch.bfloat16)
+    idx = oracle.select_topk(rng.random(cfg.S).astype(np.float32), cfg.L, cfg.k)
+    say("[gemm dX] C5 shape: GPU")
+    Rd = R.cuda()
+    lemo.lemo_gather_gemm_dx(dY.cuda(), W.cuda(), Rd, torch.from_numpy(idx).cuda())
+    torch.cuda.synchronize()
+    got, before = wl.to_bf16_bits(Rd), wl.as_numpy(R)
+    mask = np.ones(cfg.S, dtype=bool); mask[idx] = False
+    np.testing.assert_array_equal(got[mask], before[mask])
+    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, cfg.M - 257, cfg.M - 129, cfg.M - 1], rng.integers(0, cfg.M, 24)]))
+    say(f"[gemm dX] C5 shape: oracle on {len(rows)} rows")
+    Wt = np.ascontiguousarray(wl.as_numpy(W).T)
+    sub = before[idx[rows]].copy()
+    want = oracle.gather_gemm_add(wl.as_numpy(dY), rows.astype(np.int32), Wt, sub, None)
+    assert_gemm_add_close(got[idx[rows]], want, before[idx[rows]], wl.as_numpy(dY)[rows], Wt, np.arange(len(rows)))
+
+
 # ------------------------------------------------------------------------------------ weight gradient of the selective-load GEMM
 
 @pytest.mark.parametrize("S,C,N,M", [(300, 64, 40, 130), (1000, 256, 304, 517), (513, 1000, 264, 513), (64, 8, 8, 1), (700, 512, 4096, 300)])
