@@ -153,7 +153,7 @@ def cpu_baseline(cfg, lay, wl, steps_note=""):
 def measure_fused_output_projection(cfg, lemo, ev, stream, kept, reps=10):
     """Outside the timed step: the attention block's output projection (C -> C) over the M kept rows, added into
     the [S, C] residual stream at the kept positions (Sec. 4.4's in-place add).  Fused = one lemo_gather_gemm_add;
-    unfused = lemo_gather_gemm into a compact [M, C] buffer, then lemo_scatter_grad."""
+    unfused = lemo_gather_gemm into a compact [M, C] buffer, then lemo_scatter_grad.  Timed alternately."""
     import torch
     S, C, M = cfg.S, cfg.C, cfg.M
     dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
@@ -163,22 +163,11 @@ def measure_fused_output_projection(cfg, lemo, ev, stream, kept, reps=10):
     R = torch.randn((S, C), device="cuda", dtype=torch.float32, generator=g).to(dt)
     Y = torch.empty((M, C), device="cuda", dtype=dt)
 
-    def timed(fn):
-        fn()
-        marks = [ev.create() for _ in range(reps + 1)]
-        ev.record(marks[0], stream)
-        for i in range(reps):
-            fn()
-            ev.record(marks[i + 1], stream)
-        torch.cuda.synchronize()
-        return sum(ev.elapsed_ms(marks[i], marks[i + 1]) for i in range(reps)) / reps
-
     def unfused():
         lemo.lemo_gather_gemm(A, None, Wo, Y=Y)
         lemo.lemo_scatter_grad(Y, kept, R)
 
-    t_fused = timed(lambda: lemo.lemo_gather_gemm_add(A, None, Wo, R, kept))
-    t_unfused = timed(unfused)
+    t_fused, t_unfused = timed_alternately(ev, stream, [lambda: lemo.lemo_gather_gemm_add(A, None, Wo, R, kept), unfused], reps)
     flops = 2.0 * M * C * C
     esz = 2 if cfg.dtype == "bf16" else 4
     return {"what": f"output projection {C}->{C} over M={M} kept rows added into the [{S},{C}] residual rows",
@@ -189,27 +178,16 @@ def measure_fused_output_projection(cfg, lemo, ev, stream, kept, reps=10):
 def measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, Y, reps=10):
     """Outside the timed step: what folding the gather into the GEMM's A-tile load saves (Sec. 4.4, selective
     load).  Unfolded = materialise the kept rows (torch.index_select, one read and one
-    write of M x C) and run the same GEMM kernel on the compact copy."""
+    write of M x C) and run the same GEMM kernel on the compact copy.  Timed alternately."""
     import torch
     kept64 = kept.long()
     Xc = torch.empty((cfg.M, cfg.C), dtype=X.dtype, device=X.device)
-
-    def timed(fn):
-        fn()
-        marks = [ev.create() for _ in range(reps + 1)]
-        ev.record(marks[0], stream)
-        for i in range(reps):
-            fn()
-            ev.record(marks[i + 1], stream)
-        torch.cuda.synchronize()
-        return sum(ev.elapsed_ms(marks[i], marks[i + 1]) for i in range(reps)) / reps
 
     def unfolded():
         torch.index_select(X, 0, kept64, out=Xc)
         lemo.lemo_gather_gemm(Xc, None, W, Y=Y)
 
-    t_fold = timed(lambda: lemo.lemo_gather_gemm(X, kept, W, Y=Y))
-    t_unf = timed(unfolded)
+    t_fold, t_unf = timed_alternately(ev, stream, [lambda: lemo.lemo_gather_gemm(X, kept, W, Y=Y), unfolded], reps)
     esz = 2 if cfg.dtype == "bf16" else 4
     return {"what": "consumer GEMM reading the kept rows in place vs torch.index_select into a compact copy + the same GEMM",
             "folded_ms": round(t_fold, 5), "unfolded_ms": round(t_unf, 5), "bytes_saved": 2.0 * cfg.M * cfg.C * esz}
@@ -307,6 +285,22 @@ def timed_calls(ev, stream, fn, reps):
         ev.record(marks[i + 1], stream)
     torch.cuda.synchronize()
     return sum(ev.elapsed_ms(marks[i], marks[i + 1]) for i in range(reps)) / reps
+
+
+def timed_alternately(ev, stream, fns, reps):
+    """Mean milliseconds of each of `fns`, called in turn (a, b, a, b, ...) so that all of them see the same clocks and
+    temperatures; one warm-up round."""
+    import torch
+    for fn in fns:
+        fn()
+    marks = [[ev.create() for _ in range(len(fns) + 1)] for _ in range(reps)]
+    for r in range(reps):
+        ev.record(marks[r][0], stream)
+        for i, fn in enumerate(fns):
+            fn()
+            ev.record(marks[r][i + 1], stream)
+    torch.cuda.synchronize()
+    return [sum(ev.elapsed_ms(marks[r][i], marks[r][i + 1]) for r in range(reps)) / reps for i in range(len(fns))]
 
 
 class LayerRun:

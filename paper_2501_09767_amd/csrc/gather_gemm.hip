@@ -23,7 +23,10 @@ constexpr int GG_CPR = GG_KB / 16;       // 16-byte pieces per row per stage
 constexpr int GG_STAGE = (GG_BM + GG_BN) * GG_STRIDE;
 constexpr int GG_LDS = 2 * GG_STAGE;     // 147456 bytes of the CU's 160 KB
 constexpr int GG_NLD = GG_BM * GG_CPR / GG_THREADS;  // 8 loads per thread per operand per stage
-constexpr int GG_GROUP_M = 4;            // tile rows walked together (keeps a die's 32 tiles to a 4 x 8 patch)
+#ifndef LEMO_GG_GROUP_M
+#define LEMO_GG_GROUP_M 4
+#endif
+constexpr int GG_GROUP_M = LEMO_GG_GROUP_M;  // tile rows walked together (4 keeps a die's 32 tiles to a 4 x 8 patch)
 
 // How the operands lie in memory (an MFMA lane always wants 8 consecutive contraction elements of one operand row):
 //   GG_NT  A rows and B rows run along the contraction (X[idx] [M,C] against an nn.Linear weight [N,C]); 16-byte reads.

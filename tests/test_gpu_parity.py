@@ -1155,14 +1155,23 @@ def test_hot_path_replayed_from_a_hip_graph(lemo):
     Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     dX = torch.empty((S, C), dtype=torch.bfloat16, device="cuda")
 
+    col = torch.empty((H, S), dtype=torch.float32, device="cuda")
+    dg = torch.empty((H, S), dtype=torch.float32, device="cuda")
+    scores2 = torch.empty(S, dtype=torch.float32, device="cuda")
+    scores3 = torch.empty(S, dtype=torch.float32, device="cuda")
+    kept2 = torch.empty(M, dtype=torch.int32, device="cuda")
+
     def path():
-        lemo.lemo_score_segments(Q, K, L, scores=scores, workspace=ws)
+        lemo.lemo_score_segments(Q, K, L, scores=scores, colsum_per_head=col, diag_per_head=dg, workspace=ws)
         lemo.lemo_select_topk(scores, L, k, kept_idx=kept)
+        lemo.lemo_head_mean_select_topk(col, dg, L, k, scores=scores2, kept_idx=kept2)   # the same two steps in one launch
+        lemo.lemo_score_segments_static(Q, K, L, scores3)                                  # the scoring without a workspace
         lemo.lemo_gather_gemm(X, kept, W, Y=Y)
         lemo.lemo_scatter_grad(G, kept, dX, mode=lemo.SCATTER_ZERO_PAD)
 
     def outputs():
         torch.cuda.synchronize()
+        assert torch.equal(scores, scores2) and torch.equal(kept, kept2) and torch.equal(scores, scores3)
         return [t.clone() for t in (scores, kept, Y, dX)]
 
     path()  # eager first: the first call of an entry point sets kernel attributes, which is not a stream operation
@@ -1174,14 +1183,16 @@ def test_hot_path_replayed_from_a_hip_graph(lemo):
         say(f"[graph] replay {rep}")
         Q.copy_(rnd(S, H, d))  # eager work between the replays
         X.copy_(rnd(S, C))
-        for t in (scores, Y, dX):
+        for t in (scores, scores2, scores3, Y, dX):
             t.fill_(7.0)
         kept.fill_(-1)
+        kept2.fill_(-1)
         graph.replay()
         replayed = outputs()
-        for t in (scores, Y, dX):
+        for t in (scores, scores2, scores3, Y, dX):
             t.fill_(5.0)
         kept.fill_(-2)
+        kept2.fill_(-2)
         path()
         eager = outputs()
         for a, b, what in zip(replayed, eager, ("scores", "kept_idx", "Y", "dX")):
