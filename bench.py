@@ -14,7 +14,6 @@ machine in the same run (a library GEMM of the consumer's shape, a 1 GiB device 
 """
 import argparse
 import ctypes
-import glob
 import hashlib
 import json
 import os
@@ -35,16 +34,20 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 # The figures belong to the kernel sources they were measured on: "sources" is sources_digest() at that time, and the
 # bench reports traffic as null when the sources have changed since.
 MEASURED_TRAFFIC_BYTES = {
-    "sources": "unmeasured",
-    "C5:rowstats": 2129783382, "C5:colsum": 2228509924, "C5:head_mean": 8542739, "C5:select": 229023,
-    "C5:gather_gemm": 1732136254, "C5:scatter": 242876184,
+    "sources": "49280715e7660c3a",
+    "C5:rowstats": 2067631584, "C5:colsum": 2112126141, "C5:head_mean_select": 8641736,
+    "C5:gather_gemm": 1687026848, "C5:scatter": 242876436,
 }
 
 
+HOT_PATH_SOURCES = ("lemo_common.hpp", "score.hip", "select.hip", "gather_gemm.hip", "scatter.hip")
+
+
 def sources_digest() -> str:
-    """sha256 over the kernel sources (what the measured traffic figures are tied to)."""
+    """sha256 over the sources of the timed step's kernels (what the measured traffic figures are tied to)."""
     h = hashlib.sha256()
-    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2501_09767_amd", "csrc", "*"))):
+    for name in HOT_PATH_SOURCES:
+        path = os.path.join(ROOT, "paper_2501_09767_amd", "csrc", name)
         h.update(os.path.basename(path).encode())
         with open(path, "rb") as f:
             h.update(f.read())

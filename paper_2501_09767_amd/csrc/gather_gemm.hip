@@ -26,6 +26,9 @@ constexpr int GG_NLD = GG_BM * GG_CPR / GG_THREADS;  // 8 loads per thread per o
 #ifndef LEMO_GG_GROUP_M
 #define LEMO_GG_GROUP_M 4
 #endif
+#ifndef LEMO_GG_EARLY_BARRIER
+#define LEMO_GG_EARLY_BARRIER 1
+#endif
 constexpr int GG_GROUP_M = LEMO_GG_GROUP_M;  // tile rows walked together (4 keeps a die's 32 tiles to a 4 x 8 patch)
 
 // How the operands lie in memory (an MFMA lane always wants 8 consecutive contraction elements of one operand row):
@@ -263,6 +266,16 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
         for (int c = 0; c < GG_NCH; ++c) {
             u32x4 nb[4];
             __builtin_amdgcn_sched_barrier(0);
+#if LEMO_GG_EARLY_BARRIER
+            // The slab's one barrier stands before its LAST chunk: by then this thread's LDS writes of slab kt+1 (the
+            // last one follows MFMA 46 of 64) and its reads of this stage (the last chunk's fragments, read during the
+            // chunk before) have been issued, and the barrier waits for them.  The last chunk's MFMAs then cover the
+            // reads of the next slab's first fragments, which would otherwise stand between the barrier and an MFMA.
+            if (c == GG_NCH - 1) {
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#endif
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -286,20 +299,28 @@ __global__ __launch_bounds__(GG_THREADS, 1) void gather_gemm_kernel(const T* __r
                         if (j == 3) fa[i] = a_frag(cur, i, c + 1);
                         if (i == 2) nb[j] = b_frag(cur, j, c + 1);
                     }
+#if LEMO_GG_EARLY_BARRIER
+                    else {  // behind the barrier: the first fragments of the next slab
+                        if (j == 3) fa[i] = a_frag(nxt, i, 0);
+                        if (i == 2) nb[j] = b_frag(nxt, j, 0);
+                    }
+#endif
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            if (c < GG_NCH - 1) {
+            if (LEMO_GG_EARLY_BARRIER || c < GG_NCH - 1) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) fb[j] = nb[j];
             }
         }
+#if !LEMO_GG_EARLY_BARRIER
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             fa[i] = a_frag(nxt, i, 0);
             fb[i] = b_frag(nxt, i, 0);
         }
+#endif
     };
     // the ragged last slab (if any) is slab nfull; it must be fetched with zero fill once its register set is free
     int kt = 0;
