@@ -420,6 +420,37 @@ def measure_ceilings(cfg, ev, stream, X, W, kept, lemo):
             "sweep_issue_mix_tflops": round(mix_tflops, 1)}
 
 
+def measure_constant_operands(cfg, lemo, ev, stream, run):
+    """The step's three MFMA kernels on operands of all ones, same shapes, same launches, timed in runs of six calls
+    beside the same on the step's own data.  The instruction streams are the same; what differs is how much of the chip's datapath switches, and
+    with it the clock the power management grants.  The gap between the two is what the kernels lose to that, not to
+    their schedule."""
+    import torch
+    Q1, K1 = torch.ones_like(run.Q), torch.ones_like(run.K)
+    X1, W1 = torch.ones_like(run.X), torch.ones_like(run.W)
+    lse2 = torch.empty_like(run.lse2)
+    col, dg = torch.empty_like(run.col), torch.empty_like(run.dg)
+    lemo.lemo_score_rowstats(Q1, K1, flags=run.flags, lse2=lse2)
+    flops_sweep = float(cfg.d) * cfg.H * cfg.S * (cfg.S + 1)
+    flops_gemm = 2.0 * cfg.M * cfg.C * cfg.N
+    res = {"what": "the step's MFMA kernels on all-ones operands of the same shapes, six calls in a row, beside six on the step's data: "
+                   "same instruction streams, less switching, higher granted clock"}
+    pairs = {
+        "rowstats": (lambda: lemo.lemo_score_rowstats(run.Q, run.K, flags=run.flags, lse2=run.lse2),
+                     lambda: lemo.lemo_score_rowstats(Q1, K1, flags=run.flags, lse2=lse2), flops_sweep),
+        "colsum": (lambda: lemo.lemo_score_colsums(run.Q, run.K, cfg.L, run.lse2, flags=run.flags, colsum_per_head=run.col, diag_per_head=run.dg),
+                   lambda: lemo.lemo_score_colsums(Q1, K1, cfg.L, lse2, flags=run.flags, colsum_per_head=col, diag_per_head=dg), flops_sweep),
+        "gather_gemm": (lambda: lemo.lemo_gather_gemm(run.X, run.kept, run.W, Y=run.Y),
+                        lambda: lemo.lemo_gather_gemm(X1, run.kept, W1, Y=run.Y), flops_gemm),
+    }
+    for name, (real, const, flops) in pairs.items():
+        t_real, t_const = timed_calls(ev, stream, real, 6), timed_calls(ev, stream, const, 6)
+        res[name] = {"step_data_ms": round(t_real, 5), "ones_ms": round(t_const, 5),
+                     "ones_tflops": round(flops / t_const * 1e-9, 2), "ones_frac_mfma_peak": round(flops / t_const * 1e-9 / PEAK_BF16_TFLOPS, 4)}
+    lemo.lemo_gather_gemm(run.X, run.kept, run.W, Y=run.Y)  # leave the step's own output behind
+    return res
+
+
 def measure_select(cfg, lemo, ev, stream, col, dg, flags, batch=128):
     """Outside the timed step: head mean + selection as two launches and as one, against the empty-launch floor, and the
     same kernels on `batch` independent score sets in one launch (segments are independent, so a batch is simply a
@@ -541,6 +572,7 @@ def main():
                 report[name]["frac_sweep_issue_mix"] = round(report[name]["tflops"] / ceil["sweep_issue_mix_tflops"], 4)
         if "scatter" in report:
             report["scatter"]["frac_device_copy"] = round(report["scatter"]["gbs"] / ceil["device_copy_gbs"], 4)
+        out["constant_operands"] = measure_constant_operands(cfg, lemo, ev, stream, run)
         out["select"] = measure_select(cfg, lemo, ev, stream, run.col, run.dg, flags)
         out["gather_fold"] = measure_gather_fold(cfg, lemo, ev, stream, X, W, kept, run.Y)
         out["fused_in_place_add"] = measure_fused_output_projection(cfg, lemo, ev, stream, kept)
