@@ -22,9 +22,15 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 
+# Per-file flags.  attention.hip: its 64-queries-per-wave kernel may use the whole register file (one wave per SIMD), and
+# for such a kernel the compiler would otherwise give every MFMA its result in the accumulation registers, with a copy
+# around each use by vector arithmetic; this makes MFMAs write ordinary vector registers.
+FILE_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def _compile(src: str, extra) -> str:
     obj = os.path.join(OBJDIR, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -32,6 +32,9 @@ namespace lemo {
 #ifndef LEMO_AT_NQ
 #define LEMO_AT_NQ 1
 #endif
+#ifndef LEMO_AT_PIPE
+#define LEMO_AT_PIPE 1
+#endif
 constexpr int AT_THREADS = LEMO_AT_THREADS;
 constexpr int AT_NQ = LEMO_AT_NQ;                   // 32-query subtiles per wave
 constexpr int AT_BQ = (AT_THREADS / 64) * 32 * AT_NQ;  // queries per workgroup
@@ -297,6 +300,376 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// head_dim 128: the same computation with 64 queries per wave, one wave per SIMD, the overlap written out.
+//
+// With 32 queries per wave every K and V^T fragment read (16 x 16 bytes per lane and 32-key subtile) feeds one pair of
+// MFMA chains, and at full matrix-core rate that alone is the CU's whole LDS bandwidth.  Two query subtiles per wave
+// halve it, but their 128 accumulator registers leave room for one wave per SIMD only, so matrix and vector work are
+// interleaved by hand.  Stages of keys that need no mask ("hot" stages) run as one branch-free stream: per key subtile
+// four groups of 8 MFMAs, each carrying a share of another tile's exponentials (Q0, Q1: the wave's two query subtiles):
+//
+//   G1  S0 = K Q0^T                    | exponentials 8..15 of the pending tile (previous subtile, Q1)
+//   G2  O1^T += V^T(previous) P1^T     | exponentials 0..7 of S0
+//   G3  S1 = K Q1^T                    | exponentials 8..15 of S0          ; V^T fragments of this subtile
+//   G4  O0^T += V^T P0^T               | exponentials 0..7 of S1           ; K fragments of the next subtile
+//
+// A branch anywhere inside would let the compiler collect the vector work behind the MFMAs, so a hot stage has none:
+// * no rescale: inside hot stages the reference of the exponentials is FROZEN at the value the stages before left
+//   (the first stage, and every stage that needs a mask, run the ordinary online softmax with its running reference).
+//   This is exact unless a later logit exceeds the frozen reference by more than binary32's exponent range; then a
+//   normaliser comes out huge or non-finite, and a workgroup that finds one goes through its keys again with the
+//   ordinary softmax in every stage, before it stores anything.
+// * no "is there a next stage" test: the next stage's loads go through a descriptor of size zero when there is none.
+// * no "is a tile pending" test: entering a hot stage the pending tile is an empty one (logits -inf, probabilities 0).
+// Stages (128 keys: K rows and V^T rows, 64 KB) are filled by LDS-direct loads issued during the first half of the
+// stage before, with the rows' indices fetched two stages ahead; rows are unpadded and piece p of row r sits at
+// position p ^ (r mod 16).  The MFMAs of this file must write ordinary vector registers (their results feed vector
+// arithmetic): the file is compiled with -mllvm -amdgpu-mfma-vgpr-form, without which a kernel that may use the whole
+// register file gets its MFMA results in the accumulation registers and a copy around every use.
+constexpr int AP_THREADS = 256;
+constexpr int AP_BQ = 256;                 // queries per workgroup
+constexpr int AP_TILE = 128 * 256;         // bytes of a K tile (128 keys x 256 B) and of a V^T tile (128 value rows x 128 keys)
+constexpr int AP_STAGE = 2 * AP_TILE;
+constexpr int AP_LDS = 2 * AP_STAGE;
+constexpr int AP_NLD = 8;                  // 16-byte loads per thread, tile and stage
+
+__device__ __forceinline__ void ap_fence() { __builtin_amdgcn_sched_barrier(0); }
+// keeps an addition where it is written: without it the compiler postpones the running sums of the hot stream to the
+// point where they are next read, and parks every exponential in a spare register until then
+__device__ __forceinline__ void ap_pin(float& x) { asm volatile("" : "+v"(x)); }
+// before a barrier that hands a stage over: this wave's LDS-direct loads have landed, its LDS reads have returned
+__device__ __forceinline__ void ap_settle() {
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_waitcnt(LGKMCNT0);
+}
+
+__global__ __launch_bounds__(AP_THREADS, 1) void kept_attention_pipe_kernel(AttnParams p) {
+    using T = bf16_t;
+    constexpr int NCH = 8;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int b = blockIdx.x, x = b % NUM_XCD, w_ = b / NUM_XCD;
+    const int slot = w_ / p.n_qblocks;
+    int qb = w_ - slot * p.n_qblocks;
+    const int h = x * p.heads_per_xcd + slot;
+    if (h >= p.H) return;
+    const bool causal = (p.flags & LEMO_CAUSAL) != 0;
+    if (causal) qb = p.n_qblocks - 1 - qb;
+    const int g = (int)(((long long)h * p.H_kv) / p.H);
+    const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be: what follows from it stays scalar
+    const int M = p.M;
+    const float c2 = p.c2;
+    const int m0 = qb * AP_BQ, mw0 = m0 + wave * 64;
+
+    // resident operand: this wave's 64 queries (rows gathered through idx), as MFMA B fragments
+    u32x4 qf[2][NCH];
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+        const int m = mw0 + qs * 32 + l32;
+        const long long tok = m < M ? (p.idx ? (long long)p.idx[m] : (long long)m) : -1;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            qf[qs][c] = u32x4{0u, 0u, 0u, 0u};
+            if (tok >= 0) qf[qs][c] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.Q + tok * p.q_ts + (long long)h * p.q_hs) + c * 32 + half * 16);
+        }
+    }
+
+    const int k_last = causal ? min(m0 + AP_BQ, M) - 1 : M - 1;          // last key any wave of the workgroup needs
+    const int nstage = k_last / AT_KT + 1;
+    const bool active = mw0 < M;                                         // the wave holds at least one query
+    const int hot_last = causal ? mw0 : M - 1;                           // a stage whose last key is <= this needs no mask for this wave
+
+    // ---- staging: LDS-direct loads, unit u = i*256 + tid -> row i*16 + tid/16, position tid%16, which holds piece (tid%16) ^ (row%16)
+    const int s_row = tid >> 4, s_piece = (tid & 15) ^ (s_row & 15);
+    const int k_row_bytes = (int)p.k_ts * 2;
+    const u32x4 k_rsrc = raw_rsrc(reinterpret_cast<const char*>(p.K + (long long)g * p.k_hs), (long long)p.k_bytes - (long long)g * p.k_hs * 2);
+    const u32x4 v_rsrc = raw_rsrc(reinterpret_cast<const char*>(p.Vt + (long long)g * 128 * p.Mpad), (long long)128 * p.Mpad * 2);
+    int v_voff[AP_NLD];
+#pragma unroll
+    for (int i = 0; i < AP_NLD; ++i) v_voff[i] = (i * 16 + s_row) * p.Mpad * 2 + s_piece * 16;
+    unsigned tok[AP_NLD], tok_next[AP_NLD];  // byte offsets of the K rows of the stage being requested / of the one after it
+    auto fetch_tok = [&](int t, unsigned (&dst)[AP_NLD]) {  // rows past the end repeat the last kept row (masked later)
+        const int n0 = t * AT_KT;
+#pragma unroll
+        for (int i = 0; i < AP_NLD; ++i) {
+            const int n = min(n0 + i * 16 + s_row, M - 1);
+            dst[i] = (unsigned)(p.idx ? p.idx[n] : n) * (unsigned)k_row_bytes + (unsigned)s_piece * 16u;
+        }
+    };
+    const unsigned lds_w = lds_offset_of(smem) + (unsigned)wave * 1024u;
+    // load n (0..15) of the stage that starts at key n0, into stage buffer `buf`: K rows first, then V^T rows
+    auto stage_load_one = [&](int n, int buf, int n0, const u32x4& kd, const u32x4& vd) {
+        const unsigned dst = lds_w + (unsigned)buf * AP_STAGE + (unsigned)(n & 7) * 4096u;
+        if (n < 8) lds_direct_b128(kd, dst, (int)tok[n & 7]);
+        else lds_direct_b128(vd, dst + AP_TILE, v_voff[n & 7], n0 * 2);
+    };
+
+    // ---- fragments
+    const int f_swz = l32 & 15;
+    auto k_frag = [&](const char* sk, int ks, int c) {
+        return *reinterpret_cast<const u32x4*>(sk + (ks * 32 + l32) * 256 + (((2 * c + half) ^ f_swz) << 4));
+    };
+    auto v_frag = [&](const char* sv, int ks, int n) {  // n = dv*2 + c: value rows dv*32.., keys 16c + 8*half .. of the subtile (quad-exchanged order)
+        return *reinterpret_cast<const u32x4*>(sv + ((n >> 1) * 32 + l32) * 256 + (((ks * 4 + 2 * (n & 1) + half) ^ f_swz) << 4));
+    };
+
+    bool frozen = true;  // workgroup-uniform: which pass this is
+    f32x16 o[2][4];      // O^T accumulators: o[qs][dv][r] = element (value row dv*32 + acc_row(r), query column l32 of subtile qs)
+    float ltot[2];
+    for (;;) {
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+        for (int dv = 0; dv < 4; ++dv) o[qs][dv] = f32x16{0};
+    float mrun[2] = {-INFINITY, -INFINITY};  // reference of the exponentials (base-2 units, identical in both half-waves)
+    float la[2] = {0.f, 0.f}, lb[2] = {0.f, 0.f};  // this half-wave's share of the normaliser, in two partial sums
+
+    // the ordinary online softmax of one 32 x 32 tile (first stage, stages that need a mask, the repair pass)
+    auto slow_tile = [&](int qs, int kmin, const u32x4 (&kfr)[NCH], const u32x4 (&vfr)[8]) {
+        const int qmin = mw0 + qs * 32;
+        if (causal && kmin > qmin + 31) return;  // every key lies after every query (wave-uniform)
+        f32x16 acc = {0};
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) mma_chunk<T>(acc, kfr[c], qf[qs][c]);  // acc[key row][query col]
+        const bool all_allowed = (kmin + 31 < M) && (!causal || kmin + 31 <= qmin);
+        if (!all_allowed) {
+            const int lim = causal ? min(qmin + l32, M - 1) : M - 1;  // last key this lane's query may use
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = (kmin + acc_row(r, lane) <= lim) ? acc[r] : -INFINITY;
+        }
+        float t0 = fmaxf(fmaxf(acc[0], acc[1]), acc[2]), t1 = fmaxf(fmaxf(acc[3], acc[4]), acc[5]);
+        float t2 = fmaxf(fmaxf(acc[6], acc[7]), acc[8]), t3 = fmaxf(fmaxf(acc[9], acc[10]), acc[11]);
+        float t4 = fmaxf(fmaxf(acc[12], acc[13]), acc[14]);
+        float tmax = fmaxf(fmaxf(fmaxf(t0, t1), t2), fmaxf(fmaxf(t3, t4), acc[15])) * c2;
+        {  // the other half-wave holds the other 16 keys of the same query: both take the larger maximum
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+            tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        }
+        // lazy reference: it only moves when the tile's maximum exceeds it by more than 2^8
+        const float mn = tmax > mrun[qs] + 8.f ? tmax : mrun[qs];
+        const float ms = mn == -INFINITY ? 0.f : mn;  // nothing allowed so far (padding rows only): keep arguments finite
+        const float corr = __builtin_amdgcn_exp2f(mrun[qs] - ms);
+        float pr[16], s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            pr[r] = __builtin_amdgcn_exp2f(fmaf(acc[r], c2, -ms));
+            if (r & 1) s1 += pr[r]; else s0 += pr[r];
+        }
+        la[qs] = fmaf(la[qs], corr, s0);
+        lb[qs] = fmaf(lb[qs], corr, s1);
+        if (__any(mn > mrun[qs])) {  // the reference moved for some query of the wave: rescale what has been summed
+#pragma unroll
+            for (int dv = 0; dv < 4; ++dv)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[qs][dv][r] *= corr;
+        }
+        mrun[qs] = mn;
+        u32x4 pbs[2];  // P^T as B operand: registers 8c .. 8c+7 are this lane's 8 key slots of chunk c
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+            pbs[c] = u32x4{pack_bf16x2_hw(pr[8 * c + 0], pr[8 * c + 1]), pack_bf16x2_hw(pr[8 * c + 2], pr[8 * c + 3]),
+                           pack_bf16x2_hw(pr[8 * c + 4], pr[8 * c + 5]), pack_bf16x2_hw(pr[8 * c + 6], pr[8 * c + 7])};
+#pragma unroll
+        for (int n = 0; n < 8; ++n) mma_chunk<T>(o[qs][n >> 1], vfr[n], pbs[n & 1]);  // o[value row][query col]
+    };
+
+    // ---- state of the hot stream: the pending tile (previous subtile, Q1) -- its logits, the first half of its
+    // probabilities, and the V^T fragments of its subtile
+    f32x16 S0, S1;
+    u32x4 pb[2][2];
+    u32x4 kf[NCH], vf[8];
+    float nm[2];  // minus the (finite) reference of each query subtile
+
+    fetch_tok(0, tok);
+#pragma unroll
+    for (int n = 0; n < 16; ++n) stage_load_one(n, 0, 0, k_rsrc, v_rsrc);
+    fetch_tok(1, tok);
+    fetch_tok(2, tok_next);
+    ap_settle();
+    // A wave's stages come in three runs: the first stage (ordinary softmax: it sets the reference), then the stages that
+    // need no mask (hot), then the rest (masked, or past the wave's last query).  Each run is a loop of its own, so that
+    // the register allocator sees the hot stream alone.  Every wave passes one barrier per stage, whichever loop it is in.
+    auto stage_head = [&](int t, bool& more, int& k0, int& nbuf, int& n_next, const char*& sk, const char*& sv, u32x4& kd, u32x4& vd) {
+        __syncthreads();  // stage t is complete; every wave is done reading stage t-1
+        more = t + 1 < nstage;
+        k0 = t * AT_KT; nbuf = (t + 1) & 1; n_next = (t + 1) * AT_KT;
+        sk = smem + (t & 1) * AP_STAGE;
+        sv = sk + AP_TILE;
+        // the next stage's loads: through descriptors of size zero when there is no next stage (nothing is read then)
+        kd = k_rsrc; vd = v_rsrc;
+        kd[2] = more ? kd[2] : 0u;
+        vd[2] = more ? vd[2] : 0u;
+    };
+    auto stage_tail = [&](int t, bool more) {
+        ap_settle();
+        if (more) {  // after the wait, so that these index loads have the whole next stage to arrive
+#pragma unroll
+            for (int i = 0; i < AP_NLD; ++i) tok[i] = tok_next[i];
+            fetch_tok(t + 3, tok_next);
+        }
+    };
+    auto slow_stage = [&](int t) {
+        bool more; int k0, nbuf, n_next; const char* sk; const char* sv; u32x4 kd, vd;
+        stage_head(t, more, k0, nbuf, n_next, sk, sv, kd, vd);
+            if (more) {
+#pragma unroll
+                for (int n = 0; n < 16; ++n) stage_load_one(n, nbuf, n_next, k_rsrc, v_rsrc);
+            }
+            if (active && !(causal && k0 > mw0 + 63)) {  // otherwise every key of the stage lies after every query of the wave
+#pragma unroll 1
+                for (int ks = 0; ks < 4; ++ks) {
+                    const int kmin = k0 + ks * 32;
+                    if (kmin >= M || (causal && kmin > mw0 + 63)) break;
+                    u32x4 kfr[NCH], vfr[8];
+#pragma unroll
+                    for (int c = 0; c < NCH; ++c) kfr[c] = k_frag(sk, ks, c);
+#pragma unroll
+                    for (int n = 0; n < 8; ++n) vfr[n] = v_frag(sv, ks, n);
+                    slow_tile(0, kmin, kfr, vfr);
+                    slow_tile(1, kmin, kfr, vfr);
+                }
+            }
+        stage_tail(t, more);
+    };
+    // One stream of exponentials: eight logits of a tile (one chunk of 16 keys) become eight probabilities, added to the
+    // query's running sums (even elements to la, odd ones to lb) and packed in pairs into the B operand pb[qs][hh].
+    // The exponential of an element is issued in one slot and consumed (added, packed) when the next one is issued, so
+    // that no instruction waits on the transcendental unit; the last element is consumed in the first slot of the next
+    // group (`flush`).
+    struct Hold { float prev, even; };
+    Hold hA{0.f, 0.f}, hB{0.f, 0.f}, hC{0.f, 0.f}, hD{0.f, 0.f};  // A: S1 8..15 -> pb[1][1]; B: S0 0..7 -> pb[0][0]; C: S0 8..15 -> pb[0][1]; D: S1 0..7 -> pb[1][0]
+    auto consume = [&](Hold& hd, int j, int qs, int hh) {  // hd.prev is the exponential of element j
+        if (j & 1) {
+            lb[qs] += hd.prev;
+            ap_pin(lb[qs]);
+            pb[qs][hh][j >> 1] = pack_bf16x2_hw(hd.even, hd.prev);
+        } else {
+            la[qs] += hd.prev;
+            ap_pin(la[qs]);
+            hd.even = hd.prev;
+        }
+    };
+    auto feed = [&](Hold& hd, int j, float logit, int qs, int hh) {  // element j of the chunk
+        const float e = __builtin_amdgcn_exp2f(fmaf(logit, c2, nm[qs]));
+        if (j > 0) consume(hd, j - 1, qs, hh);
+        hd.prev = e;
+    };
+    auto hot_stage = [&](int t) {
+        bool more; int k0, nbuf, n_next; const char* sk; const char* sv; u32x4 kd, vd;
+        stage_head(t, more, k0, nbuf, n_next, sk, sv, kd, vd);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) kf[c] = k_frag(sk, 0, c);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            // the next stage's sixteen loads all ride on the first subtile, one every other slot, so that they have three
+            // subtiles' time to land before the stage's closing wait
+            auto ride = [&](int n) { stage_load_one(n, nbuf, n_next, kd, vd); };
+            // G1: S0 = K Q0^T | exponentials 8..15 of the pending tile
+            S0 = f32x16{0};
+            ap_fence();
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                mma_chunk<T>(S0, kf[c], qf[0][c]);
+                if (ks == 0 && (c & 1) == 0) ride(0 + (c >> 1));
+                if (c == 0) consume(hD, 7, 1, 0);  // the pending tile's first chunk is complete
+                feed(hA, c, S1[8 + c], 1, 1);
+                ap_fence();
+            }
+            // G2: O1^T += V^T(pending) P1^T | exponentials 0..7 of S0 (none that needs S0 in the first slot: its last MFMA is still running)
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                mma_chunk<T>(o[1][c >> 1], vf[c], pb[1][c & 1]);
+                if (ks == 0 && (c & 1) == 0) ride(4 + (c >> 1));
+                if (c == 0) consume(hA, 7, 1, 1);  // the pending tile's second chunk is complete (first used by the next MFMA)
+                if (c == 1) feed(hB, 0, S0[0], 0, 0);
+                if (c >= 1) feed(hB, c == 1 ? 1 : c, S0[c == 1 ? 1 : c], 0, 0);
+                ap_fence();
+            }
+            // G3: S1 = K Q1^T | exponentials 8..15 of S0 ; V^T fragments of this subtile (the pending tile's are no longer needed)
+            S1 = f32x16{0};
+            ap_fence();
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                mma_chunk<T>(S1, kf[c], qf[1][c]);
+                if (ks == 0 && (c & 1) == 0) ride(8 + (c >> 1));
+                vf[c] = v_frag(sv, ks, c);
+                if (c == 0) consume(hB, 7, 0, 0);
+                feed(hC, c, S0[8 + c], 0, 1);
+                ap_fence();
+            }
+            // G4: O0^T += V^T P0^T | exponentials 0..7 of S1 ; K fragments of the next subtile
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                mma_chunk<T>(o[0][c >> 1], vf[c], pb[0][c & 1]);
+                if (ks == 0 && (c & 1) == 0) ride(12 + (c >> 1));
+                if (ks < 3) kf[c] = k_frag(sk, ks + 1, c);
+                if (c == 0) consume(hC, 7, 0, 1);
+                if (c == 1) feed(hD, 0, S1[0], 1, 0);
+                if (c >= 1) feed(hD, c == 1 ? 1 : c, S1[c == 1 ? 1 : c], 1, 0);
+                ap_fence();
+            }
+        }
+        stage_tail(t, more);
+    };
+    // hot stages: 1 <= t < t_hot, all keys of the stage at or before the wave's first query (causal) and below M
+    const int t_hot = (frozen && active) ? max(1, min(min((hot_last + 1) / AT_KT, M / AT_KT), nstage)) : 1;
+    if (nstage > 0) slow_stage(0);
+    if (t_hot > 1) {
+        // the hot stream starts with an empty pending tile (logits -inf, probabilities and V^T fragments zero) ...
+#pragma unroll
+        for (int r = 0; r < 16; ++r) S1[r] = -INFINITY;
+        pb[1][0] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int n = 0; n < 8; ++n) vf[n] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int qs = 0; qs < 2; ++qs) nm[qs] = -(mrun[qs] == -INFINITY ? 0.f : mrun[qs]);
+        for (int t = 1; t < t_hot; ++t) hot_stage(t);
+        // ... and ends by finishing the one that is left: its last eight exponentials, then its product
+        consume(hD, 7, 1, 0);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) feed(hA, c, S1[8 + c], 1, 1);
+        consume(hA, 7, 1, 1);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) mma_chunk<T>(o[1][c >> 1], vf[c], pb[1][c & 1]);
+    }
+    for (int t = t_hot; t < nstage; ++t) slow_stage(t);
+
+    // the normaliser of each query; a value that is not finite or has come close to the end of binary32's range means that
+    // a frozen reference was overtaken by too much: then everything is done again with the ordinary softmax throughout
+    bool bad = false;
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+        const float l = la[qs] + lb[qs];
+        ltot[qs] = l + __shfl_xor(l, 32);
+        bad |= !(ltot[qs] < 0x1p100f);
+    }
+    if (!frozen || !__syncthreads_or(bad)) break;
+    frozen = false;
+    }
+
+    // normalise and store: lane (query l32, half) holds value rows 8*(r/4) + 4*half + r%4 of every 32-row tile
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+        const float inv = ltot[qs] > 0.f ? 1.f / ltot[qs] : 0.f;
+        const int m = mw0 + qs * 32 + l32;
+        if (m >= M) continue;
+        uint16_t* orow = p.O + (long long)m * p.o_ts + (long long)h * p.o_hs;
+#pragma unroll
+        for (int dv = 0; dv < 4; ++dv)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int c0 = dv * 32 + gq * 8 + half * 4;
+                uint2 v;
+                v.x = pack_bf16x2_hw(o[qs][dv][gq * 4 + 0] * inv, o[qs][dv][gq * 4 + 1] * inv);
+                v.y = pack_bf16x2_hw(o[qs][dv][gq * 4 + 2] * inv, o[qs][dv][gq * 4 + 3] * inv);
+                *reinterpret_cast<uint2*>(orow + c0) = v;  // host guarantees 8-byte alignment of every output row
+            }
+    }
+}
+
 template <int D>
 static int launch_attn_t(AttnParams p, hipStream_t st) {
     using G = AGeo<D>;
@@ -306,8 +679,21 @@ static int launch_attn_t(AttnParams p, hipStream_t st) {
         attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&kept_attention_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS);
     });
     if (attr_err != hipSuccess) return (int)attr_err;
-    p.n_qblocks = (p.M + AT_BQ - 1) / AT_BQ;
     p.heads_per_xcd = (p.H + NUM_XCD - 1) / NUM_XCD;
+#if LEMO_AT_PIPE
+    if (D == 128) {
+        static std::once_flag once2;
+        static hipError_t attr_err2 = hipSuccess;
+        std::call_once(once2, [] {
+            attr_err2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&kept_attention_pipe_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, AP_LDS);
+        });
+        if (attr_err2 != hipSuccess) return (int)attr_err2;
+        p.n_qblocks = (p.M + AP_BQ - 1) / AP_BQ;
+        hipLaunchKernelGGL(kept_attention_pipe_kernel, dim3((unsigned)(NUM_XCD * p.heads_per_xcd * p.n_qblocks)), dim3(AP_THREADS), AP_LDS, st, p);
+        return (int)hipGetLastError();
+    }
+#endif
+    p.n_qblocks = (p.M + AT_BQ - 1) / AT_BQ;
     hipLaunchKernelGGL((kept_attention_kernel<D>), dim3((unsigned)(NUM_XCD * p.heads_per_xcd * p.n_qblocks)), dim3(AT_THREADS), G::LDS, st, p);
     return (int)hipGetLastError();
 }

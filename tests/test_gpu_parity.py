@@ -876,6 +876,35 @@ def test_kept_attention_small_shapes(lemo, S, H, Hkv, d, M, causal):
     assert_attention_close(wl.to_bf16_bits(O), want, wl.as_numpy(V)[idx])
 
 
+@pytest.mark.parametrize("dominant", [500, 840, 30])
+def test_kept_attention_reference_overflow_is_repaired(lemo, dominant):
+    """With 128-wide heads the attention kernel freezes the reference of its exponentials in the stages of keys that need
+    no mask; a key far later whose logit exceeds that reference by more than the binary32 exponent range overflows the
+    normaliser, and the workgroup must then go through its keys again with the ordinary running reference.  A logit of
+    ~360 nats against a first-stage maximum near 0 forces that path.  dominant = 500: met in unmasked stages by the later
+    query blocks (by every block without the mask), next to rows that never overflow; 840: under the causal mask only
+    ever met in masked stages, which keep a running reference; 30: inside the first stage, whose maximum is tracked."""
+    say(f"[attention] frozen-reference overflow -> second pass, dominant key {dominant}")
+    S, H, d = 900, 2, 128
+    rng = np.random.default_rng(321)
+    q = np.full((S, H, d), 4.0, dtype=np.float32)
+    q[:300] = rng.standard_normal((300, H, d)).astype(np.float32)      # ordinary rows as well
+    k = (rng.standard_normal((S, H, d)) * 0.05).astype(np.float32)
+    k[dominant] = 8.0                                                  # scale * <q, k> = 128*32/sqrt(128) = 362
+    k[777] = -8.0
+    Q = torch.from_numpy(q).to(torch.bfloat16)
+    K = torch.from_numpy(k).to(torch.bfloat16)
+    V = torch.from_numpy(rng.standard_normal((S, H, d)).astype(np.float32)).to(torch.bfloat16)
+    for flags in (lemo.CAUSAL, 0):
+        O = lemo.lemo_kept_attention(Q.cuda(), K.cuda(), V.cuda(), None, flags=flags)
+        torch.cuda.synchronize()
+        want = oracle.kept_attention(wl.as_numpy(Q), wl.as_numpy(K), wl.as_numpy(V), np.arange(S, dtype=np.int32), flags=flags)
+        assert_attention_close(wl.to_bf16_bits(O), want, wl.as_numpy(V))
+        # a row that sees the dominant key is that key's value row
+        if flags == 0 or dominant < S - 1:
+            np.testing.assert_array_equal(wl.to_bf16_bits(O)[S - 1], np.broadcast_to(wl.as_numpy(V)[dominant], (H, d)))
+
+
 def test_kept_attention_options(lemo):
     say("[attention] options")
     S, H, Hkv, d, M = 600, 4, 2, 128, 333
