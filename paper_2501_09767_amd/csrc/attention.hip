@@ -322,9 +322,14 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
 //   normaliser comes out huge or non-finite, and a workgroup that finds one goes through its keys again with the
 //   ordinary softmax in every stage, before it stores anything.
 // * no "is there a next stage" test: the next stage's loads go through a descriptor of size zero when there is none.
-// * no "is a tile pending" test: entering a hot stage the pending tile is an empty one (logits -inf, probabilities 0).
-// Stages (128 keys: K rows and V^T rows, 64 KB) are filled by LDS-direct loads issued during the first half of the
-// stage before, with the rows' indices fetched two stages ahead; rows are unpadded and piece p of row r sits at
+// * no "is a tile pending" test: the run of hot stages starts with an empty pending tile (logits -inf, probabilities
+//   0), carries the pending tile from stage to stage in registers, and finishes the last one after the run.
+// The exponential of an element is issued in one slot and added and packed in the next, so that nothing waits on the
+// transcendental unit, and every running sum is pinned where it is written (the compiler would otherwise postpone the
+// additions and park each exponential in a spare register).  A wave's stages come in three runs -- the first stage,
+// the hot stages, the rest -- each a loop of its own, which keeps the register allocator's view of the hot stream clean.
+// Stages (128 keys: K rows and V^T rows, 64 KB) are filled by LDS-direct loads that ride on the first key subtile of
+// the stage before, with the rows' indices fetched two stages ahead; rows are unpadded and piece p of row r sits at
 // position p ^ (r mod 16).  The MFMAs of this file must write ordinary vector registers (their results feed vector
 // arithmetic): the file is compiled with -mllvm -amdgpu-mfma-vgpr-form, without which a kernel that may use the whole
 // register file gets its MFMA results in the accumulation registers and a copy around every use.
@@ -581,7 +586,7 @@ __global__ __launch_bounds__(AP_THREADS, 1) void kept_attention_pipe_kernel(Attn
             // G2: O1^T += V^T(pending) P1^T | exponentials 0..7 of S0 (none that needs S0 in the first slot: its last MFMA is still running)
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
-                mma_chunk<T>(o[1][c >> 1], vf[c], pb[1][c & 1]);
+                mma_chunk<T>(o[1][c & 3], vf[(c & 3) * 2 + (c >> 2)], pb[1][c >> 2]);  // chunk-major: consecutive MFMAs, different accumulators
                 if (ks == 0 && (c & 1) == 0) ride(4 + (c >> 1));
                 if (c == 0) consume(hA, 7, 1, 1);  // the pending tile's second chunk is complete (first used by the next MFMA)
                 if (c == 1) feed(hB, 0, S0[0], 0, 0);
@@ -603,7 +608,7 @@ __global__ __launch_bounds__(AP_THREADS, 1) void kept_attention_pipe_kernel(Attn
             // G4: O0^T += V^T P0^T | exponentials 0..7 of S1 ; K fragments of the next subtile
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
-                mma_chunk<T>(o[0][c >> 1], vf[c], pb[0][c & 1]);
+                mma_chunk<T>(o[0][c & 3], vf[(c & 3) * 2 + (c >> 2)], pb[0][c >> 2]);
                 if (ks == 0 && (c & 1) == 0) ride(12 + (c >> 1));
                 if (ks < 3) kf[c] = k_frag(sk, ks + 1, c);
                 if (c == 0) consume(hC, 7, 0, 1);
@@ -633,7 +638,7 @@ __global__ __launch_bounds__(AP_THREADS, 1) void kept_attention_pipe_kernel(Attn
         for (int c = 0; c < NCH; ++c) feed(hA, c, S1[8 + c], 1, 1);
         consume(hA, 7, 1, 1);
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) mma_chunk<T>(o[1][c >> 1], vf[c], pb[1][c & 1]);
+        for (int c = 0; c < NCH; ++c) mma_chunk<T>(o[1][c & 3], vf[(c & 3) * 2 + (c >> 2)], pb[1][c >> 2]);  // chunk-major: consecutive MFMAs, different accumulators
     }
     for (int t = t_hot; t < nstage; ++t) slow_stage(t);
 
