@@ -876,6 +876,24 @@ def test_kept_attention_small_shapes(lemo, S, H, Hkv, d, M, causal):
     assert_attention_close(wl.to_bf16_bits(O), want, wl.as_numpy(V)[idx])
 
 
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("M", [127, 128, 129, 255, 256, 257, 320, 384, 385, 511, 512, 513, 640, 769, 1024])
+def test_kept_attention_stage_and_block_edges(lemo, M, causal):
+    """128-wide heads, kept counts around the kernel's granularities (32-key subtiles, 64-query waves, 128-key stages,
+    256-query workgroups): the last stage is ragged or exactly full, waves of the last workgroup hold no query at all, the
+    run of stages that need no mask is empty, one stage long, or ends exactly at a workgroup's first query."""
+    say(f"[attention] edges M={M} causal={causal}")
+    S, H, Hkv, d = M + 37, 4, 2, 128
+    Q, K = wl.tiny_qk(S, H, Hkv, d, "bf16", seed=1000 + M, heavy=3)
+    V = torch.from_numpy(np.random.default_rng(M).standard_normal((S, Hkv, d)).astype(np.float32)).to(torch.bfloat16)
+    idx = np.sort(np.random.default_rng(M + 1).permutation(S)[:M]).astype(np.int32)
+    flags = lemo.CAUSAL if causal else 0
+    O = lemo.lemo_kept_attention(Q.cuda(), K.cuda(), V.cuda(), torch.from_numpy(idx).cuda(), flags=flags)
+    torch.cuda.synchronize()
+    want = oracle.kept_attention(wl.as_numpy(Q), wl.as_numpy(K), wl.as_numpy(V), idx, flags=flags)
+    assert_attention_close(wl.to_bf16_bits(O), want, wl.as_numpy(V)[idx])
+
+
 @pytest.mark.parametrize("dominant", [500, 840, 30])
 def test_kept_attention_reference_overflow_is_repaired(lemo, dominant):
     """With 128-wide heads the attention kernel freezes the reference of its exponentials in the stages of keys that need
