@@ -18,6 +18,7 @@
 // P is rounded to bf16 for the second product (as in every flash-attention kernel); the normaliser is summed from the
 // unrounded values.
 #include <mutex>
+#include <type_traits>
 
 #include "lemo_common.hpp"
 
@@ -307,13 +308,12 @@ __global__ __launch_bounds__(AT_THREADS, 1) void kept_attention_kernel(AttnParam
 // With 32 queries per wave every K and V^T fragment read (16 x 16 bytes per lane and 32-key subtile) feeds one pair of
 // MFMA chains, and at full matrix-core rate that alone is the CU's whole LDS bandwidth.  Two query subtiles per wave
 // halve it, but their 128 accumulator registers leave room for one wave per SIMD only, so matrix and vector work are
-// interleaved by hand.  Stages of keys that need no mask ("hot" stages) run as one branch-free stream: per key subtile
-// four groups of 8 MFMAs, each carrying a share of another tile's exponentials (Q0, Q1: the wave's two query subtiles):
-//
-//   G1  S0 = K Q0^T                    | exponentials 8..15 of the pending tile (previous subtile, Q1)
-//   G2  O1^T += V^T(previous) P1^T     | exponentials 0..7 of S0
-//   G3  S1 = K Q1^T                    | exponentials 8..15 of S0          ; V^T fragments of this subtile
-//   G4  O0^T += V^T P0^T               | exponentials 0..7 of S1           ; K fragments of the next subtile
+// interleaved by hand.  Stages of keys that need no mask ("hot" stages) run as one branch-free stream of groups of 16
+// MFMAs.  With the tiles in the order a(n) = (key subtile n, query subtile 0), b(n) = (n, 1), a(n+1), ..., group k
+//   * accumulates the logits of tile k+1          (a chain of 8 MFMAs, in the even slots),
+//   * multiplies the probabilities of tile k-1 into its O^T accumulators (8 MFMAs, in the odd slots),
+//   * turns the logits of tile k into probabilities (vector work: one element per slot),
+// so nothing inside a group waits for anything else inside it, and no two dependent MFMAs stand next to each other.
 //
 // A branch anywhere inside would let the compiler collect the vector work behind the MFMAs, so a hot stage has none:
 // * no rescale: inside hot stages the reference of the exponentials is FROZEN at the value the stages before left
@@ -539,83 +539,79 @@ __global__ __launch_bounds__(AP_THREADS, 1) void kept_attention_pipe_kernel(Attn
             }
         stage_tail(t, more);
     };
-    // One stream of exponentials: eight logits of a tile (one chunk of 16 keys) become eight probabilities, added to the
-    // query's running sums (even elements to la, odd ones to lb) and packed in pairs into the B operand pb[qs][hh].
-    // The exponential of an element is issued in one slot and consumed (added, packed) when the next one is issued, so
-    // that no instruction waits on the transcendental unit; the last element is consumed in the first slot of the next
-    // group (`flush`).
+    // The stream of exponentials of one tile: its sixteen logits become sixteen probabilities, added to the query's
+    // running sums (even elements to la, odd ones to lb) and packed in pairs into the B operand pb[qs] (two chunks of
+    // 16 keys).  The exponential of an element is issued in one slot and consumed (added, packed) when the next one is
+    // issued, so that no instruction waits on the transcendental unit; the last element is consumed in the first slot of
+    // the next group.
     struct Hold { float prev, even; };
-    Hold hA{0.f, 0.f}, hB{0.f, 0.f}, hC{0.f, 0.f}, hD{0.f, 0.f};  // A: S1 8..15 -> pb[1][1]; B: S0 0..7 -> pb[0][0]; C: S0 8..15 -> pb[0][1]; D: S1 0..7 -> pb[1][0]
-    auto consume = [&](Hold& hd, int j, int qs, int hh) {  // hd.prev is the exponential of element j
+    Hold h0{0.f, 0.f}, h1{0.f, 0.f};  // of the Q0 tiles, of the Q1 tiles
+    auto consume = [&](Hold& hd, int j, int qs) {  // hd.prev is the exponential of element j (0..15)
         if (j & 1) {
             lb[qs] += hd.prev;
             ap_pin(lb[qs]);
-            pb[qs][hh][j >> 1] = pack_bf16x2_hw(hd.even, hd.prev);
+            pb[qs][j >> 3][(j & 7) >> 1] = pack_bf16x2_hw(hd.even, hd.prev);
         } else {
             la[qs] += hd.prev;
             ap_pin(la[qs]);
             hd.even = hd.prev;
         }
     };
-    auto feed = [&](Hold& hd, int j, float logit, int qs, int hh) {  // element j of the chunk
+    auto feed = [&](Hold& hd, int j, float logit, int qs) {  // element j of the tile
         const float e = __builtin_amdgcn_exp2f(fmaf(logit, c2, nm[qs]));
-        if (j > 0) consume(hd, j - 1, qs, hh);
+        if (j > 0) consume(hd, j - 1, qs);
         hd.prev = e;
     };
+    // One group of 16 slots.  Tiles in the order a(n) = (subtile n, Q0), b(n) = (subtile n, Q1), a(n+1), ...; group k
+    // accumulates the logits of tile k+1 (a chain of 8 MFMAs, even slots), multiplies the probabilities of tile k-1 into
+    // its O^T accumulators (8 MFMAs, odd slots, chunk-major so that neighbours differ in accumulator) and turns the logits
+    // of tile k into probabilities (one element per slot).  Nothing inside a group depends on anything else inside it.
+    //   EVEN(n): logits of b(n) (K fragments of subtile n, each refilled with subtile n+1's right after its use),
+    //            product of b(n-1) (V^T fragments of subtile n-1, each refilled with subtile n's right after its use),
+    //            exponentials of a(n)
+    //   ODD(n):  logits of a(n+1), product of a(n), exponentials of b(n)
+    auto group = [&](auto odd_tag, const char* sk, const char* sv, int ks, bool refill_k, auto&& ride) {
+        constexpr bool ODD = decltype(odd_tag)::value;
+        constexpr int QL = ODD ? 0 : 1;   // query subtile whose logits are accumulated
+        constexpr int QP = ODD ? 0 : 1;   // ... whose product is taken: ODD a(n) -> Q0; EVEN b(n-1) -> Q1
+        constexpr int QE = ODD ? 1 : 0;   // ... whose exponentials are formed
+        f32x16& SL = ODD ? S0 : S1;
+        f32x16& SE = ODD ? S1 : S0;
+        Hold& hd = ODD ? h1 : h0;
+        Hold& hp = ODD ? h0 : h1;         // of the tile whose product is taken: its last exponential is still to be consumed
+        SL = f32x16{0};
+        ap_fence();
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            mma_chunk<T>(SL, kf[c], qf[QL][c]);
+            if (!ODD && refill_k) kf[c] = k_frag(sk, ks + 1, c);
+            ride(2 * c);
+            if (c == 0) consume(hp, 15, QP);  // completes pb[QP][1], which the group's fifth product MFMA is the first to read
+            feed(hd, 2 * c, SE[2 * c], QE);
+            ap_fence();
+            mma_chunk<T>(o[QP][c & 3], vf[(c & 3) * 2 + (c >> 2)], pb[QP][c >> 2]);
+            if (!ODD) vf[(c & 3) * 2 + (c >> 2)] = v_frag(sv, ks, (c & 3) * 2 + (c >> 2));
+            ride(2 * c + 1);
+            feed(hd, 2 * c + 1, SE[2 * c + 1], QE);
+            ap_fence();
+        }
+    };
+    using EvenT = std::integral_constant<bool, false>;
+    using OddT = std::integral_constant<bool, true>;
     auto hot_stage = [&](int t) {
         bool more; int k0, nbuf, n_next; const char* sk; const char* sv; u32x4 kd, vd;
         stage_head(t, more, k0, nbuf, n_next, sk, sv, kd, vd);
 #pragma unroll
         for (int c = 0; c < NCH; ++c) kf[c] = k_frag(sk, 0, c);
+        // the next stage's sixteen loads ride on the stage's first group, one per slot, so that they have the other seven
+        // groups' time to land before the stage's closing wait
+        auto ride = [&](int n) { stage_load_one(n, nbuf, n_next, kd, vd); };
+        auto no_ride = [&](int) {};
+        group(OddT{}, sk, sv, 0, false, ride);      // ODD(4t - 1): logits of a(4t), product of a(4t-1), exponentials of b(4t-1)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            // the next stage's sixteen loads all ride on the first subtile, one every other slot, so that they have three
-            // subtiles' time to land before the stage's closing wait
-            auto ride = [&](int n) { stage_load_one(n, nbuf, n_next, kd, vd); };
-            // G1: S0 = K Q0^T | exponentials 8..15 of the pending tile
-            S0 = f32x16{0};
-            ap_fence();
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                mma_chunk<T>(S0, kf[c], qf[0][c]);
-                if (ks == 0 && (c & 1) == 0) ride(0 + (c >> 1));
-                if (c == 0) consume(hD, 7, 1, 0);  // the pending tile's first chunk is complete
-                feed(hA, c, S1[8 + c], 1, 1);
-                ap_fence();
-            }
-            // G2: O1^T += V^T(pending) P1^T | exponentials 0..7 of S0 (none that needs S0 in the first slot: its last MFMA is still running)
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                mma_chunk<T>(o[1][c & 3], vf[(c & 3) * 2 + (c >> 2)], pb[1][c >> 2]);  // chunk-major: consecutive MFMAs, different accumulators
-                if (ks == 0 && (c & 1) == 0) ride(4 + (c >> 1));
-                if (c == 0) consume(hA, 7, 1, 1);  // the pending tile's second chunk is complete (first used by the next MFMA)
-                if (c == 1) feed(hB, 0, S0[0], 0, 0);
-                if (c >= 1) feed(hB, c == 1 ? 1 : c, S0[c == 1 ? 1 : c], 0, 0);
-                ap_fence();
-            }
-            // G3: S1 = K Q1^T | exponentials 8..15 of S0 ; V^T fragments of this subtile (the pending tile's are no longer needed)
-            S1 = f32x16{0};
-            ap_fence();
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                mma_chunk<T>(S1, kf[c], qf[1][c]);
-                if (ks == 0 && (c & 1) == 0) ride(8 + (c >> 1));
-                vf[c] = v_frag(sv, ks, c);
-                if (c == 0) consume(hB, 7, 0, 0);
-                feed(hC, c, S0[8 + c], 0, 1);
-                ap_fence();
-            }
-            // G4: O0^T += V^T P0^T | exponentials 0..7 of S1 ; K fragments of the next subtile
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                mma_chunk<T>(o[0][c & 3], vf[(c & 3) * 2 + (c >> 2)], pb[0][c >> 2]);
-                if (ks == 0 && (c & 1) == 0) ride(12 + (c >> 1));
-                if (ks < 3) kf[c] = k_frag(sk, ks + 1, c);
-                if (c == 0) consume(hC, 7, 0, 1);
-                if (c == 1) feed(hD, 0, S1[0], 1, 0);
-                if (c >= 1) feed(hD, c == 1 ? 1 : c, S1[c == 1 ? 1 : c], 1, 0);
-                ap_fence();
-            }
+            group(EvenT{}, sk, sv, ks, ks < 3, no_ride);
+            if (ks < 3) group(OddT{}, sk, sv, ks, false, no_ride);
         }
         stage_tail(t, more);
     };
@@ -623,22 +619,24 @@ __global__ __launch_bounds__(AP_THREADS, 1) void kept_attention_pipe_kernel(Attn
     const int t_hot = (frozen && active) ? max(1, min(min((hot_last + 1) / AT_KT, M / AT_KT), nstage)) : 1;
     if (nstage > 0) slow_stage(0);
     if (t_hot > 1) {
-        // the hot stream starts with an empty pending tile (logits -inf, probabilities and V^T fragments zero) ...
+        // the hot stream starts with empty tiles in flight (logits -inf, probabilities and V^T fragments zero) ...
 #pragma unroll
         for (int r = 0; r < 16; ++r) S1[r] = -INFINITY;
-        pb[1][0] = u32x4{0u, 0u, 0u, 0u};
+        pb[0][0] = pb[0][1] = pb[1][0] = pb[1][1] = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int n = 0; n < 8; ++n) vf[n] = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int qs = 0; qs < 2; ++qs) nm[qs] = -(mrun[qs] == -INFINITY ? 0.f : mrun[qs]);
         for (int t = 1; t < t_hot; ++t) hot_stage(t);
-        // ... and ends by finishing the one that is left: its last eight exponentials, then its product
-        consume(hD, 7, 1, 0);
+        // ... and ends by finishing the two that are left: a(last) has its probabilities, b(last) its logits
+        consume(h0, 15, 0);
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) feed(hA, c, S1[8 + c], 1, 1);
-        consume(hA, 7, 1, 1);
+        for (int i = 0; i < 8; ++i) mma_chunk<T>(o[0][i & 3], vf[(i & 3) * 2 + (i >> 2)], pb[0][i >> 2]);
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) mma_chunk<T>(o[1][c & 3], vf[(c & 3) * 2 + (c >> 2)], pb[1][c >> 2]);  // chunk-major: consecutive MFMAs, different accumulators
+        for (int j = 0; j < 16; ++j) feed(h1, j, S1[j], 1);
+        consume(h1, 15, 1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mma_chunk<T>(o[1][i & 3], vf[(i & 3) * 2 + (i >> 2)], pb[1][i >> 2]);
     }
     for (int t = t_hot; t < nstage; ++t) slow_stage(t);
 
