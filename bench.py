@@ -34,9 +34,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 # The figures belong to the kernel sources they were measured on: "sources" is sources_digest() at that time, and the
 # bench reports traffic as null when the sources have changed since.
 MEASURED_TRAFFIC_BYTES = {
-    "sources": "49280715e7660c3a",
-    "C5:rowstats": 2062767028, "C5:colsum": 2108309222, "C5:head_mean_select": 8641978,
-    "C5:gather_gemm": 1687060360, "C5:scatter": 242876208,
+    "sources": "c7e7cdca3b2de7e5",
+    "C5:rowstats": 2084561862, "C5:colsum": 2093587592, "C5:head_mean_select": 8641864,
+    "C5:gather_gemm": 1687025269, "C5:scatter": 242876820,
 }
 
 
@@ -409,15 +409,21 @@ def measure_ceilings(cfg, ev, stream, X, W, kept, lemo):
     def mix():
         waves[0] = lemo.lemo_probe_sweep_issue_mix(tiles, sink)
 
+    def mix_random():
+        waves[0] = lemo.lemo_probe_sweep_issue_mix(tiles, sink, operand_seed=20250109)
+
     t_mix = timed_calls(ev, stream, mix, 3)
     mix_tflops = 8 * 32768.0 * tiles * waves[0] / t_mix * 1e-9
+    t_mixr = timed_calls(ev, stream, mix_random, 3)
+    mixr_tflops = 8 * 32768.0 * tiles * waves[0] / t_mixr * 1e-9
     return {"what": "same machine, same run: torch.matmul (library GEMM) on a compact copy of the consumer GEMM's operands; "
                     "1 GiB device copy (read + write counted); one empty kernel launch, back to back on the stream; "
                     "sweep_issue_mix = the sweeps' minimal instruction mix per 32x32 logit tile (8 dependent MFMAs + 16 x (fma, exp2, add), "
-                    "two waves per SIMD) from registers only, quoted as the MFMA flops of the tiles",
+                    "two waves per SIMD) from registers only, quoted as the MFMA flops of the tiles, once with the same operand fragments for every MFMA "
+                    "and once with pseudo-random operands that change from MFMA to MFMA (what the clock is when the matrix cores' inputs switch)",
             "library_gemm_ms": round(t_mm, 5), "library_gemm_tflops": round(2.0 * cfg.M * cfg.C * cfg.N / t_mm * 1e-9, 2),
             "device_copy_gbs": round(2.0 * (1 << 30) / t_cp * 1e-6, 1), "empty_launch_us": round(t_empty * 1e3, 3),
-            "sweep_issue_mix_tflops": round(mix_tflops, 1)}
+            "sweep_issue_mix_tflops": round(mix_tflops, 1), "sweep_issue_mix_random_operands_tflops": round(mixr_tflops, 1)}
 
 
 def measure_constant_operands(cfg, lemo, ev, stream, run):
@@ -570,6 +576,7 @@ def main():
         for name in ("rowstats", "colsum"):
             if "tflops" in report.get(name, {}):
                 report[name]["frac_sweep_issue_mix"] = round(report[name]["tflops"] / ceil["sweep_issue_mix_tflops"], 4)
+                report[name]["frac_sweep_issue_mix_random_operands"] = round(report[name]["tflops"] / ceil["sweep_issue_mix_random_operands_tflops"], 4)
         if "scatter" in report:
             report["scatter"]["frac_device_copy"] = round(report["scatter"]["gbs"] / ceil["device_copy_gbs"], 4)
         out["constant_operands"] = measure_constant_operands(cfg, lemo, ev, stream, run)

@@ -193,9 +193,12 @@ int lemo_launch_floor(void* stream);
  * fma, one exp2 and one add in binary32; this enqueues a register-only kernel that issues exactly that, two wavefronts
  * per SIMD on every compute unit, `tiles_per_wave` tiles each (even, at most 2^24).  Timed by the caller, it gives the
  * rate at which the matrix cores and the vector ALU together get through this mix on the machine at hand:
- * 8 * 32768 flops * tiles_per_wave * *waves / seconds.  `sink`: one float of device memory (not written in practice);
- * `waves` (host, out): wavefronts launched. */
-int lemo_probe_sweep_issue_mix(int32_t tiles_per_wave, float* sink, int32_t* waves /* host, out */, void* stream);
+ * 8 * 32768 flops * tiles_per_wave * *waves / seconds.  `operand_seed` 0: the same small-integer operand fragments for
+ * every MFMA (next to nothing switches at the matrix cores' inputs: the rate at the chip's highest clock); non-zero:
+ * pseudo-random unit-scale operands drawn from the seed that change from MFMA to MFMA, as a sweep's data does (the rate
+ * at the clock the chip's power management grants on such data).  `sink`: one float of device memory (not written in
+ * practice); `waves` (host, out): wavefronts launched. */
+int lemo_probe_sweep_issue_mix(int32_t tiles_per_wave, uint32_t operand_seed, float* sink, int32_t* waves /* host, out */, void* stream);
 
 /*
  * Block-wise informativeness (Sec. 4.2 "Block-wise Elimination", Eq. 2, and the token-block scores of

@@ -232,11 +232,11 @@ int lemo_head_mean_select_topk(const float* colsum_per_head, const float* diag_p
 
 int lemo_launch_floor(void* stream) { return hip_rc(launch_empty(static_cast<hipStream_t>(stream))); }
 
-int lemo_probe_sweep_issue_mix(int32_t tiles_per_wave, float* sink, int32_t* waves, void* stream) {
+int lemo_probe_sweep_issue_mix(int32_t tiles_per_wave, uint32_t operand_seed, float* sink, int32_t* waves, void* stream) {
     if (!sink || !waves) return LEMO_ERR_NULL;
     if (tiles_per_wave <= 0 || tiles_per_wave > (1 << 24) || (tiles_per_wave & 1)) return LEMO_ERR_SHAPE;
     int w = 0;
-    const int rc = launch_issue_mix(tiles_per_wave, sink, &w, static_cast<hipStream_t>(stream));
+    const int rc = launch_issue_mix(tiles_per_wave, operand_seed, sink, &w, static_cast<hipStream_t>(stream));
     if (rc != 0) return LEMO_ERR_HIP;
     *waves = w;
     return LEMO_OK;

@@ -132,7 +132,7 @@ int launch_select(const float* scores, int S, int L, int k, int* kept, hipStream
 int launch_head_mean_select(const float* colsum, const float* diag, int S, int H, int exclude_self, int L, int k, float* scores, int* kept,
                             hipStream_t st);
 int launch_empty(hipStream_t st);
-int launch_issue_mix(int tiles, float* sink, int* waves_out, hipStream_t st);
+int launch_issue_mix(int tiles, unsigned operand_seed, float* sink, int* waves_out, hipStream_t st);
 int launch_block_mean(const float* token_blocks, int nb, float* out, hipStream_t st);
 int launch_select_threshold(const float* token_blocks, int S, int b, float t_host, const float* t_dev, int* kept, int* kept_count,
                             hipStream_t st);

@@ -82,7 +82,7 @@ def _load() -> ctypes.CDLL:
     lib.lemo_launch_floor.restype = ctypes.c_int
     lib.lemo_launch_floor.argtypes = [vp]
     lib.lemo_probe_sweep_issue_mix.restype = ctypes.c_int
-    lib.lemo_probe_sweep_issue_mix.argtypes = [i32, vp, ctypes.POINTER(i32), vp]
+    lib.lemo_probe_sweep_issue_mix.argtypes = [i32, u32, vp, ctypes.POINTER(i32), vp]
     lib.lemo_gather_gemm_dx.restype = ctypes.c_int
     lib.lemo_gather_gemm_dx.argtypes = [vp, i64, i64, vp, i64, vp, i64, i64, vp, i32, i32, ctypes.c_int, vp]
     lib.lemo_select_topk.restype = ctypes.c_int
@@ -363,13 +363,14 @@ def lemo_launch_floor() -> None:
     _check(_lib.lemo_launch_floor(_stream()), "lemo_launch_floor")
 
 
-def lemo_probe_sweep_issue_mix(tiles_per_wave: int, sink: torch.Tensor) -> int:
-    """Enqueue the register-only instruction mix of the scoring sweeps (measurement aid) -> wavefronts launched."""
+def lemo_probe_sweep_issue_mix(tiles_per_wave: int, sink: torch.Tensor, operand_seed: int = 0) -> int:
+    """Enqueue the register-only instruction mix of the scoring sweeps (measurement aid) -> wavefronts launched.
+    operand_seed 0: constant operands; non-zero: pseudo-random operands that change from MFMA to MFMA."""
     _dev(sink)
     if sink.dtype != torch.float32 or sink.numel() < 1:
         raise ValueError("sink must hold one float32")
     waves = ctypes.c_int32(0)
-    _check(_lib.lemo_probe_sweep_issue_mix(int(tiles_per_wave), _ptr(sink), ctypes.byref(waves), _stream()), "lemo_probe_sweep_issue_mix")
+    _check(_lib.lemo_probe_sweep_issue_mix(int(tiles_per_wave), int(operand_seed) & 0xffffffff, _ptr(sink), ctypes.byref(waves), _stream()), "lemo_probe_sweep_issue_mix")
     return int(waves.value)
 
 
